@@ -1,0 +1,145 @@
+/*
+ * pmpd.h -- C ABI of the MI355X (gfx950) library for the decode-phase linear layers of
+ * Progressive Mixed-Precision Decoding (PMPD).
+ *
+ * The paper (Section 4.2, Algorithm 1 deployment stage) decodes token i with the model
+ * variant m_p whose weight precision p is chosen per step by a precision-switching
+ * scheduler; all variants are read from ONE nested weight store so that switching costs
+ * no extra memory (Section 2.1; Section 5 "PMPD Implementation Details").  At batch 1 the
+ * linear layers are memory-bound matrix-vector products (Section 1; Section 5.2 "GPU
+ * Evaluation"), so a b-bit step should move only b bits per weight.
+ *
+ * This library implements that path for b in {4,3,2}:
+ *     q_b = q4 >> (4-b)                       nested code (top b bits of the 4-bit code)
+ *     W_b = a_g + s_g * 2^(4-b) * (q_b + 0.5) group g = 128 consecutive input features
+ *     y   = W_b x                             fp16 x, fp32 accumulation, fp32 y
+ * The weights are stored once as 4 bit-planes (plane 0 = most significant bit); a b-bit
+ * pass reads planes 0..b-1 and the (scale, min) words only.
+ *
+ * Conventions
+ *   - Every function returns an int32 status: PMPD_OK or a negative PMPD_E* code;
+ *     pmpd_last_error() gives a thread-local message for the last failure.
+ *   - "host" / "device" on a pointer says where the memory lives.  The library never
+ *     allocates, frees or keeps device memory: every device buffer is the caller's and
+ *     must outlive the calls that use it.  Objects returned by *_create are host objects
+ *     owned by the library until *_destroy.
+ *   - Device work is enqueued on the caller's HIP stream (passed as void*, NULL = the
+ *     default stream) and is asynchronous; there is no hidden synchronisation.
+ *   - Arguments are validated on the host before anything is launched, so every error
+ *     path can be exercised without a GPU.  There is no CPU fallback: a call that needs
+ *     the GPU fails with PMPD_EHIP when none is usable.
+ *
+ * Storage format ("tile-plane"), shared by pack, unpack and the kernels:
+ *   rows padded to a multiple of 64; row r -> tile T = r/64, lane l = r%64;
+ *   feature i -> group g = i/128, word d = (i%128)/32, u = i%32 = 2*p + half,
+ *   p = 4*m + 2*v + h (m 0..3, v 0..1, h 0..1); G = in_features/128.
+ *   plane k: uint32 words, weight (r,i) is bit (16*half + 8*v + 4*h + 3 - k + m) mod 32
+ *            of word ((T*G + g)*64 + l)*4 + d        -> plane_bytes = padded_rows*in/8
+ *   scale_min: uint32 word (T*G + g)*64 + l = fp16 scale (low half) | fp16 min (high half)
+ *   A wave of 64 lanes reads one contiguous 1 KiB chunk per (tile, group, plane).
+ */
+#ifndef PMPD_H_
+#define PMPD_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PMPD_OK 0
+#define PMPD_EINVAL (-1)  /* null pointer, bad shape, bit-width outside {2,3,4}, bad count */
+#define PMPD_EALIGN (-2)  /* a buffer is not aligned as documented */
+#define PMPD_ESCHED (-3)  /* schedule violates Eq. 2-3 (range / precedence) */
+#define PMPD_EHIP (-4)    /* HIP runtime failure or no usable GPU */
+#define PMPD_ESIZE (-5)   /* caller-provided buffer too small */
+
+#define PMPD_GROUP 128     /* input features per quantisation group */
+#define PMPD_ROW_TILE 64   /* rows per storage tile (one per lane of a wave) */
+#define PMPD_MAX_BATCH 8   /* rows of X accepted by pmpd_gemm's skinny path */
+
+/* One packed linear layer.  Plain data; the pointers are the caller's (device memory for
+ * pmpd_gemv / pmpd_gemm / stacks, host memory for pmpd_unpack).  planes[k] must be 16-byte
+ * aligned, scale_min 4-byte aligned.  planes[b..3] are never read by a b-bit call and may be
+ * NULL for it. */
+typedef struct pmpd_layer {
+  int32_t out_features;
+  int32_t in_features; /* multiple of 128 */
+  int32_t group_size;  /* must be 128 */
+  int32_t reserved;    /* must be 0 */
+  const void* planes[4];
+  const void* scale_min;
+} pmpd_layer_t;
+
+typedef struct pmpd_stack pmpd_stack_t;       /* a list of layers prepared for one-launch decode steps */
+typedef struct pmpd_schedule pmpd_schedule_t; /* precision-switching schedule <P, S> */
+
+const char* pmpd_strerror(int32_t status);
+const char* pmpd_last_error(void);
+
+/* Bytes of one plane and of the scale_min array for a layer of this shape. */
+int32_t pmpd_packed_size(int32_t out_features, int32_t in_features, int32_t group_size,
+                         size_t* plane_bytes, size_t* scale_min_bytes);
+
+/* Offline stage (Algorithm 1, line 1 hands over quantised variants; this turns 4-bit codes
+ * into the nested store).  All pointers host.  q4: row-major [out][in], values 0..15.
+ * scale, minv: fp16 bit patterns, row-major [out][in/128].  planes[k], scale_min: host
+ * buffers of the sizes pmpd_packed_size reports; fully overwritten (padding rows zero). */
+int32_t pmpd_pack(const uint8_t* q4, const uint16_t* scale, const uint16_t* minv, int32_t out_features,
+                  int32_t in_features, int32_t group_size, void* const planes[4], void* scale_min);
+
+/* Host inverse of pmpd_pack for the top b planes: qb_out[r][i] = q4[r][i] >> (4-b), b in 1..4.
+ * Reads host_layer->planes[0..b-1] only. */
+int32_t pmpd_unpack(const pmpd_layer_t* host_layer, int32_t b, uint8_t* qb_out);
+
+/* y = W_b x for one layer (the decode-phase linear layer, Algorithm 1 line 16).
+ * x: device, fp16 [in], 16-byte aligned.  y: device, fp32 [out].  b in {2,3,4}. */
+int32_t pmpd_gemv(const pmpd_layer_t* layer, int32_t b, const void* x, float* y, void* stream);
+
+/* Y[j][r] = sum_i W_b[r][i] X[j][i] for 1 <= m <= PMPD_MAX_BATCH; weights are read once.
+ * X: device, fp16 row-major [m][in], 16-byte aligned.  Y: device, fp32 row-major [m][out]. */
+int32_t pmpd_gemm(const pmpd_layer_t* layer, int32_t b, const void* X, int32_t m, float* Y, void* stream);
+
+/* ---- a stack of layers decoded with one launch per step --------------------------------- *
+ * The paper observes that per-kernel CPU launch work becomes the bottleneck once the layers
+ * are this fast (Section 5.2 "GPU Evaluation"); a stack runs every linear layer of a decode
+ * step in one launch.  Layer l reads x_base + x_offset[l] (fp16 elements, offset multiple of 8)
+ * and writes y_base + y_offset[l] (fp32 elements).  The layers are independent of each other.
+ * The stack's device-side tables live in a caller-provided device workspace of at least
+ * pmpd_stack_workspace_size() bytes (256-byte aligned), which must stay untouched while the
+ * stack exists.  pmpd_stack_create copies the tables there synchronously. */
+int32_t pmpd_stack_workspace_size(const pmpd_layer_t* layers, int32_t n_layers, size_t* bytes);
+int32_t pmpd_stack_create(const pmpd_layer_t* layers, int32_t n_layers, const int64_t* x_offset,
+                          const int64_t* y_offset, void* workspace, size_t workspace_bytes,
+                          pmpd_stack_t** out);
+void pmpd_stack_destroy(pmpd_stack_t* stack);
+
+/* One decode step: every layer of the stack at bit-width b, one kernel launch. */
+int32_t pmpd_decode_step(const pmpd_stack_t* stack, int32_t b, const void* x_base, float* y_base,
+                         void* stream);
+
+/* ---- precision-switching schedule (Section 4.2, Eq. 1-3; Algorithm 1 lines 14 and 20) ----- *
+ * precisions[0..n-1] strictly decreasing bit-widths; st[j] = index of the first decode step
+ * run at precisions[j].  Requirements: st[0] == 0 (decoding starts at the allocated decode
+ * precision), 0 <= st[j] <= max_steps, st non-decreasing (a higher precision never starts after
+ * a lower one, Eq. 3).  st[j] == max_steps means "never reached".  Violations -> PMPD_ESCHED. */
+int32_t pmpd_schedule_create(const int32_t* precisions, const int32_t* st, int32_t n, int32_t max_steps,
+                             pmpd_schedule_t** out);
+void pmpd_schedule_destroy(pmpd_schedule_t* schedule);
+/* Bit-width of decode step `step` (>= 0): the lowest precision whose switch point is <= step. */
+int32_t pmpd_schedule_bits(const pmpd_schedule_t* schedule, int32_t step, int32_t* b_out);
+/* Mean bit-width over steps 0..n_steps-1 (Section 5 "Baselines"); negative on error. */
+double pmpd_schedule_avg_bits(const pmpd_schedule_t* schedule, int32_t n_steps);
+
+/* Steps step0 .. step0+n_steps-1 of a decode run, each at the schedule's bit-width (which must
+ * be in {2,3,4}).  Step k reads x_base + (k-step0)*x_step_stride and writes
+ * y_base + (k-step0)*y_step_stride (strides in elements; 0 reuses the same buffers). */
+int32_t pmpd_decode_run(const pmpd_stack_t* stack, const pmpd_schedule_t* schedule, int32_t step0,
+                        int32_t n_steps, const void* x_base, int64_t x_step_stride, float* y_base,
+                        int64_t y_step_stride, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PMPD_H_ */

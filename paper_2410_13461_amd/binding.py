@@ -1,0 +1,319 @@
+"""ctypes binding of libpmpd.so (names follow include/pmpd.h)."""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass, field
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+from . import build as _build
+
+GROUP = 128
+ROW_TILE = 64
+MAX_BATCH = 8
+
+EXPORTS = (
+    "pmpd_strerror", "pmpd_last_error", "pmpd_packed_size", "pmpd_pack", "pmpd_unpack", "pmpd_gemv", "pmpd_gemm",
+    "pmpd_stack_workspace_size", "pmpd_stack_create", "pmpd_stack_destroy", "pmpd_decode_step",
+    "pmpd_schedule_create", "pmpd_schedule_destroy", "pmpd_schedule_bits", "pmpd_schedule_avg_bits",
+    "pmpd_decode_run",
+)
+
+
+class PMPDError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"pmpd status {status}: {message}")
+        self.status = status
+
+
+class _Layer(ctypes.Structure):
+    _fields_ = [
+        ("out_features", ctypes.c_int32),
+        ("in_features", ctypes.c_int32),
+        ("group_size", ctypes.c_int32),
+        ("reserved", ctypes.c_int32),
+        ("planes", ctypes.c_void_p * 4),
+        ("scale_min", ctypes.c_void_p),
+    ]
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _build.LIB
+
+
+def _load():
+    """Load the in-tree library; build it only if it is absent.  No fallback."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build()
+    L = ctypes.CDLL(_build.LIB)
+    i32, i64, vp, sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
+    P = ctypes.POINTER
+    L.pmpd_strerror.restype = ctypes.c_char_p
+    L.pmpd_strerror.argtypes = [i32]
+    L.pmpd_last_error.restype = ctypes.c_char_p
+    L.pmpd_last_error.argtypes = []
+    L.pmpd_packed_size.restype = i32
+    L.pmpd_packed_size.argtypes = [i32, i32, i32, P(sz), P(sz)]
+    L.pmpd_pack.restype = i32
+    L.pmpd_pack.argtypes = [vp, vp, vp, i32, i32, i32, P(vp), vp]
+    L.pmpd_unpack.restype = i32
+    L.pmpd_unpack.argtypes = [P(_Layer), i32, vp]
+    L.pmpd_gemv.restype = i32
+    L.pmpd_gemv.argtypes = [P(_Layer), i32, vp, vp, vp]
+    L.pmpd_gemm.restype = i32
+    L.pmpd_gemm.argtypes = [P(_Layer), i32, vp, i32, vp, vp]
+    L.pmpd_stack_workspace_size.restype = i32
+    L.pmpd_stack_workspace_size.argtypes = [P(_Layer), i32, P(sz)]
+    L.pmpd_stack_create.restype = i32
+    L.pmpd_stack_create.argtypes = [P(_Layer), i32, P(i64), P(i64), vp, sz, P(vp)]
+    L.pmpd_stack_destroy.restype = None
+    L.pmpd_stack_destroy.argtypes = [vp]
+    L.pmpd_decode_step.restype = i32
+    L.pmpd_decode_step.argtypes = [vp, i32, vp, vp, vp]
+    L.pmpd_schedule_create.restype = i32
+    L.pmpd_schedule_create.argtypes = [P(i32), P(i32), i32, i32, P(vp)]
+    L.pmpd_schedule_destroy.restype = None
+    L.pmpd_schedule_destroy.argtypes = [vp]
+    L.pmpd_schedule_bits.restype = i32
+    L.pmpd_schedule_bits.argtypes = [vp, i32, P(i32)]
+    L.pmpd_schedule_avg_bits.restype = ctypes.c_double
+    L.pmpd_schedule_avg_bits.argtypes = [vp, i32]
+    L.pmpd_decode_run.restype = i32
+    L.pmpd_decode_run.argtypes = [vp, vp, i32, i32, vp, i64, vp, i64, vp]
+    _lib = L
+    return L
+
+
+def exported_symbols() -> List[str]:
+    """Names from include/pmpd.h that the loaded library really exports."""
+    L = _load()
+    return [n for n in EXPORTS if hasattr(L, n)]
+
+
+def _check(status: int):
+    if status != 0:
+        raise PMPDError(status, _load().pmpd_last_error().decode())
+
+
+def _np_ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _stream_handle(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+# ------------------------------------------------------------------- packing ----
+def packed_size(out_features: int, in_features: int, group_size: int = GROUP) -> Tuple[int, int]:
+    pb, sb = ctypes.c_size_t(), ctypes.c_size_t()
+    _check(_load().pmpd_packed_size(out_features, in_features, group_size, ctypes.byref(pb), ctypes.byref(sb)))
+    return pb.value, sb.value
+
+
+def pack(q4: np.ndarray, scale: np.ndarray, minv: np.ndarray, group_size: int = GROUP):
+    """Host pack: (q4 uint8 [out,in], scale fp16 [out,in/128], minv fp16) -> (4 plane arrays, scale_min array)."""
+    q4 = np.ascontiguousarray(q4, dtype=np.uint8)
+    out_f, in_f = q4.shape
+    s = np.ascontiguousarray(np.asarray(scale, dtype=np.float16)).view(np.uint16)
+    a = np.ascontiguousarray(np.asarray(minv, dtype=np.float16)).view(np.uint16)
+    pb, sb = packed_size(out_f, in_f, group_size)
+    if s.shape != (out_f, in_f // group_size) or a.shape != s.shape:
+        raise PMPDError(-1, "scale/minv must have shape [out, in/group]")
+    planes = [np.empty(pb // 4, dtype=np.uint32) for _ in range(4)]
+    sm = np.empty(sb // 4, dtype=np.uint32)
+    arr = (ctypes.c_void_p * 4)(*[p.ctypes.data for p in planes])
+    _check(_load().pmpd_pack(_np_ptr(q4), _np_ptr(s), _np_ptr(a), out_f, in_f, group_size, arr, _np_ptr(sm)))
+    return planes, sm
+
+
+def unpack(planes: Sequence[Optional[np.ndarray]], b: int, out_features: int, in_features: int) -> np.ndarray:
+    """Host unpack of the top b planes; planes[b:] may be None."""
+    lay = _Layer(out_features, in_features, GROUP, 0)
+    keep = []
+    for k in range(4):
+        p = planes[k] if k < len(planes) else None
+        if p is not None:
+            p = np.ascontiguousarray(p, dtype=np.uint32)
+            keep.append(p)
+            lay.planes[k] = p.ctypes.data
+        else:
+            lay.planes[k] = None
+    dummy = np.zeros(1, dtype=np.uint32)
+    lay.scale_min = dummy.ctypes.data
+    qb = np.empty((out_features, in_features), dtype=np.uint8)
+    _check(_load().pmpd_unpack(ctypes.byref(lay), b, _np_ptr(qb)))
+    return qb
+
+
+# ------------------------------------------------------------- device layers ----
+@dataclass
+class PackedLayer:
+    """A packed layer resident in device memory (tensors are owned here)."""
+
+    out_features: int
+    in_features: int
+    planes: list  # 4 torch int32 tensors (entries may be None)
+    scale_min: object  # torch int32 tensor
+    _struct: _Layer = field(default=None, repr=False)
+
+    def struct(self) -> _Layer:
+        if self._struct is None:
+            lay = _Layer(self.out_features, self.in_features, GROUP, 0)
+            for k in range(4):
+                lay.planes[k] = self.planes[k].data_ptr() if self.planes[k] is not None else None
+            lay.scale_min = self.scale_min.data_ptr()
+            self._struct = lay
+        return self._struct
+
+    def bytes_at(self, b: int) -> int:
+        """Bytes a b-bit pass streams: b planes plus the scale/min words."""
+        pb, sb = packed_size(self.out_features, self.in_features)
+        return b * pb + sb
+
+
+def upload_layer(planes, scale_min, out_features: int, in_features: int, device="cuda") -> PackedLayer:
+    import torch
+
+    dp = [torch.from_numpy(p.view(np.int32)).to(device) if p is not None else None for p in planes]
+    ds = torch.from_numpy(scale_min.view(np.int32)).to(device)
+    return PackedLayer(out_features, in_features, dp, ds)
+
+
+def _dev_ptr(t):
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def gemv(layer: PackedLayer, b: int, x, y=None, stream=None):
+    """y = W_b x.  x: torch fp16 [in] on the GPU; returns torch fp32 [out]."""
+    import torch
+
+    if y is None:
+        y = torch.empty(layer.out_features, dtype=torch.float32, device=x.device)
+    _check(_load().pmpd_gemv(ctypes.byref(layer.struct()), b, _dev_ptr(x), _dev_ptr(y), _stream_handle(stream)))
+    return y
+
+
+def gemm(layer: PackedLayer, b: int, X, Y=None, stream=None):
+    """Y = X W_b^T for 1..8 rows of X.  X: torch fp16 [m, in]; returns torch fp32 [m, out]."""
+    import torch
+
+    m = X.shape[0]
+    if Y is None:
+        Y = torch.empty((m, layer.out_features), dtype=torch.float32, device=X.device)
+    _check(_load().pmpd_gemm(ctypes.byref(layer.struct()), b, _dev_ptr(X), m, _dev_ptr(Y), _stream_handle(stream)))
+    return Y
+
+
+class Stack:
+    """A list of device layers prepared for one-launch decode steps."""
+
+    def __init__(self, layers: Sequence[PackedLayer], x_offsets: Optional[Sequence[int]] = None,
+                 y_offsets: Optional[Sequence[int]] = None, device="cuda"):
+        import torch
+
+        self.layers = list(layers)
+        n = len(self.layers)
+        if x_offsets is None:
+            x_offsets, acc = [], 0
+            for l in self.layers:
+                x_offsets.append(acc)
+                acc += l.in_features
+        if y_offsets is None:
+            y_offsets, acc = [], 0
+            for l in self.layers:
+                y_offsets.append(acc)
+                acc += l.out_features
+        self.x_offsets, self.y_offsets = list(x_offsets), list(y_offsets)
+        self.x_elems = max(o + l.in_features for o, l in zip(self.x_offsets, self.layers)) if n else 0
+        self.y_elems = max(o + l.out_features for o, l in zip(self.y_offsets, self.layers)) if n else 0
+        arr = (_Layer * max(n, 1))(*[l.struct() for l in self.layers])
+        need = ctypes.c_size_t()
+        L = _load()
+        _check(L.pmpd_stack_workspace_size(arr, n, ctypes.byref(need)))
+        self.workspace = torch.empty(need.value + 256, dtype=torch.uint8, device=device)
+        base = self.workspace.data_ptr()
+        aligned = (base + 255) // 256 * 256
+        xo = (ctypes.c_int64 * n)(*self.x_offsets)
+        yo = (ctypes.c_int64 * n)(*self.y_offsets)
+        h = ctypes.c_void_p()
+        _check(L.pmpd_stack_create(arr, n, xo, yo, ctypes.c_void_p(aligned), need.value, ctypes.byref(h)))
+        self._h = h
+
+    def bytes_at(self, b: int) -> int:
+        return sum(l.bytes_at(b) for l in self.layers)
+
+    def close(self):
+        if getattr(self, "_h", None):
+            _load().pmpd_stack_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def decode_step(stack: Stack, b: int, x, y, stream=None):
+    """One decode step over the stack at bit-width b.  x: fp16 [x_elems], y: fp32 [y_elems]."""
+    _check(_load().pmpd_decode_step(stack._h, b, _dev_ptr(x), _dev_ptr(y), _stream_handle(stream)))
+    return y
+
+
+class Schedule:
+    """Precision-switching schedule <P, S>."""
+
+    def __init__(self, precisions: Sequence[int], st: Sequence[int], max_steps: int):
+        n = len(precisions)
+        if len(st) != n:
+            raise PMPDError(-1, "precisions and st must have the same length")
+        p = (ctypes.c_int32 * max(n, 1))(*precisions)
+        s = (ctypes.c_int32 * max(n, 1))(*st)
+        h = ctypes.c_void_p()
+        _check(_load().pmpd_schedule_create(p, s, n, max_steps, ctypes.byref(h)))
+        self._h = h
+        self.max_steps = max_steps
+
+    def bits(self, step: int) -> int:
+        b = ctypes.c_int32()
+        _check(_load().pmpd_schedule_bits(self._h, step, ctypes.byref(b)))
+        return b.value
+
+    def avg_bits(self, n_steps: int) -> float:
+        v = _load().pmpd_schedule_avg_bits(self._h, n_steps)
+        if v < 0:
+            raise PMPDError(-1, _load().pmpd_last_error().decode())
+        return v
+
+    def close(self):
+        if getattr(self, "_h", None):
+            _load().pmpd_schedule_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def decode_run(stack: Stack, schedule: Schedule, step0: int, n_steps: int, x, x_step_stride: int, y,
+               y_step_stride: int, stream=None):
+    """Steps step0..step0+n_steps-1, each at the schedule's bit-width."""
+    _check(_load().pmpd_decode_run(stack._h, schedule._h, step0, n_steps, _dev_ptr(x), x_step_stride, _dev_ptr(y),
+                                   y_step_stride, _stream_handle(stream)))
+    return y

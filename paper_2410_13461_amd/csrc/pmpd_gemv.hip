@@ -1,0 +1,585 @@
+// HIP kernels (gfx950, wave64) and launchers for the PMPD decode linear layers.
+//
+// Mapping.  Lane l of a wave owns row 64*T + l of a row tile T; the wave walks the
+// quantisation groups g of its K-range.  Per (tile, group) the wave issues one coalesced
+// 1 KiB global_load_dwordx4 per bit-plane (16 bytes = 128 weights of one row per lane) and one
+// 256-byte load of the (scale, min) words.  The activation vector sits in LDS; all lanes read
+// the same x words (broadcast reads, no bank conflicts) because they work on the same columns.
+// No cross-lane reduction exists; split-K partial sums of different waves meet in LDS in a
+// fixed order, so results are run-to-run identical.
+//
+// Unpack.  The storage format places the bit of plane k for weight u = 2p + half,
+// p = 4m + 2v + h, at bit (16 half + 8 v + 4 h + 3 - k + m) mod 32.  For each m one bit-select
+// chain (v_bfi_b32, B-1 ops) merges the B plane words into a word whose 4-bit fields, after a
+// rotate by m, are complete codes: byte v, nibble h, 16-bit half `half`.  One v_and_or_b32
+// masks the field of both halves and ORs in the fp16 exponent 0x6400, giving the pair
+// (1024 + c*q, 1024 + c*q') with c = 1 (low nibble) or 16 (high nibble) without any shift; the
+// planes that a b-bit pass does not read are simply absent from the mask, so the field holds
+// q~ = q_b * 2^(4-b).  v_dot2_f32_f16 multiplies the pair with the matching pair of x in fp32.
+// The constant 1024 and the factor 16 are removed per group with sums of x prepared once per
+// workgroup:
+//     sum_i W_b[r][i] x[i] = sum_g { a_g X_g + s_g ( accL + accH/16 + F_g ) }
+//     X_g = sum of x over the group, F_g = 2^(3-b) X_g - 1024 (X_g^low + X_g^high / 16)
+// where "low"/"high" are the columns whose field is the low/high nibble (i mod 4 < 2 / >= 2).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+#include "pmpd_common.hpp"
+
+#ifndef PMPD_PF
+#define PMPD_PF 1  // groups of plane words kept in flight ahead of the one being consumed
+#endif
+#ifndef PMPD_USE_SCHED_BARRIER
+#define PMPD_USE_SCHED_BARRIER 1
+#endif
+#if PMPD_USE_SCHED_BARRIER
+#define PMPD_SCHED_BARRIER() __builtin_amdgcn_sched_barrier(0)
+#else
+#define PMPD_SCHED_BARRIER()
+#endif
+
+namespace pmpd {
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+// Pointers into device global memory that were read from a table keep the generic address space;
+// naming the global one lets the compiler emit global_load (vmcnt only) instead of flat_load.
+typedef const __attribute__((address_space(1))) u32x4* global_u32x4_ptr;
+typedef const __attribute__((address_space(1))) uint32_t* global_u32_ptr;
+
+__device__ __forceinline__ float dot2(uint32_t w, uint32_t x, float acc) {
+  return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, w), __builtin_bit_cast(half2_t, x), acc, false);
+}
+
+// (a & mask) | (b & ~mask) in one VALU op.
+__device__ __forceinline__ uint32_t bfi(uint32_t mask, uint32_t a, uint32_t b) {
+  uint32_t d;
+  asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(d) : "s"(mask), "v"(a), "v"(b));
+  return d;
+}
+
+// (a & mask) | c in one VALU op.
+__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t c) {
+  uint32_t d;
+  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "s"(mask), "v"(c));
+  return d;
+}
+
+__device__ __forceinline__ uint32_t word_of(const u32x4& v, int d) {
+  return d == 0 ? v.x : d == 1 ? v.y : d == 2 ? v.z : v.w;
+}
+
+__device__ __forceinline__ float half_bits_to_float(uint32_t bits16) {
+  return static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(bits16)));
+}
+
+// Sub-slot masks: bit positions congruent to j mod 4.
+__host__ __device__ constexpr uint32_t slot_mask(int j) { return 0x11111111u << (j & 3); }
+
+// Merge the B plane words of one 32-weight word into the word whose fields (rotated by m)
+// are the codes of pairs 4m .. 4m+3.  Plane k sits in sub-slot (3 - k + m) mod 4.
+template <int B>
+__device__ __forceinline__ uint32_t merge_planes(const uint32_t (&p)[B], int m) {
+  if constexpr (B == 4) {
+    uint32_t hi = bfi(slot_mask(3 + m), p[0], p[1]);
+    uint32_t lo = bfi(slot_mask(1 + m), p[2], p[3]);
+    return bfi(slot_mask(3 + m) | slot_mask(2 + m), hi, lo);
+  } else if constexpr (B == 3) {
+    uint32_t lo = bfi(slot_mask(2 + m), p[1], p[2]);
+    return bfi(slot_mask(3 + m), p[0], lo);
+  } else {
+    return bfi(slot_mask(3 + m), p[0], p[1]);
+  }
+}
+
+// Multiply-accumulate one group (128 columns) of the lane's row against M activation vectors.
+//   pl[k]: the lane's 16 bytes of plane k;  xs: the group's 16 uint4 of x in LDS for vector 0,
+//   vector j lies xstride uint4 further.  The unpack runs once, the dot products M times.
+template <int B, int M>
+__device__ __forceinline__ void mac_group(const u32x4 (&pl)[B], const uint4* __restrict__ xs, int xstride,
+                                          float (&accL)[M], float (&accH)[M]) {
+  constexpr uint32_t kKeep = (0xFu << (4 - B)) & 0xFu;  // top B bits of a 4-bit field
+  const uint32_t maskL = kKeep * 0x00010001u;
+  const uint32_t maskH = maskL << 4;
+  uint32_t magic = 0x64006400u;  // fp16 pair (1024, 1024)
+  asm volatile("" : "+v"(magic));
+  float l0[M], l1[M], h0[M], h1[M];
+#pragma unroll
+  for (int j = 0; j < M; ++j) l0[j] = l1[j] = h0[j] = h1[j] = 0.f;
+  // The scheduler barriers below pin the order "LDS reads of the next step, unpack, dot
+  // products" so that the compiler cannot hoist the unpack of the whole group above the first
+  // dot product (which would keep 64 unpacked registers alive and spill).
+  if constexpr (M == 1) {
+    uint4 xc[4];
+#pragma unroll
+    for (int m = 0; m < 4; ++m) xc[m] = xs[m];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      uint4 xn[4];
+      if (d < 3) {
+#pragma unroll
+        for (int m = 0; m < 4; ++m) xn[m] = xs[(d + 1) * 4 + m];
+      }
+      uint32_t p[B];
+#pragma unroll
+      for (int k = 0; k < B; ++k) p[k] = word_of(pl[k], d);
+#pragma unroll
+      for (int m = 0; m < 4; ++m) {
+        uint32_t u = merge_planes<B>(p, m);
+        uint32_t w = (m == 0) ? u : __builtin_amdgcn_alignbit(u, u, m);
+        uint32_t w8 = w >> 8;
+        l0[0] = dot2(and_or(w, maskL, magic), xc[m].x, l0[0]);
+        h0[0] = dot2(and_or(w, maskH, magic), xc[m].y, h0[0]);
+        l1[0] = dot2(and_or(w8, maskL, magic), xc[m].z, l1[0]);
+        h1[0] = dot2(and_or(w8, maskH, magic), xc[m].w, h1[0]);
+      }
+      PMPD_SCHED_BARRIER();
+      if (d < 3) {
+#pragma unroll
+        for (int m = 0; m < 4; ++m) xc[m] = xn[m];
+      }
+    }
+  } else {
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      uint32_t p[B];
+#pragma unroll
+      for (int k = 0; k < B; ++k) p[k] = word_of(pl[k], d);
+#pragma unroll
+      for (int m = 0; m < 4; ++m) {
+        uint4 xq[M];
+#pragma unroll
+        for (int j = 0; j < M; ++j) xq[j] = xs[j * xstride + d * 4 + m];
+        uint32_t u = merge_planes<B>(p, m);
+        uint32_t w = (m == 0) ? u : __builtin_amdgcn_alignbit(u, u, m);
+        uint32_t w8 = w >> 8;
+        const uint32_t r0 = and_or(w, maskL, magic), r1 = and_or(w, maskH, magic);
+        const uint32_t r2 = and_or(w8, maskL, magic), r3 = and_or(w8, maskH, magic);
+#pragma unroll
+        for (int j = 0; j < M; ++j) {
+          l0[j] = dot2(r0, xq[j].x, l0[j]);
+          h0[j] = dot2(r1, xq[j].y, h0[j]);
+          l1[j] = dot2(r2, xq[j].z, l1[j]);
+          h1[j] = dot2(r3, xq[j].w, h1[j]);
+        }
+        PMPD_SCHED_BARRIER();
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < M; ++j) {
+    accL[j] = l0[j] + l1[j];
+    accH[j] = h0[j] + h1[j];
+  }
+}
+
+// LDS image of one K-chunk of the activations: for each of the M vectors `cg` groups of x as
+// fp16 (16 uint4 per group), then (X_g, F_g) per (vector, group), then M*NW*64 floats where
+// the split-K partial sums meet.
+__host__ __device__ inline size_t lds_bytes(int cg, int m, int n_waves) {
+  return static_cast<size_t>(m) * cg * (256 + 8) + static_cast<size_t>(m) * n_waves * 64 * 4;
+}
+
+// Groups per K-chunk: the whole row when it fits in about 32 KiB of LDS, else as many as fit.
+__host__ __device__ inline int chunk_groups(int n_groups, int m) {
+  const int fit = (32 * 1024) / (m * 256);
+  return n_groups < fit ? n_groups : fit;
+}
+
+// Copy groups [c0, c0+cn) of the M activation vectors into LDS and prepare the per-group sums.
+template <int B, int M, int NW>
+__device__ __forceinline__ void stage_activations(const _Float16* __restrict__ x, int in_f, int c0, int cn, int cg,
+                                                  uint4* xs, float2* cs) {
+  const int n16 = cn * 16;
+#pragma unroll 1
+  for (int j = 0; j < M; ++j) {
+    const uint4* xg = reinterpret_cast<const uint4*>(x + static_cast<int64_t>(j) * in_f) + c0 * 16;
+    for (int idx = threadIdx.x; idx < n16; idx += NW * 64) {
+      const uint4 v = xg[idx];
+      xs[j * cg * 16 + idx] = v;
+      // columns 8*idx .. 8*idx+7: (0,1) low, (2,3) high, (4,5) low, (6,7) high
+      const half2_t a = __builtin_bit_cast(half2_t, v.x), b = __builtin_bit_cast(half2_t, v.y);
+      const half2_t c = __builtin_bit_cast(half2_t, v.z), e = __builtin_bit_cast(half2_t, v.w);
+      float lo = (static_cast<float>(a.x) + static_cast<float>(a.y)) + (static_cast<float>(c.x) + static_cast<float>(c.y));
+      float hi = (static_cast<float>(b.x) + static_cast<float>(b.y)) + (static_cast<float>(e.x) + static_cast<float>(e.y));
+#pragma unroll
+      for (int off = 1; off < 16; off <<= 1) {
+        lo += __shfl_xor(lo, off, 16);
+        hi += __shfl_xor(hi, off, 16);
+      }
+      if ((idx & 15) == 0) {
+        const float X = lo + hi;
+        const float F = X * (B == 4 ? 0.5f : B == 3 ? 1.0f : 2.0f) - 1024.0f * (lo + hi * 0.0625f);
+        cs[j * cg + (idx >> 4)] = make_float2(X, F);
+      }
+    }
+  }
+}
+
+// One workgroup: TPW = NW / SPLITK consecutive row tiles starting at tile0, each split over
+// SPLITK waves along K; K is walked in chunks of cg groups whose activations fit in LDS.
+// x: M vectors of in_f fp16, y: M vectors of out_f fp32.
+template <int B, int M, int NW, int SPLITK, int PF>
+__device__ __forceinline__ void run_tiles(const LayerDesc& L, int tile0, const _Float16* __restrict__ x,
+                                          float* __restrict__ y, uint4* lds) {
+  static_assert(NW % SPLITK == 0, "waves must divide evenly over the K splits");
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int G = L.n_groups;
+  const int cg = chunk_groups(G, M);
+  uint4* xs = lds;
+  float2* cs = reinterpret_cast<float2*>(lds + M * cg * 16);
+  float* red = reinterpret_cast<float*>(cs + M * cg);
+
+  const int tile = tile0 + wave / SPLITK;
+  const int ks = wave % SPLITK;
+  const bool active = tile < L.n_tiles;
+  const int64_t base = (static_cast<int64_t>(active ? tile : 0) * G) * 64 + lane;  // + g*64 per group
+  global_u32x4_ptr pp[B];
+#pragma unroll
+  for (int k = 0; k < B; ++k) pp[k] = (global_u32x4_ptr)(L.plane[k]) + base;
+  global_u32_ptr sp = (global_u32_ptr)(L.sa) + base;
+
+  float yacc[M];
+#pragma unroll
+  for (int j = 0; j < M; ++j) yacc[j] = 0.f;
+
+  for (int c0 = 0; c0 < G; c0 += cg) {
+    const int cn = (G - c0 < cg) ? (G - c0) : cg;
+    if (c0) __syncthreads();  // everyone is done with the previous chunk's image
+    stage_activations<B, M, NW>(x, L.in_f, c0, cn, cg, xs, cs);
+    __syncthreads();
+    const int g0 = c0 + cn * ks / SPLITK, g1 = c0 + cn * (ks + 1) / SPLITK;
+    if (active && g0 < g1) {
+      // Register ring of PF groups in flight.  Loads are unconditional with the group index
+      // clamped to the last one of the range, so the loop body is branch-free for the loads
+      // and the ring needs no register copies; the few clamped reloads hit the cache.
+      u32x4 nb[PF][B];
+      uint32_t nsa[PF];
+#pragma unroll
+      for (int j = 0; j < PF; ++j) {
+        const int gl = (g0 + j < g1) ? (g0 + j) : (g1 - 1);
+#pragma unroll
+        for (int k = 0; k < B; ++k) nb[j][k] = pp[k][gl * 64];
+        nsa[j] = sp[gl * 64];
+      }
+      for (int g = g0; g < g1; g += PF) {
+#pragma unroll
+        for (int j = 0; j < PF; ++j) {
+          const int gc = g + j;
+          u32x4 cur[B];
+#pragma unroll
+          for (int k = 0; k < B; ++k) cur[k] = nb[j][k];
+          const uint32_t csa = nsa[j];
+          const int gl = (gc + PF < g1) ? (gc + PF) : (g1 - 1);
+#pragma unroll
+          for (int k = 0; k < B; ++k) nb[j][k] = pp[k][gl * 64];
+          nsa[j] = sp[gl * 64];
+          if (gc < g1) {
+            float accL[M], accH[M];
+            mac_group<B, M>(cur, xs + (gc - c0) * 16, cg * 16, accL, accH);
+            const float s = half_bits_to_float(csa & 0xffffu);
+            const float a = half_bits_to_float(csa >> 16);
+#pragma unroll
+            for (int j2 = 0; j2 < M; ++j2) {
+              const float2 c = cs[j2 * cg + (gc - c0)];
+              const float u = fmaf(accH[j2], 0.0625f, accL[j2]) + c.y;
+              yacc[j2] = fmaf(s, u, yacc[j2]);
+              yacc[j2] = fmaf(a, c.x, yacc[j2]);
+            }
+          }
+        }
+      }
+    }
+  }
+  if constexpr (SPLITK > 1) {
+#pragma unroll
+    for (int j = 0; j < M; ++j) red[(j * NW + wave) * 64 + lane] = yacc[j];
+    __syncthreads();
+    if (ks == 0) {
+#pragma unroll
+      for (int j = 0; j < M; ++j) {
+        float sum = yacc[j];
+#pragma unroll
+        for (int q = 1; q < SPLITK; ++q) sum += red[(j * NW + wave + q) * 64 + lane];
+        yacc[j] = sum;
+      }
+    }
+  }
+  if (ks == 0 && active) {
+    const int row = tile * 64 + lane;
+    if (row < L.out_f) {
+#pragma unroll
+      for (int j = 0; j < M; ++j) y[static_cast<int64_t>(j) * L.out_f + row] = yacc[j];
+    }
+  }
+}
+
+template <int B, int NW, int SPLITK, int PF>
+__global__ __launch_bounds__(NW * 64, 4) void pmpd_gemv_stack_kernel(const LayerDesc* __restrict__ layers,
+                                                                   const WorkItem* __restrict__ items,
+                                                                   const _Float16* __restrict__ x_base,
+                                                                   float* __restrict__ y_base) {
+  extern __shared__ uint4 lds[];
+  const WorkItem it = items[blockIdx.x];
+  const LayerDesc L = layers[it.layer];
+  run_tiles<B, 1, NW, SPLITK, PF>(L, it.tile0, x_base + L.x_off, y_base + L.y_off, lds);
+}
+
+template <int B, int M, int NW, int SPLITK, int PF>
+__global__ __launch_bounds__(NW * 64, 4) void pmpd_gemv_layer_kernel(LayerDesc L, const _Float16* __restrict__ x,
+                                                                   float* __restrict__ y) {
+  extern __shared__ uint4 lds[];
+  run_tiles<B, M, NW, SPLITK, PF>(L, static_cast<int>(blockIdx.x) * (NW / SPLITK), x, y, lds);
+}
+
+// ------------------------------------------------------------------ host side ----
+static int32_t hip_fail(hipError_t e, const char* what) {
+  return fail(PMPD_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+static LayerDesc make_desc(const pmpd_layer_t& L, int64_t x_off, int64_t y_off) {
+  LayerDesc d;
+  for (int k = 0; k < 4; ++k) d.plane[k] = L.planes[k];
+  d.sa = L.scale_min;
+  d.x_off = x_off;
+  d.y_off = y_off;
+  d.out_f = L.out_features;
+  d.in_f = L.in_features;
+  d.n_groups = L.in_features / kGroup;
+  d.n_tiles = static_cast<int32_t>(padded_rows(L.out_features) / kTile);
+  return d;
+}
+
+static int32_t check_bits(int32_t b, const char* who) {
+  if (b < 2 || b > 4) return fail(PMPD_EINVAL, "%s: bit-width %d outside {2,3,4}", who, b);
+  return PMPD_OK;
+}
+
+// Launch shapes.  A stack has thousands of row tiles, so whole-K waves (no split) keep x
+// staging rare; a single layer has few tiles and splits K to put more waves on the machine.
+template <int B, int M, int NW, int SPLITK>
+static hipError_t launch_layer(const LayerDesc& d, const void* x, float* y, hipStream_t s) {
+  const int tpw = NW / SPLITK;
+  const unsigned grid = static_cast<unsigned>((d.n_tiles + tpw - 1) / tpw);
+  const size_t lds = lds_bytes(chunk_groups(d.n_groups, M), M, NW);
+  hipLaunchKernelGGL((pmpd_gemv_layer_kernel<B, M, NW, SPLITK, PMPD_PF>), dim3(grid), dim3(NW * 64), lds, s, d,
+                     static_cast<const _Float16*>(x), y);
+  return hipGetLastError();
+}
+
+template <int B, int M>
+static hipError_t launch_layer_bm(const LayerDesc& d, const void* x, float* y, hipStream_t s) {
+  // Split K until about 2048 waves exist or a wave would get fewer than 4 groups of a chunk.
+  const int cg = chunk_groups(d.n_groups, M);
+  int splitk = 1;
+  while (splitk < 8 && static_cast<int64_t>(d.n_tiles) * splitk < 2048 && cg / (splitk * 2) >= 4) splitk *= 2;
+  switch (splitk) {
+    case 1: return launch_layer<B, M, 4, 1>(d, x, y, s);
+    case 2: return launch_layer<B, M, 4, 2>(d, x, y, s);
+    case 4: return launch_layer<B, M, 4, 4>(d, x, y, s);
+    default: return launch_layer<B, M, 8, 8>(d, x, y, s);
+  }
+}
+
+template <int B>
+static hipError_t launch_layer_b(const LayerDesc& d, const void* x, int m, float* y, hipStream_t s) {
+  switch (m) {
+    case 1: return launch_layer_bm<B, 1>(d, x, y, s);
+    case 2: return launch_layer_bm<B, 2>(d, x, y, s);
+    case 3: return launch_layer_bm<B, 3>(d, x, y, s);
+    case 4: return launch_layer_bm<B, 4>(d, x, y, s);
+    case 5: return launch_layer_bm<B, 5>(d, x, y, s);
+    case 6: return launch_layer_bm<B, 6>(d, x, y, s);
+    case 7: return launch_layer_bm<B, 7>(d, x, y, s);
+    default: return launch_layer_bm<B, 8>(d, x, y, s);
+  }
+}
+
+static int32_t linear_entry(const char* who, const pmpd_layer_t* layer, int32_t b, const void* x, int32_t m, float* y,
+                            void* stream) {
+  int32_t rc = check_bits(b, who);
+  if (rc) return rc;
+  rc = check_layer(layer, b, who);
+  if (rc) return rc;
+  if (m < 1 || m > PMPD_MAX_BATCH) return fail(PMPD_EINVAL, "%s: batch %d outside 1..%d", who, m, PMPD_MAX_BATCH);
+  if (!x || !y) return fail(PMPD_EINVAL, "%s: x or y is NULL", who);
+  if (reinterpret_cast<uintptr_t>(x) % 16) return fail(PMPD_EALIGN, "%s: x not 16-byte aligned", who);
+  if (reinterpret_cast<uintptr_t>(y) % 4) return fail(PMPD_EALIGN, "%s: y not 4-byte aligned", who);
+  const LayerDesc d = make_desc(*layer, 0, 0);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = b == 4 ? launch_layer_b<4>(d, x, m, y, s)
+                 : b == 3 ? launch_layer_b<3>(d, x, m, y, s)
+                          : launch_layer_b<2>(d, x, m, y, s);
+  if (e != hipSuccess) return hip_fail(e, who);
+  return PMPD_OK;
+}
+
+}  // namespace pmpd
+
+using namespace pmpd;
+
+struct pmpd_stack {
+  std::vector<LayerDesc> layers;
+  std::vector<WorkItem> items[2];  // work lists for the two launch shapes below
+  const LayerDesc* d_layers = nullptr;
+  const WorkItem* d_items[2] = {nullptr, nullptr};
+  int max_in = 0;
+  int shape = 0;
+};
+
+// Stack launch shapes: index 0 = 4 waves, one tile each, whole K; index 1 = 4 waves on one tile, K split 4 ways.
+static constexpr int kStackTilesPerWg[2] = {4, 1};
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+static void build_items(const std::vector<LayerDesc>& layers, int tiles_per_wg, std::vector<WorkItem>& out) {
+  // Longest rows first: the last workgroups to start are the short ones, which trims the tail.
+  std::vector<int> order(layers.size());
+  for (size_t i = 0; i < order.size(); ++i) order[i] = static_cast<int>(i);
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return layers[a].in_f > layers[b].in_f; });
+  out.clear();
+  for (int li : order)
+    for (int t = 0; t < layers[li].n_tiles; t += tiles_per_wg) out.push_back(WorkItem{li, t});
+}
+
+static size_t stack_bytes(const std::vector<LayerDesc>& layers, size_t n_items0, size_t n_items1) {
+  return align_up(layers.size() * sizeof(LayerDesc), 256) + align_up(n_items0 * sizeof(WorkItem), 256) +
+         align_up(n_items1 * sizeof(WorkItem), 256);
+}
+
+static int32_t check_stack_args(const pmpd_layer_t* layers, int32_t n, const char* who) {
+  if (!layers) return fail(PMPD_EINVAL, "%s: layers is NULL", who);
+  if (n < 1 || n > 65536) return fail(PMPD_EINVAL, "%s: n_layers %d outside 1..65536", who, n);
+  for (int i = 0; i < n; ++i) {
+    int32_t rc = check_layer(&layers[i], 4, who);
+    if (rc) return rc;
+  }
+  return PMPD_OK;
+}
+
+template <int B>
+static hipError_t launch_stack(const pmpd_stack* st, const void* x, float* y, hipStream_t s) {
+  const int q = st->shape;
+  const unsigned grid = static_cast<unsigned>(st->items[q].size());
+  const size_t lds = lds_bytes(chunk_groups(st->max_in / kGroup, 1), 1, 4);
+  if (q == 0) {
+    hipLaunchKernelGGL((pmpd_gemv_stack_kernel<B, 4, 1, PMPD_PF>), dim3(grid), dim3(256), lds, s, st->d_layers, st->d_items[0],
+                       static_cast<const _Float16*>(x), y);
+  } else {
+    hipLaunchKernelGGL((pmpd_gemv_stack_kernel<B, 4, 4, PMPD_PF>), dim3(grid), dim3(256), lds, s, st->d_layers, st->d_items[1],
+                       static_cast<const _Float16*>(x), y);
+  }
+  return hipGetLastError();
+}
+
+extern "C" {
+
+int32_t pmpd_gemv(const pmpd_layer_t* layer, int32_t b, const void* x, float* y, void* stream) {
+  return linear_entry("pmpd_gemv", layer, b, x, 1, y, stream);
+}
+
+int32_t pmpd_gemm(const pmpd_layer_t* layer, int32_t b, const void* X, int32_t m, float* Y, void* stream) {
+  return linear_entry("pmpd_gemm", layer, b, X, m, Y, stream);
+}
+
+int32_t pmpd_stack_workspace_size(const pmpd_layer_t* layers, int32_t n, size_t* bytes) {
+  int32_t rc = check_stack_args(layers, n, "pmpd_stack_workspace_size");
+  if (rc) return rc;
+  if (!bytes) return fail(PMPD_EINVAL, "pmpd_stack_workspace_size: bytes is NULL");
+  size_t items[2] = {0, 0};
+  for (int i = 0; i < n; ++i) {
+    int64_t tiles = padded_rows(layers[i].out_features) / kTile;
+    for (int q = 0; q < 2; ++q) items[q] += static_cast<size_t>((tiles + kStackTilesPerWg[q] - 1) / kStackTilesPerWg[q]);
+  }
+  *bytes = align_up(static_cast<size_t>(n) * sizeof(LayerDesc), 256) + align_up(items[0] * sizeof(WorkItem), 256) +
+           align_up(items[1] * sizeof(WorkItem), 256);
+  return PMPD_OK;
+}
+
+int32_t pmpd_stack_create(const pmpd_layer_t* layers, int32_t n, const int64_t* x_offset, const int64_t* y_offset,
+                          void* workspace, size_t workspace_bytes, pmpd_stack_t** out) {
+  int32_t rc = check_stack_args(layers, n, "pmpd_stack_create");
+  if (rc) return rc;
+  if (!x_offset || !y_offset || !workspace || !out) return fail(PMPD_EINVAL, "pmpd_stack_create: NULL argument");
+  if (reinterpret_cast<uintptr_t>(workspace) % 256) return fail(PMPD_EALIGN, "pmpd_stack_create: workspace not 256-byte aligned");
+  for (int i = 0; i < n; ++i) {
+    if (x_offset[i] < 0 || x_offset[i] % 8) return fail(PMPD_EALIGN, "pmpd_stack_create: x_offset[%d] must be a non-negative multiple of 8", i);
+    if (y_offset[i] < 0) return fail(PMPD_EINVAL, "pmpd_stack_create: y_offset[%d] is negative", i);
+  }
+  auto* st = new pmpd_stack;
+  for (int i = 0; i < n; ++i) {
+    st->layers.push_back(make_desc(layers[i], x_offset[i], y_offset[i]));
+    st->max_in = std::max(st->max_in, layers[i].in_features);
+  }
+  for (int q = 0; q < 2; ++q) build_items(st->layers, kStackTilesPerWg[q], st->items[q]);
+  const size_t need = stack_bytes(st->layers, st->items[0].size(), st->items[1].size());
+  if (workspace_bytes < need) {
+    delete st;
+    return fail(PMPD_ESIZE, "pmpd_stack_create: workspace %zu bytes, need %zu", workspace_bytes, need);
+  }
+  char* w = static_cast<char*>(workspace);
+  hipError_t e = hipMemcpy(w, st->layers.data(), st->layers.size() * sizeof(LayerDesc), hipMemcpyHostToDevice);
+  st->d_layers = reinterpret_cast<const LayerDesc*>(w);
+  w += align_up(st->layers.size() * sizeof(LayerDesc), 256);
+  for (int q = 0; q < 2 && e == hipSuccess; ++q) {
+    e = hipMemcpy(w, st->items[q].data(), st->items[q].size() * sizeof(WorkItem), hipMemcpyHostToDevice);
+    st->d_items[q] = reinterpret_cast<const WorkItem*>(w);
+    w += align_up(st->items[q].size() * sizeof(WorkItem), 256);
+  }
+  if (e != hipSuccess) {
+    delete st;
+    return hip_fail(e, "pmpd_stack_create copy");
+  }
+  // PMPD_STACK_SHAPE=1 selects the split-K shape (tuning aid); default is whole-K waves.
+  const char* env = std::getenv("PMPD_STACK_SHAPE");
+  st->shape = (env && env[0] == '1') ? 1 : 0;
+  *out = st;
+  return PMPD_OK;
+}
+
+void pmpd_stack_destroy(pmpd_stack_t* stack) { delete stack; }
+
+int32_t pmpd_decode_step(const pmpd_stack_t* stack, int32_t b, const void* x_base, float* y_base, void* stream) {
+  int32_t rc = check_bits(b, "pmpd_decode_step");
+  if (rc) return rc;
+  if (!stack || !x_base || !y_base) return fail(PMPD_EINVAL, "pmpd_decode_step: NULL argument");
+  if (reinterpret_cast<uintptr_t>(x_base) % 16) return fail(PMPD_EALIGN, "pmpd_decode_step: x_base not 16-byte aligned");
+  if (reinterpret_cast<uintptr_t>(y_base) % 4) return fail(PMPD_EALIGN, "pmpd_decode_step: y_base not 4-byte aligned");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = b == 4 ? launch_stack<4>(stack, x_base, y_base, s)
+                 : b == 3 ? launch_stack<3>(stack, x_base, y_base, s)
+                          : launch_stack<2>(stack, x_base, y_base, s);
+  if (e != hipSuccess) return hip_fail(e, "pmpd_decode_step launch");
+  return PMPD_OK;
+}
+
+int32_t pmpd_decode_run(const pmpd_stack_t* stack, const pmpd_schedule_t* schedule, int32_t step0, int32_t n_steps,
+                        const void* x_base, int64_t x_step_stride, float* y_base, int64_t y_step_stride, void* stream) {
+  if (!stack || !schedule || !x_base || !y_base) return fail(PMPD_EINVAL, "pmpd_decode_run: NULL argument");
+  if (step0 < 0 || n_steps < 0) return fail(PMPD_EINVAL, "pmpd_decode_run: negative step index or count");
+  if (x_step_stride < 0 || y_step_stride < 0 || x_step_stride % 8) return fail(PMPD_EALIGN, "pmpd_decode_run: strides must be non-negative and x_step_stride a multiple of 8");
+  // Validate every step's bit-width before the first launch.
+  for (int32_t k = 0; k < n_steps; ++k) {
+    int32_t b = 0;
+    int32_t rc = pmpd_schedule_bits(schedule, step0 + k, &b);
+    if (rc) return rc;
+    rc = check_bits(b, "pmpd_decode_run");
+    if (rc) return rc;
+  }
+  for (int32_t k = 0; k < n_steps; ++k) {
+    int32_t b = 0;
+    pmpd_schedule_bits(schedule, step0 + k, &b);
+    const _Float16* x = static_cast<const _Float16*>(x_base) + static_cast<int64_t>(k) * x_step_stride;
+    float* y = y_base + static_cast<int64_t>(k) * y_step_stride;
+    int32_t rc = pmpd_decode_step(stack, b, x, y, stream);
+    if (rc) return rc;
+  }
+  return PMPD_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,224 @@
+// Host side of the PMPD library: error reporting, argument checks, the storage format
+// (pack / unpack) and the precision-switching schedule.  Nothing here touches the GPU.
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <thread>
+#include <vector>
+
+#include "pmpd_common.hpp"
+
+namespace pmpd {
+
+static thread_local char g_err[512] = "";
+
+int32_t fail(int32_t status, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return status;
+}
+
+int32_t check_shape(int32_t out_f, int32_t in_f, int32_t group) {
+  if (group != kGroup) return fail(PMPD_EINVAL, "group_size must be %d (got %d)", kGroup, group);
+  if (out_f <= 0) return fail(PMPD_EINVAL, "out_features must be positive (got %d)", out_f);
+  if (in_f <= 0 || in_f % kGroup) return fail(PMPD_EINVAL, "in_features must be a positive multiple of %d (got %d)", kGroup, in_f);
+  return PMPD_OK;
+}
+
+int32_t check_layer(const pmpd_layer_t* L, int32_t b, const char* who) {
+  if (!L) return fail(PMPD_EINVAL, "%s: layer is NULL", who);
+  if (b < 1 || b > 4) return fail(PMPD_EINVAL, "%s: bit-width %d outside 1..4", who, b);
+  if (L->reserved != 0) return fail(PMPD_EINVAL, "%s: layer.reserved must be 0", who);
+  int32_t rc = check_shape(L->out_features, L->in_features, L->group_size);
+  if (rc) return rc;
+  for (int k = 0; k < b; ++k) {
+    if (!L->planes[k]) return fail(PMPD_EINVAL, "%s: planes[%d] is NULL but bit-width is %d", who, k, b);
+    if (reinterpret_cast<uintptr_t>(L->planes[k]) % 16) return fail(PMPD_EALIGN, "%s: planes[%d] not 16-byte aligned", who, k);
+  }
+  if (!L->scale_min) return fail(PMPD_EINVAL, "%s: scale_min is NULL", who);
+  if (reinterpret_cast<uintptr_t>(L->scale_min) % 4) return fail(PMPD_EALIGN, "%s: scale_min not 4-byte aligned", who);
+  return PMPD_OK;
+}
+
+// Bit of plane k that holds weight u (0..31) of a 32-weight word:
+// u = 2p + half, p = 4m + 2v + h  ->  (16 half + 8 v + 4 h + 3 - k + m) mod 32.
+static inline int bit_position(int k, int u) {
+  int half = u & 1, p = u >> 1;
+  int m = p >> 2, v = (p >> 1) & 1, h = p & 1;
+  return (16 * half + 8 * v + 4 * h + 3 - k + m) & 31;
+}
+
+}  // namespace pmpd
+
+using namespace pmpd;
+
+extern "C" {
+
+const char* pmpd_strerror(int32_t status) {
+  switch (status) {
+    case PMPD_OK: return "ok";
+    case PMPD_EINVAL: return "invalid argument";
+    case PMPD_EALIGN: return "misaligned buffer";
+    case PMPD_ESCHED: return "invalid precision-switching schedule";
+    case PMPD_EHIP: return "HIP runtime failure";
+    case PMPD_ESIZE: return "buffer too small";
+    default: return "unknown status";
+  }
+}
+
+const char* pmpd_last_error(void) { return g_err; }
+
+int32_t pmpd_packed_size(int32_t out_f, int32_t in_f, int32_t group, size_t* plane_bytes, size_t* sm_bytes) {
+  int32_t rc = check_shape(out_f, in_f, group);
+  if (rc) return rc;
+  if (!plane_bytes || !sm_bytes) return fail(PMPD_EINVAL, "pmpd_packed_size: output pointer is NULL");
+  int64_t rows = padded_rows(out_f);
+  *plane_bytes = static_cast<size_t>(rows) * static_cast<size_t>(in_f) / 8;
+  *sm_bytes = static_cast<size_t>(rows) * static_cast<size_t>(in_f / kGroup) * 4;
+  return PMPD_OK;
+}
+
+int32_t pmpd_pack(const uint8_t* q4, const uint16_t* scale, const uint16_t* minv, int32_t out_f, int32_t in_f,
+                  int32_t group, void* const planes[4], void* scale_min) {
+  int32_t rc = check_shape(out_f, in_f, group);
+  if (rc) return rc;
+  if (!q4 || !scale || !minv || !planes || !scale_min) return fail(PMPD_EINVAL, "pmpd_pack: NULL argument");
+  for (int k = 0; k < 4; ++k) {
+    if (!planes[k]) return fail(PMPD_EINVAL, "pmpd_pack: planes[%d] is NULL", k);
+    if (reinterpret_cast<uintptr_t>(planes[k]) % 4) return fail(PMPD_EALIGN, "pmpd_pack: planes[%d] not 4-byte aligned", k);
+  }
+  if (reinterpret_cast<uintptr_t>(scale_min) % 4) return fail(PMPD_EALIGN, "pmpd_pack: scale_min not 4-byte aligned");
+
+  const int64_t G = in_f / kGroup;
+  const int64_t n_tiles = padded_rows(out_f) / kTile;
+  uint32_t* pl[4];
+  for (int k = 0; k < 4; ++k) pl[k] = static_cast<uint32_t*>(planes[k]);
+  uint32_t* sm = static_cast<uint32_t*>(scale_min);
+
+  int pos[4][32];
+  for (int k = 0; k < 4; ++k)
+    for (int u = 0; u < 32; ++u) pos[k][u] = bit_position(k, u);
+
+  // Tiles are independent: split them over host threads.
+  unsigned hw = std::thread::hardware_concurrency();
+  int n_thr = static_cast<int>(std::min<int64_t>(std::max(1u, std::min(hw, 16u)), n_tiles));
+  std::vector<int> bad(n_thr, 0);
+  auto work = [&](int tid) {
+    for (int64_t T = tid; T < n_tiles; T += n_thr) {
+      for (int64_t g = 0; g < G; ++g) {
+        for (int l = 0; l < kTile; ++l) {
+          const int64_t r = T * kTile + l;
+          const int64_t base = ((T * G + g) * kTile + l);
+          uint32_t w[4][4] = {};
+          if (r < out_f) {
+            const uint8_t* src = q4 + r * static_cast<int64_t>(in_f) + g * kGroup;
+            for (int d = 0; d < 4; ++d)
+              for (int u = 0; u < 32; ++u) {
+                uint32_t code = src[d * 32 + u];
+                if (code > 15) { bad[tid] = 1; code &= 15; }
+                for (int k = 0; k < 4; ++k) w[k][d] |= ((code >> (3 - k)) & 1u) << pos[k][u];
+              }
+            sm[base] = static_cast<uint32_t>(scale[r * G + g]) | (static_cast<uint32_t>(minv[r * G + g]) << 16);
+          } else {
+            sm[base] = 0;
+          }
+          for (int k = 0; k < 4; ++k)
+            for (int d = 0; d < 4; ++d) pl[k][base * 4 + d] = w[k][d];
+        }
+      }
+    }
+  };
+  std::vector<std::thread> pool;
+  for (int t = 1; t < n_thr; ++t) pool.emplace_back(work, t);
+  work(0);
+  for (auto& t : pool) t.join();
+  for (int t = 0; t < n_thr; ++t)
+    if (bad[t]) return fail(PMPD_EINVAL, "pmpd_pack: a code is outside 0..15");
+  return PMPD_OK;
+}
+
+int32_t pmpd_unpack(const pmpd_layer_t* L, int32_t b, uint8_t* qb_out) {
+  int32_t rc = check_layer(L, b, "pmpd_unpack");
+  if (rc) return rc;
+  if (!qb_out) return fail(PMPD_EINVAL, "pmpd_unpack: qb_out is NULL");
+  const int64_t in_f = L->in_features, out_f = L->out_features, G = in_f / kGroup;
+  int pos[4][32];
+  for (int k = 0; k < 4; ++k)
+    for (int u = 0; u < 32; ++u) pos[k][u] = bit_position(k, u);
+  for (int64_t r = 0; r < out_f; ++r) {
+    const int64_t T = r / kTile, l = r % kTile;
+    for (int64_t g = 0; g < G; ++g) {
+      const int64_t base = ((T * G + g) * kTile + l) * 4;
+      for (int d = 0; d < 4; ++d)
+        for (int u = 0; u < 32; ++u) {
+          uint32_t code = 0;
+          for (int k = 0; k < b; ++k) {
+            uint32_t word = static_cast<const uint32_t*>(L->planes[k])[base + d];
+            code = (code << 1) | ((word >> pos[k][u]) & 1u);
+          }
+          qb_out[r * in_f + g * kGroup + d * 32 + u] = static_cast<uint8_t>(code);
+        }
+    }
+  }
+  return PMPD_OK;
+}
+
+// ------------------------------------------------------------------ schedule ----
+struct pmpd_schedule {
+  std::vector<int32_t> precisions;
+  std::vector<int32_t> st;
+  int32_t max_steps;
+};
+
+int32_t pmpd_schedule_create(const int32_t* precisions, const int32_t* st, int32_t n, int32_t max_steps,
+                             pmpd_schedule_t** out) {
+  if (!precisions || !st || !out) return fail(PMPD_EINVAL, "pmpd_schedule_create: NULL argument");
+  if (n < 1 || n > 16) return fail(PMPD_EINVAL, "pmpd_schedule_create: need 1..16 precisions (got %d)", n);
+  if (max_steps < 1) return fail(PMPD_EINVAL, "pmpd_schedule_create: max_steps must be positive");
+  for (int j = 0; j < n; ++j) {
+    if (precisions[j] < 1 || precisions[j] > 16) return fail(PMPD_EINVAL, "pmpd_schedule_create: precision %d out of range", precisions[j]);
+    if (j && precisions[j] >= precisions[j - 1]) return fail(PMPD_EINVAL, "pmpd_schedule_create: precisions must be strictly decreasing");
+  }
+  if (st[0] != 0) return fail(PMPD_ESCHED, "schedule: the first (highest) precision must start at step 0 (got %d)", st[0]);
+  for (int j = 0; j < n; ++j) {
+    if (st[j] < 0 || st[j] > max_steps) return fail(PMPD_ESCHED, "schedule: switch point %d outside [0, %d]", st[j], max_steps);
+    if (j && st[j] < st[j - 1]) return fail(PMPD_ESCHED, "schedule: precedence violated, %d-bit starts at %d before %d-bit at %d", precisions[j], st[j], precisions[j - 1], st[j - 1]);
+  }
+  auto* s = new pmpd_schedule;
+  s->precisions.assign(precisions, precisions + n);
+  s->st.assign(st, st + n);
+  s->max_steps = max_steps;
+  *out = s;
+  return PMPD_OK;
+}
+
+void pmpd_schedule_destroy(pmpd_schedule_t* s) { delete s; }
+
+int32_t pmpd_schedule_bits(const pmpd_schedule_t* s, int32_t step, int32_t* b_out) {
+  if (!s || !b_out) return fail(PMPD_EINVAL, "pmpd_schedule_bits: NULL argument");
+  if (step < 0) return fail(PMPD_EINVAL, "pmpd_schedule_bits: negative step");
+  // st is non-decreasing and precisions decreasing: the last reached entry is the lowest precision.
+  int32_t b = s->precisions[0];
+  for (size_t j = 1; j < s->st.size(); ++j)
+    if (s->st[j] <= step) b = s->precisions[j];
+  *b_out = b;
+  return PMPD_OK;
+}
+
+double pmpd_schedule_avg_bits(const pmpd_schedule_t* s, int32_t n_steps) {
+  if (!s || n_steps < 1) { fail(PMPD_EINVAL, "pmpd_schedule_avg_bits: bad argument"); return -1.0; }
+  // Segment lengths instead of a per-step loop: precision j is active on [st[j], st[j+1]),
+  // clipped to the first n_steps steps (st is non-decreasing, so no segment is negative).
+  const size_t n = s->st.size();
+  int64_t total = 0;
+  for (size_t j = 0; j < n; ++j) {
+    int64_t lo = std::min<int64_t>(s->st[j], n_steps);
+    int64_t hi = (j + 1 < n) ? std::min<int64_t>(s->st[j + 1], n_steps) : n_steps;
+    total += (hi - lo) * s->precisions[j];
+  }
+  return static_cast<double>(total) / static_cast<double>(n_steps);
+}
+
+}  // extern "C"

@@ -1,0 +1,243 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element,
+on the same seeded inputs.  Bars: pack/unpack bit-exact (checked on the CPU side);
+linear layers  ||y - y*||_2 / ||y*||_2 <= 1e-3  and  |y[r] - y*[r]| <= 2e-3 * sum_i |W[r][i]||x[i]|."""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+import pmpd_synth as synth
+
+pytestmark = pytest.mark.gpu
+
+REL_L2 = 1e-3
+ABS_FACTOR = 2e-3
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def assert_parity(y_gpu: np.ndarray, y_ref: np.ndarray, budget: np.ndarray, what: str):
+    y_gpu = np.asarray(y_gpu, dtype=np.float64).reshape(y_ref.shape)
+    assert np.all(np.isfinite(y_gpu)), f"{what}: non-finite output"
+    err = np.abs(y_gpu - y_ref)
+    bound = ABS_FACTOR * budget
+    worst = np.argmax(err - bound)
+    assert np.all(err <= bound), (
+        f"{what}: |dy|={err.flat[worst]:.3e} > {bound.flat[worst]:.3e} at flat index {worst}")
+    denom = np.linalg.norm(y_ref)
+    if denom > 0:
+        rel = np.linalg.norm(y_gpu - y_ref) / denom
+        assert rel <= REL_L2, f"{what}: relative L2 error {rel:.3e}"
+    else:
+        assert np.all(y_gpu == 0)
+
+
+@pytest.fixture(scope="module")
+def pmpd():
+    import torch
+
+    assert torch.cuda.is_available()
+    import paper_2410_13461_amd as lib
+
+    return lib
+
+
+def _device_layer(pmpd, q4, s, a):
+    planes, sm = pmpd.pack(q4, s, a)
+    return pmpd.upload_layer(planes, sm, q4.shape[0], q4.shape[1])
+
+
+def _run_gemv(pmpd, layer, b, x_np):
+    import torch
+
+    x = torch.from_numpy(x_np).cuda()
+    y = pmpd.gemv(layer, b, x)
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+# shapes: several row tiles, ragged tails (out not a multiple of 64), K long enough for every
+# split-K launch shape, and the non-power-of-two rows of the Llama MLPs (11008 = 86 groups).
+SHAPES = [(64, 128), (100, 384), (257, 1408), (512, 4096), (200, 11008), (4096, 256), (130, 2048)]
+
+
+@pytest.mark.parametrize("b", [4, 3, 2])
+@pytest.mark.parametrize("out_f,in_f", SHAPES)
+def test_gemv_matches_oracle(pmpd, b, out_f, in_f):
+    _say(f"[gemv] out={out_f} in={in_f} b={b}")
+    q4, s, a = synth.draw_weights(100, out_f, in_f, out_f, in_f, random_min=True)
+    x = synth.draw_x(100, 0, out_f, in_f, in_f)[0]
+    layer = _device_layer(pmpd, q4, s, a)
+    y = _run_gemv(pmpd, layer, b, x)
+    y_ref, t = oracle.linear(q4, s, a, b, x)
+    assert_parity(y, y_ref[0], t[0], f"gemv {out_f}x{in_f} b={b}")
+
+
+@pytest.mark.parametrize("b", [4, 3, 2])
+def test_gemv_config0_full_layer(pmpd, b):
+    """The 4096x4096 single-layer workload, seed 0, a = -8 s."""
+    _say(f"[gemv cfg0] b={b}")
+    q4, s, a = synth.draw_weights(0, 0, 0, 4096, 4096)
+    x = synth.draw_x(0, 0, 0, 0, 4096)[0]
+    layer = _device_layer(pmpd, q4, s, a)
+    y = _run_gemv(pmpd, layer, b, x)
+    y_ref, t = oracle.linear(q4, s, a, b, x)
+    assert_parity(y, y_ref[0], t[0], f"cfg0 b={b}")
+    # same launch twice: bit-identical (fixed reduction order, no atomics)
+    y2 = _run_gemv(pmpd, layer, b, x)
+    assert np.array_equal(y, y2)
+
+
+@pytest.mark.parametrize("b", [4, 3, 2])
+def test_gemv_ignores_planes_below_b(pmpd, b):
+    """Planes b..3 live in separately allocated, poisoned buffers (or are absent)."""
+    import torch
+
+    _say(f"[gemv prefix] b={b}")
+    out_f, in_f = 192, 1024
+    q4, s, a = synth.draw_weights(7, 1, 1, out_f, in_f, random_min=True)
+    x = synth.draw_x(7, 0, 1, 1, in_f)[0]
+    planes, sm = pmpd.pack(q4, s, a)
+    y_ref, t = oracle.linear(q4, s, a, b, x)
+    rng = np.random.default_rng(3)
+    poisoned = [p if k < b else rng.integers(0, 2 ** 32, size=p.size, dtype=np.uint32) for k, p in enumerate(planes)]
+    y_poison = _run_gemv(pmpd, pmpd.upload_layer(poisoned, sm, out_f, in_f), b, x)
+    absent = [p if k < b else None for k, p in enumerate(planes)]
+    y_absent = _run_gemv(pmpd, pmpd.upload_layer(absent, sm, out_f, in_f), b, x)
+    y_clean = _run_gemv(pmpd, pmpd.upload_layer(planes, sm, out_f, in_f), b, x)
+    assert np.array_equal(y_poison, y_clean)
+    assert np.array_equal(y_absent, y_clean)
+    assert_parity(y_clean, y_ref[0], t[0], f"prefix b={b}")
+
+
+@pytest.mark.parametrize("b", [4, 3, 2])
+def test_gemv_adversarial_inputs(pmpd, b):
+    _say(f"[gemv adversarial] b={b}")
+    out_f, in_f = 128, 1024
+    rng = np.random.default_rng(11)
+    q_rand, s, a = synth.draw_weights(8, 2, 2, out_f, in_f, random_min=True)
+    x_rand = synth.draw_x(8, 0, 2, 2, in_f)[0]
+    G = in_f // 128
+    cases = {}
+    # codes: all zero, all fifteen, one plane only, alternating
+    for name, q in (("zeros", np.zeros_like(q_rand)), ("fifteens", np.full_like(q_rand, 15)),
+                    ("msb-only", np.full_like(q_rand, 8)), ("lsb-only", np.full_like(q_rand, 1)),
+                    ("alternating", (np.arange(in_f, dtype=np.uint8) % 2 * 15)[None, :].repeat(out_f, 0))):
+        cases["codes-" + name] = (q, s, a, x_rand)
+    # scales at the ends of their range, minima far from -8 s
+    s_ext = np.where(rng.random((out_f, G)) < 0.5, 1e-3, 1e-2).astype(np.float16)
+    cases["scale-extremes"] = (q_rand, s_ext, a, x_rand)
+    a_zero = np.zeros_like(a)
+    cases["min-zero"] = (q_rand, s, a_zero, x_rand)
+    # activations: zeros, ones, one-hot, one huge entry, tiny entries, single sign
+    x_hot = np.zeros(in_f, dtype=np.float16); x_hot[517] = 1
+    x_huge = x_rand.copy(); x_huge[300] = np.float16(30000.0)
+    cases["x-zero"] = (q_rand, s, a, np.zeros(in_f, dtype=np.float16))
+    cases["x-ones"] = (q_rand, s, a, np.ones(in_f, dtype=np.float16))
+    cases["x-one-hot"] = (q_rand, s, a, x_hot)
+    cases["x-huge-entry"] = (q_rand, s, a, x_huge)
+    cases["x-tiny"] = (q_rand, s, a, (x_rand.astype(np.float32) * 1e-4).astype(np.float16))
+    cases["x-positive"] = (q_rand, s, a, np.abs(x_rand))
+    for name, (q, sv, av, xv) in cases.items():
+        layer = _device_layer(pmpd, q, sv, av)
+        y = _run_gemv(pmpd, layer, b, xv)
+        y_ref, t = oracle.linear(q, sv, av, b, xv)
+        assert_parity(y, y_ref[0], t[0], f"{name} b={b}")
+    # one-hot activations must return the dequantised column exactly (one weight, no rounding)
+    W = oracle.dequant(q_rand, s, a, b)
+    y = _run_gemv(pmpd, _device_layer(pmpd, q_rand, s, a), b, x_hot)
+    assert np.allclose(y, W[:, 517], rtol=2e-6, atol=0)
+
+
+@pytest.mark.parametrize("b", [4, 3, 2])
+@pytest.mark.parametrize("m", [1, 2, 3, 4, 8])
+def test_gemm_skinny_matches_oracle(pmpd, b, m):
+    import torch
+
+    _say(f"[gemm] m={m} b={b}")
+    for (out_f, in_f) in ((200, 2048), (128, 5632)):
+        q4, s, a = synth.draw_weights(9, out_f, m, out_f, in_f, random_min=True)
+        X = synth.draw_x(9, 0, out_f, m, in_f, m=m)
+        layer = _device_layer(pmpd, q4, s, a)
+        Y = pmpd.gemm(layer, b, torch.from_numpy(X).cuda())
+        torch.cuda.synchronize()
+        y_ref, t = oracle.linear(q4, s, a, b, X)
+        assert_parity(Y.cpu().numpy(), y_ref, t, f"gemm {out_f}x{in_f} m={m} b={b}")
+
+
+def _small_stack(pmpd, seed=5):
+    """A two-block stack with Llama-like proportions (hidden 256, intermediate 640, ragged)."""
+    shape = synth.StackShape("tiny", 2, 256, 640)
+    layers, raw = [], []
+    for li, (blk, pi, nm, o, i) in enumerate(shape.layers()):
+        q4, s, a = synth.draw_weights(seed, blk, pi, o, i, random_min=(pi % 2 == 1))
+        raw.append((q4, s, a))
+        layers.append(_device_layer(pmpd, q4, s, a))
+    return shape, layers, raw
+
+
+@pytest.mark.parametrize("b", [4, 3, 2])
+def test_decode_step_matches_oracle_and_single_layer_calls(pmpd, b):
+    import torch
+
+    _say(f"[decode_step] b={b}")
+    shape, layers, raw = _small_stack(pmpd)
+    stack = pmpd.Stack(layers)
+    xs = [synth.draw_x(5, 0, blk, pi, i)[0] for (blk, pi, nm, o, i) in shape.layers()]
+    x = torch.from_numpy(np.concatenate(xs)).cuda()
+    y = torch.full((stack.y_elems,), float("nan"), dtype=torch.float32, device="cuda")
+    pmpd.decode_step(stack, b, x, y)
+    torch.cuda.synchronize()
+    y = y.cpu().numpy()
+    for li, (q4, s, a) in enumerate(raw):
+        o = stack.y_offsets[li]
+        y_ref, t = oracle.linear(q4, s, a, b, xs[li])
+        assert_parity(y[o:o + q4.shape[0]], y_ref[0], t[0], f"decode_step layer {li} b={b}")
+    stack.close()
+
+
+def test_decode_run_follows_the_schedule(pmpd):
+    import torch
+
+    _say("[decode_run]")
+    shape, layers, raw = _small_stack(pmpd, seed=6)
+    stack = pmpd.Stack(layers)
+    P, st, n_steps = (4, 3, 2), (0, 2, 5), 8
+    sch = pmpd.Schedule(P, st, n_steps)
+    xs = np.stack([np.concatenate([synth.draw_x(6, k, blk, pi, i)[0] for (blk, pi, nm, o, i) in shape.layers()])
+                   for k in range(n_steps)])
+    x = torch.from_numpy(xs).cuda()
+    y = torch.zeros((n_steps, stack.y_elems), dtype=torch.float32, device="cuda")
+    pmpd.decode_run(stack, sch, 0, n_steps, x, stack.x_elems, y, stack.y_elems)
+    torch.cuda.synchronize()
+    y = y.cpu().numpy()
+    for k in range(n_steps):
+        b = oracle.schedule_bits(P, st, k)
+        assert sch.bits(k) == b
+        for li, (q4, s, a) in enumerate(raw):
+            xo, yo = stack.x_offsets[li], stack.y_offsets[li]
+            y_ref, t = oracle.linear(q4, s, a, b, xs[k, xo:xo + q4.shape[1]])
+            assert_parity(y[k, yo:yo + q4.shape[0]], y_ref[0], t[0], f"decode_run step {k} layer {li} b={b}")
+    # a run that starts in the middle picks up the schedule at that step
+    y2 = torch.zeros((3, stack.y_elems), dtype=torch.float32, device="cuda")
+    pmpd.decode_run(stack, sch, 4, 3, x[4:], stack.x_elems, y2, stack.y_elems)
+    torch.cuda.synchronize()
+    assert np.array_equal(y2.cpu().numpy(), y[4:7])
+    stack.close()
+
+
+def test_gpu_error_paths_do_not_launch(pmpd):
+    import torch
+
+    q4, s, a = synth.draw_weights(1, 0, 0, 64, 128)
+    layer = _device_layer(pmpd, q4, s, a)
+    x = torch.zeros(128, dtype=torch.float16, device="cuda")
+    with pytest.raises(pmpd.PMPDError):
+        pmpd.gemv(layer, 5, x)
+    with pytest.raises(pmpd.PMPDError):
+        pmpd.gemv(layer, 4, x[1:])  # misaligned view
+    torch.cuda.synchronize()

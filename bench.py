@@ -1,0 +1,178 @@
+#!/usr/bin/env python3
+"""Benchmark of the PMPD decode linear-layer path on one MI355X.
+
+Workload: the Llama-7B-shaped decode step (32 blocks x {q,k,v,o 4096x4096, up/gate 11008x4096,
+down 4096x11008}, batch 1, one token), seeded synthetic weights and activations, run at
+b = 4, 3 and 2.  A "step" is one token decoded at each of the three bit-widths (three launches of
+the one-launch decode step, fresh activations per step).  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
+
+
+def cpu_baseline(shape, seed, bits, budget_s=20.0):
+    """Time the CPU oracle (as it stands) on a bounded sample: rows of block 0's seven projections."""
+    import numpy as np
+
+    import oracle
+    import pmpd_synth as synth
+
+    threads = oracle.threads()
+    rows_per_layer = 256
+    per_b = {}
+    sample_weights = 0
+    t_total = 0.0
+    layers = []
+    for pi, (nm, o, i) in enumerate(shape.proj_shapes()):
+        q4, s, a = synth.draw_weights(seed, 0, pi, rows_per_layer, i)
+        planes, sa = oracle.pack(q4, s, a)
+        x = synth.draw_x(seed, 0, 0, pi, i)[0]
+        layers.append((planes, sa, rows_per_layer, i, x))
+        sample_weights += rows_per_layer * i
+    for b in bits:
+        t0 = time.perf_counter()
+        for (planes, sa, o, i, x) in layers:
+            oracle.linear_packed(planes, sa, b, o, i, x)
+        dt = time.perf_counter() - t0
+        t_total += dt
+        per_b[b] = dt / sample_weights  # seconds per weight
+        if t_total > budget_s:
+            break
+    n_w = shape.n_weights()
+    us = {b: per_b[b] * n_w * 1e6 for b in per_b}
+    return {
+        "value": sum(us.values()) / len(us),
+        "unit": "us/token",
+        "cores": threads,
+        "kind": "oracle",
+        "per_bits_us_per_token": {str(b): us[b] for b in us},
+        "sample": f"{rows_per_layer} rows of each of block 0's 7 projections ({sample_weights} weights) per bit-width, "
+                  f"scaled by weight count to the {n_w}-weight stack",
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--blocks", type=int, default=None, help="debug: fewer blocks (result is then not the named workload)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import pmpd_synth as synth
+    import paper_2410_13461_amd as pmpd
+    from paper_2410_13461_amd import workload
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    torch.cuda.set_device(0)
+    shape = synth.LLAMA_7B
+    bits = (4, 3, 2)
+    K, W = args.steps, args.warmup
+
+    t0 = time.time()
+    stack, layers, _ = workload.build_stack(shape, seed=args.seed, n_blocks=args.blocks, verbose=True)
+    print(f"stack ready: {len(layers)} layers in {time.time() - t0:.0f} s", file=sys.stderr, flush=True)
+
+    # activations of every step already on the device
+    xs = np.stack([workload.draw_step_activations(shape, args.seed, k, n_blocks=args.blocks) for k in range(W + K)])
+    x_dev = torch.from_numpy(xs).cuda()
+    y_dev = torch.zeros(stack.y_elems, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    for k in range(W):
+        for b in bits:
+            pmpd.decode_step(stack, b, x_dev[k], y_dev, stream)
+    torch.cuda.synchronize()
+
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(bits) + 1)] for _ in range(K)]
+    torch.cuda.synchronize()
+    t_wall0 = time.perf_counter()
+    for k in range(K):
+        ev[k][0].record(stream)
+        for j, b in enumerate(bits):
+            pmpd.decode_step(stack, b, x_dev[W + k], y_dev, stream)
+            ev[k][j + 1].record(stream)
+    torch.cuda.synchronize()
+    t_wall = time.perf_counter() - t_wall0
+
+    per_b_ms = {b: [] for b in bits}
+    for k in range(K):
+        for j, b in enumerate(bits):
+            per_b_ms[b].append(ev[k][j].elapsed_time(ev[k][j + 1]))
+    total_ms = ev[0][0].elapsed_time(ev[K - 1][len(bits)])
+
+    per_bits = {}
+    for b in bits:
+        ms = float(np.mean(per_b_ms[b]))
+        nbytes = stack.bytes_at(b)
+        per_bits[str(b)] = {
+            "us_per_token": ms * 1e3,
+            "min_us": float(np.min(per_b_ms[b])) * 1e3,
+            "algorithmic_bytes": nbytes,
+            "GBps": nbytes / (ms * 1e-3) / 1e9,
+            "frac_of_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        }
+    us_per_token = total_ms * 1e3 / (K * len(bits))
+
+    dom = per_bits["4"]
+    out = {
+        "metric": "decode linear-layer us/token (mean over b=4,3,2; per-bit figures in per_bits), batch 1",
+        "value": us_per_token,
+        "unit": "us/token",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": total_ms / K,
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u4-bitplane weights x f16 activations, f32 accumulate",
+        "data": "synthetic",
+        "config": {
+            "workload": "Llama-7B-shaped decode step: 32 blocks x 7 projections (224 linear layers, 6.476e9 weights), "
+                        "batch 1, one token per launch, run at b=4,3,2" if args.blocks is None else f"DEBUG {args.blocks} blocks",
+            "group_size": 128,
+            "step": "one token at each of b=4,3,2 (3 launches)",
+            "wall_ms_per_step_incl_host": t_wall * 1e3 / K,
+        },
+        "per_bits": per_bits,
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "pmpd_gemv_stack_kernel<B=4> (one launch = one b=4 decode step)",
+            "achieved": dom["GBps"],
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": dom["GBps"] / HBM_PEAK_GBS,
+            "traffic": None,
+        },
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(shape, args.seed, bits)
+    stack.close()
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

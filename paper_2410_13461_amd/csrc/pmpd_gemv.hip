@@ -34,7 +34,7 @@
 #define PMPD_PF 1  // groups of plane words kept in flight ahead of the one being consumed
 #endif
 #ifndef PMPD_USE_SCHED_BARRIER
-#define PMPD_USE_SCHED_BARRIER 1
+#define PMPD_USE_SCHED_BARRIER 0  // pinning the schedule made the register allocator spill
 #endif
 #if PMPD_USE_SCHED_BARRIER
 #define PMPD_SCHED_BARRIER() __builtin_amdgcn_sched_barrier(0)
@@ -390,6 +390,7 @@ template <int B>
 static hipError_t launch_layer_b(const LayerDesc& d, const void* x, int m, float* y, hipStream_t s) {
   switch (m) {
     case 1: return launch_layer_bm<B, 1>(d, x, y, s);
+#ifndef PMPD_BUILD_BATCH1_ONLY  // (working builds that only time the batch-1 kernels compile faster)
     case 2: return launch_layer_bm<B, 2>(d, x, y, s);
     case 3: return launch_layer_bm<B, 3>(d, x, y, s);
     case 4: return launch_layer_bm<B, 4>(d, x, y, s);
@@ -397,6 +398,9 @@ static hipError_t launch_layer_b(const LayerDesc& d, const void* x, int m, float
     case 6: return launch_layer_bm<B, 6>(d, x, y, s);
     case 7: return launch_layer_bm<B, 7>(d, x, y, s);
     default: return launch_layer_bm<B, 8>(d, x, y, s);
+#else
+    default: return hipErrorNotSupported;
+#endif
   }
 }
 

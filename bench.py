@@ -62,6 +62,19 @@ def cpu_baseline(shape, seed, bits, budget_s=20.0):
     }
 
 
+def measured_traffic(b: int):
+    """HBM bytes per launch from the committed rocprofv3 counter summary (separate --pmc runs), or None."""
+    path = os.path.join(ROOT, "profiles", "decode_step_7b_stack_kernel.txt")
+    try:
+        for line in open(path):
+            tok = line.split()
+            if len(tok) >= 3 and tok[0] == "traffic_bytes" and tok[1] == f"b={b}":
+                return float(tok[2])
+    except OSError:
+        pass
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -164,7 +177,7 @@ def main() -> int:
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": dom["GBps"] / HBM_PEAK_GBS,
-            "traffic": None,
+            "traffic": measured_traffic(4) if args.blocks is None else None,
         },
     }
     if not args.no_cpu_baseline:

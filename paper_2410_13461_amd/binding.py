@@ -180,9 +180,9 @@ class PackedLayer:
         return self._struct
 
     def bytes_at(self, b: int) -> int:
-        """Bytes a b-bit pass streams: b planes plus the scale/min words."""
+        """Algorithmic bytes of a b-bit pass: b planes, the scale/min words, x once, y once."""
         pb, sb = packed_size(self.out_features, self.in_features)
-        return b * pb + sb
+        return b * pb + sb + 2 * self.in_features + 4 * self.out_features
 
 
 def upload_layer(planes, scale_min, out_features: int, in_features: int, device="cuda") -> PackedLayer:

@@ -255,6 +255,9 @@ __device__ __forceinline__ void run_tiles(const LayerDesc& L, int tile0, const _
     __syncthreads();
     const int g0 = c0 + cn * ks / SPLITK, g1 = c0 + cn * (ks + 1) / SPLITK;
     if (active && g0 < g1) {
+      // Weights are read exactly once per pass: nontemporal loads keep them from displacing
+      // x in the caches (measured: the same loop without arithmetic streams 6.7 TB/s with
+      // them, 5.8 TB/s without).
       // Register ring of PF groups in flight.  Loads are unconditional with the group index
       // clamped to the last one of the range, so the loop body is branch-free for the loads
       // and the ring needs no register copies; the few clamped reloads hit the cache.
@@ -264,7 +267,7 @@ __device__ __forceinline__ void run_tiles(const LayerDesc& L, int tile0, const _
       for (int j = 0; j < PF; ++j) {
         const int gl = (g0 + j < g1) ? (g0 + j) : (g1 - 1);
 #pragma unroll
-        for (int k = 0; k < B; ++k) nb[j][k] = pp[k][gl * 64];
+        for (int k = 0; k < B; ++k) nb[j][k] = __builtin_nontemporal_load(&pp[k][gl * 64]);
         nsa[j] = sp[gl * 64];
       }
       for (int g = g0; g < g1; g += PF) {
@@ -277,7 +280,7 @@ __device__ __forceinline__ void run_tiles(const LayerDesc& L, int tile0, const _
           const uint32_t csa = nsa[j];
           const int gl = (gc + PF < g1) ? (gc + PF) : (g1 - 1);
 #pragma unroll
-          for (int k = 0; k < B; ++k) nb[j][k] = pp[k][gl * 64];
+          for (int k = 0; k < B; ++k) nb[j][k] = __builtin_nontemporal_load(&pp[k][gl * 64]);
           nsa[j] = sp[gl * 64];
           if (gc < g1) {
             float accL[M], accH[M];

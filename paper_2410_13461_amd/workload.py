@@ -4,6 +4,7 @@ Generation (numpy, seeded), packing (native host pack) and upload only: no oracl
 """
 from __future__ import annotations
 
+import sys
 import time
 from concurrent.futures import ThreadPoolExecutor
 from typing import List, Optional, Tuple
@@ -42,7 +43,7 @@ def build_stack(shape: synth.StackShape, seed: int = 0, n_blocks: Optional[int] 
             if host is not None:
                 kept[(blk, pi)] = host
             if verbose and (n + 1) % 28 == 0:
-                print(f"  built {n + 1}/{len(todo)} layers ({time.time() - t0:.0f} s)", flush=True)
+                print(f"  built {n + 1}/{len(todo)} layers ({time.time() - t0:.0f} s)", file=sys.stderr, flush=True)
     stack = binding.Stack(layers)
     return stack, layers, kept
 

@@ -78,8 +78,8 @@ def measured_traffic(b: int):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--blocks", type=int, default=None, help="debug: fewer blocks (result is then not the named workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
@@ -113,6 +113,13 @@ def main() -> int:
     y_dev = torch.zeros(stack.y_elems, dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
 
+    # The GPU idles at a few hundred MHz and needs some tenths of a second of work before its
+    # clocks settle: run untimed steps for that long first, then the W warm-up steps proper.
+    t_ramp = time.perf_counter()
+    while time.perf_counter() - t_ramp < 0.5:
+        for b in bits:
+            pmpd.decode_step(stack, b, x_dev[0], y_dev, stream)
+        torch.cuda.synchronize()
     for k in range(W):
         for b in bits:
             pmpd.decode_step(stack, b, x_dev[k], y_dev, stream)

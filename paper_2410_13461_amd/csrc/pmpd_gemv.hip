@@ -24,6 +24,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <vector>
@@ -32,6 +33,12 @@
 
 #ifndef PMPD_PF
 #define PMPD_PF 1  // groups of plane words kept in flight ahead of the one being consumed
+#endif
+#ifndef PMPD_X_SCALAR
+#define PMPD_X_SCALAR 1  // batch-1 dot2 kernels read x through scalar loads (1) or LDS (0)
+#endif
+#ifndef PMPD_DEFAULT_MFMA
+#define PMPD_DEFAULT_MFMA 0  // which multiply-accumulate path runs when PMPD_MAC is not set
 #endif
 #ifndef PMPD_USE_SCHED_BARRIER
 #define PMPD_USE_SCHED_BARRIER 0  // pinning the schedule made the register allocator spill
@@ -50,24 +57,51 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // naming the global one lets the compiler emit global_load (vmcnt only) instead of flat_load.
 typedef const __attribute__((address_space(1))) u32x4* global_u32x4_ptr;
 typedef const __attribute__((address_space(1))) uint32_t* global_u32_ptr;
+// Wave-uniform reads of x go through the scalar data cache into SGPRs (s_load_dwordx16): the
+// constant address space tells the compiler that the memory does not change during the kernel.
+typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
+typedef const __attribute__((address_space(4))) u32x16* const_u32x16_ptr;
 
 __device__ __forceinline__ float dot2(uint32_t w, uint32_t x, float acc) {
   return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, w), __builtin_bit_cast(half2_t, x), acc, false);
 }
 
-// (a & mask) | (b & ~mask) in one VALU op.
-__device__ __forceinline__ uint32_t bfi(uint32_t mask, uint32_t a, uint32_t b) {
-  uint32_t d;
-  asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(d) : "s"(mask), "v"(a), "v"(b));
-  return d;
+// Bit-select and mask-or use compiler-visible operations; the masks are made opaque to the optimiser
+// (an empty asm that pins them in SGPRs) so that it cannot fold them into distributed ANDs and
+// instead selects one 3-input VALU op each (v_bitop3_b32, v_and_or_b32).  No instruction is
+// emitted through inline asm, so the compiler's hazard handling sees every op.
+__device__ __forceinline__ uint32_t opaque_sgpr(uint32_t v) {
+  asm volatile("" : "+s"(v));
+  return v;
 }
 
-// (a & mask) | c in one VALU op.
-__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t c) {
-  uint32_t d;
-  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "s"(mask), "v"(c));
-  return d;
+// (a & mask) | (b & ~mask): one v_bitop3_b32 (gfx950's 3-input boolean op).  Truth table index is
+// (a << 2) | (b << 1) | mask, so "mask ? a : b" is 0b11100100.
+__device__ __forceinline__ uint32_t bfi(uint32_t mask, uint32_t a, uint32_t b) {
+  return __builtin_amdgcn_bitop3_b32(a, b, mask, 0xE4);
 }
+
+// (a & mask) | c
+__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t c) { return (a & mask) | c; }
+
+// Constants of the unpack, held in registers for the whole kernel.
+template <int B>
+struct UnpackConsts {
+  uint32_t slot[4];   // bit positions congruent to j mod 4
+  uint32_t slot2[4];  // slot[j] | slot[j-1]
+  uint32_t maskL, maskH, magic;
+  __device__ __forceinline__ UnpackConsts() {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) slot[j] = opaque_sgpr(0x11111111u << j);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) slot2[j] = opaque_sgpr((0x11111111u << j) | (0x11111111u << ((j + 3) & 3)));
+    constexpr uint32_t keep = (0xFu << (4 - B)) & 0xFu;  // top B bits of a 4-bit field
+    maskL = opaque_sgpr(keep * 0x00010001u);
+    maskH = opaque_sgpr(keep * 0x00100010u);
+    magic = 0x64006400u;  // fp16 pair (1024, 1024)
+    asm volatile("" : "+v"(magic));
+  }
+};
 
 __device__ __forceinline__ uint32_t word_of(const u32x4& v, int d) {
   return d == 0 ? v.x : d == 1 ? v.y : d == 2 ? v.z : v.w;
@@ -77,22 +111,19 @@ __device__ __forceinline__ float half_bits_to_float(uint32_t bits16) {
   return static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(bits16)));
 }
 
-// Sub-slot masks: bit positions congruent to j mod 4.
-__host__ __device__ constexpr uint32_t slot_mask(int j) { return 0x11111111u << (j & 3); }
-
 // Merge the B plane words of one 32-weight word into the word whose fields (rotated by m)
 // are the codes of pairs 4m .. 4m+3.  Plane k sits in sub-slot (3 - k + m) mod 4.
 template <int B>
-__device__ __forceinline__ uint32_t merge_planes(const uint32_t (&p)[B], int m) {
+__device__ __forceinline__ uint32_t merge_planes(const UnpackConsts<B>& uc, const uint32_t (&p)[B], int m) {
   if constexpr (B == 4) {
-    uint32_t hi = bfi(slot_mask(3 + m), p[0], p[1]);
-    uint32_t lo = bfi(slot_mask(1 + m), p[2], p[3]);
-    return bfi(slot_mask(3 + m) | slot_mask(2 + m), hi, lo);
+    uint32_t hi = bfi(uc.slot[(3 + m) & 3], p[0], p[1]);
+    uint32_t lo = bfi(uc.slot[(1 + m) & 3], p[2], p[3]);
+    return bfi(uc.slot2[(3 + m) & 3], hi, lo);
   } else if constexpr (B == 3) {
-    uint32_t lo = bfi(slot_mask(2 + m), p[1], p[2]);
-    return bfi(slot_mask(3 + m), p[0], lo);
+    uint32_t lo = bfi(uc.slot[(2 + m) & 3], p[1], p[2]);
+    return bfi(uc.slot[(3 + m) & 3], p[0], lo);
   } else {
-    return bfi(slot_mask(3 + m), p[0], p[1]);
+    return bfi(uc.slot[(3 + m) & 3], p[0], p[1]);
   }
 }
 
@@ -100,13 +131,10 @@ __device__ __forceinline__ uint32_t merge_planes(const uint32_t (&p)[B], int m) 
 //   pl[k]: the lane's 16 bytes of plane k;  xs: the group's 16 uint4 of x in LDS for vector 0,
 //   vector j lies xstride uint4 further.  The unpack runs once, the dot products M times.
 template <int B, int M>
-__device__ __forceinline__ void mac_group(const u32x4 (&pl)[B], const uint4* __restrict__ xs, int xstride,
-                                          float (&accL)[M], float (&accH)[M]) {
-  constexpr uint32_t kKeep = (0xFu << (4 - B)) & 0xFu;  // top B bits of a 4-bit field
-  const uint32_t maskL = kKeep * 0x00010001u;
-  const uint32_t maskH = maskL << 4;
-  uint32_t magic = 0x64006400u;  // fp16 pair (1024, 1024)
-  asm volatile("" : "+v"(magic));
+__device__ __forceinline__ void mac_group(const UnpackConsts<B>& uc, const u32x4 (&pl)[B],
+                                          const uint4* __restrict__ xs, int xstride, float (&accL)[M],
+                                          float (&accH)[M]) {
+  const uint32_t maskL = uc.maskL, maskH = uc.maskH, magic = uc.magic;
   float l0[M], l1[M], h0[M], h1[M];
 #pragma unroll
   for (int j = 0; j < M; ++j) l0[j] = l1[j] = h0[j] = h1[j] = 0.f;
@@ -129,7 +157,7 @@ __device__ __forceinline__ void mac_group(const u32x4 (&pl)[B], const uint4* __r
       for (int k = 0; k < B; ++k) p[k] = word_of(pl[k], d);
 #pragma unroll
       for (int m = 0; m < 4; ++m) {
-        uint32_t u = merge_planes<B>(p, m);
+        uint32_t u = merge_planes<B>(uc, p, m);
         uint32_t w = (m == 0) ? u : __builtin_amdgcn_alignbit(u, u, m);
         uint32_t w8 = w >> 8;
         l0[0] = dot2(and_or(w, maskL, magic), xc[m].x, l0[0]);
@@ -154,7 +182,7 @@ __device__ __forceinline__ void mac_group(const u32x4 (&pl)[B], const uint4* __r
         uint4 xq[M];
 #pragma unroll
         for (int j = 0; j < M; ++j) xq[j] = xs[j * xstride + d * 4 + m];
-        uint32_t u = merge_planes<B>(p, m);
+        uint32_t u = merge_planes<B>(uc, p, m);
         uint32_t w = (m == 0) ? u : __builtin_amdgcn_alignbit(u, u, m);
         uint32_t w8 = w >> 8;
         const uint32_t r0 = and_or(w, maskL, magic), r1 = and_or(w, maskH, magic);
@@ -175,6 +203,36 @@ __device__ __forceinline__ void mac_group(const u32x4 (&pl)[B], const uint4* __r
     accL[j] = l0[j] + l1[j];
     accH[j] = h0[j] + h1[j];
   }
+}
+
+// Same as mac_group<B, 1>, but the activations come from global memory through scalar loads:
+// every lane of the wave needs the same 16 dwords of x per 32-column word, so they are SGPR
+// operands of v_dot2_f32_f16 and cost neither LDS bandwidth nor vector registers.
+//   xg: the group's 4 x 16 dwords of x (fp16 pairs in natural column order).
+template <int B>
+__device__ __forceinline__ void mac_group_sx(const UnpackConsts<B>& uc, const u32x4 (&pl)[B], const_u32x16_ptr xg,
+                                             float& accL, float& accH) {
+  const uint32_t maskL = uc.maskL, maskH = uc.maskH, magic = uc.magic;
+  float l0 = 0.f, l1 = 0.f, h0 = 0.f, h1 = 0.f;
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    const u32x16 xv = xg[d];
+    uint32_t p[B];
+#pragma unroll
+    for (int k = 0; k < B; ++k) p[k] = word_of(pl[k], d);
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+      uint32_t u = merge_planes<B>(uc, p, m);
+      uint32_t w = (m == 0) ? u : __builtin_amdgcn_alignbit(u, u, m);
+      uint32_t w8 = w >> 8;
+      l0 = dot2(and_or(w, maskL, magic), xv[4 * m + 0], l0);
+      h0 = dot2(and_or(w, maskH, magic), xv[4 * m + 1], h0);
+      l1 = dot2(and_or(w8, maskL, magic), xv[4 * m + 2], l1);
+      h1 = dot2(and_or(w8, maskH, magic), xv[4 * m + 3], h1);
+    }
+  }
+  accL = l0 + l1;
+  accH = h0 + h1;
 }
 
 // LDS image of one K-chunk of the activations: for each of the M vectors `cg` groups of x as
@@ -223,10 +281,11 @@ __device__ __forceinline__ void stage_activations(const _Float16* __restrict__ x
 // One workgroup: TPW = NW / SPLITK consecutive row tiles starting at tile0, each split over
 // SPLITK waves along K; K is walked in chunks of cg groups whose activations fit in LDS.
 // x: M vectors of in_f fp16, y: M vectors of out_f fp32.
-template <int B, int M, int NW, int SPLITK, int PF>
+template <int B, int M, int NW, int SPLITK, int PF, bool XS>
 __device__ __forceinline__ void run_tiles(const LayerDesc& L, int tile0, const _Float16* __restrict__ x,
                                           float* __restrict__ y, uint4* lds) {
   static_assert(NW % SPLITK == 0, "waves must divide evenly over the K splits");
+  const UnpackConsts<B> uc;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int G = L.n_groups;
@@ -284,7 +343,11 @@ __device__ __forceinline__ void run_tiles(const LayerDesc& L, int tile0, const _
           nsa[j] = sp[gl * 64];
           if (gc < g1) {
             float accL[M], accH[M];
-            mac_group<B, M>(cur, xs + (gc - c0) * 16, cg * 16, accL, accH);
+            if constexpr (XS && M == 1) {
+              mac_group_sx<B>(uc, cur, (const_u32x16_ptr)(x) + gc * 4, accL[0], accH[0]);
+            } else {
+              mac_group<B, M>(uc, cur, xs + (gc - c0) * 16, cg * 16, accL, accH);
+            }
             const float s = half_bits_to_float(csa & 0xffffu);
             const float a = half_bits_to_float(csa >> 16);
 #pragma unroll
@@ -322,6 +385,278 @@ __device__ __forceinline__ void run_tiles(const LayerDesc& L, int tile0, const _
   }
 }
 
+// =====================================================================================
+// MFMA-assisted variant.  Unpack is unchanged; the multiply-accumulate and the sum over K go
+// to the matrix pipe, which is otherwise idle, so the VALU only pays for the unpack.
+//
+// v_mfma_f32_16x16x32_f16 computes D[i][j] += sum_k A[i][k] B[k][j] with lane l holding
+// A[l%16][8(l/16) .. 8(l/16)+7] and B[8(l/16) ..][l%16], and D[4(l/16)+t][l%16] in register t.
+// A lane's 8 unpacked weights belong to ROW l of the tile, not to row l%16, so the operand is
+// read as A[i][8G+t] = w[row 16G+i][t] (G = l/16).  Choosing B[8G+t][j] = x[t] for j == G and 0
+// elsewhere gives D[i][j] = sum_t w[16j+i][t] x[t]: column j < 4 of D holds the dot products of
+// rows 16j .. 16j+15.  Columns 4*beta + rho carry activation vector beta (up to 4 vectors per
+// MFMA, 8 with a second accumulator set), so batches 1..8 read and unpack the weights once.
+// The B operand comes straight from LDS with a per-lane address (x for the "diagonal" lanes,
+// a block of zeros for the rest): no VALU work.  Low-nibble and high-nibble pairs go to
+// separate accumulators DL, DH because they differ by the factor 16 (see the header comment).
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+
+// LDS image for the MFMA path: per vector cg groups of x (256 B each, permuted), the (X_g, F_g)
+// pairs, 256 zero bytes, then the split-K meeting point (16 B per lane, wave and accumulator set).
+constexpr int kZeroBlockVec = 20;  // 320 zero bytes: 256 read by the off-diagonal lanes, 64 of phase shift
+__host__ __device__ inline size_t lds_bytes_mfma(int cg, int m, int n_waves, int sets_times_tiles) {
+  return static_cast<size_t>(m) * cg * (256 + 8) + kZeroBlockVec * 16 +
+         static_cast<size_t>(sets_times_tiles) * n_waves * 64 * 16;
+}
+
+// Copy groups [c0, c0+cn) of the m vectors into LDS in MFMA operand order.  Within each
+// 32-column word the 16 dwords are stored as [L#1][H#1][L#2][H#2], 4 dwords each, where L
+// collects the column pairs whose code sits in a low nibble (columns 8q+0,1 and 8q+4,5) and H
+// those in a high nibble (8q+2,3 and 8q+6,7); #1 covers columns 0..15 of the word, #2 16..31.
+template <int B, int NW>
+__device__ __forceinline__ void stage_activations_mfma(const _Float16* __restrict__ x, int in_f, int m, int c0, int cn,
+                                                       int cg, uint32_t* xs, float2* cs, uint4* zeros) {
+  const int n16 = cn * 16;
+  for (int j = 0; j < m; ++j) {
+    const uint4* xg = reinterpret_cast<const uint4*>(x + static_cast<int64_t>(j) * in_f) + c0 * 16;
+    for (int idx = threadIdx.x; idx < n16; idx += NW * 64) {
+      const uint4 v = xg[idx];
+      const int q = idx & 3;  // which 8 columns of the 32-column word
+      uint32_t* dst = xs + (j * cg * 64) + (idx >> 2) * 16 + (q >> 1) * 8 + (q & 1) * 2;
+      *reinterpret_cast<uint2*>(dst) = make_uint2(v.x, v.z);
+      *reinterpret_cast<uint2*>(dst + 4) = make_uint2(v.y, v.w);
+      const half2_t a = __builtin_bit_cast(half2_t, v.x), b = __builtin_bit_cast(half2_t, v.y);
+      const half2_t c = __builtin_bit_cast(half2_t, v.z), e = __builtin_bit_cast(half2_t, v.w);
+      float lo = (static_cast<float>(a.x) + static_cast<float>(a.y)) + (static_cast<float>(c.x) + static_cast<float>(c.y));
+      float hi = (static_cast<float>(b.x) + static_cast<float>(b.y)) + (static_cast<float>(e.x) + static_cast<float>(e.y));
+#pragma unroll
+      for (int off = 1; off < 16; off <<= 1) {
+        lo += __shfl_xor(lo, off, 16);
+        hi += __shfl_xor(hi, off, 16);
+      }
+      if ((idx & 15) == 0) {
+        const float X = lo + hi;
+        const float F = X * (B == 4 ? 0.5f : B == 3 ? 1.0f : 2.0f) - 1024.0f * (lo + hi * 0.0625f);
+        cs[j * cg + (idx >> 4)] = make_float2(X, F);
+      }
+    }
+  }
+  if (threadIdx.x < kZeroBlockVec) zeros[threadIdx.x] = make_uint4(0, 0, 0, 0);
+}
+
+__device__ __forceinline__ half8_t as_half8(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+  u32x4 v = {a, b, c, d};
+  return __builtin_bit_cast(half8_t, v);
+}
+
+// One workgroup of the MFMA variant.  SETS = 1 serves m <= 4 vectors, SETS = 2 serves m <= 8.
+// Each wave owns T consecutive row tiles and reuses every B operand it reads from LDS for all
+// of them, which divides the LDS traffic per weight by T.
+template <int B, int SETS, int T, int NW, int SPLITK>
+__device__ __forceinline__ void run_tiles_mfma(const LayerDesc& L, int tile0, const _Float16* __restrict__ x, int m,
+                                               float* __restrict__ y, uint4* lds) {
+  static_assert(NW % SPLITK == 0, "waves must divide evenly over the K splits");
+  const UnpackConsts<B> uc;
+  const uint32_t maskL = uc.maskL, maskH = uc.maskH, magic = uc.magic;
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int G = L.n_groups;
+  const int cg = chunk_groups(G, m);
+  uint32_t* xs = reinterpret_cast<uint32_t*>(lds);
+  float2* cs = reinterpret_cast<float2*>(xs + m * cg * 64);
+  uint4* zeros = reinterpret_cast<uint4*>(cs + m * cg);
+  float4_t* red = reinterpret_cast<float4_t*>(zeros + kZeroBlockVec);
+
+  const int tile_first = tile0 + (wave / SPLITK) * T;
+  const int ks = wave % SPLITK;
+  const bool active = tile_first < L.n_tiles;
+  // MFMA output geometry of this lane: column j, rows 4*gq .. 4*gq+3 of the 16-row block rho.
+  const int j = lane & 15, gq = lane >> 4;
+  const int beta = j >> 2, rho = j & 3;
+  const int rows0 = 16 * rho + 4 * gq;  // first of the lane's 4 output rows within a tile
+  // Tiles past the end of the layer are clamped to the last one (loads stay in bounds, the
+  // duplicate result is not stored).
+  global_u32x4_ptr pp[T][B];
+  global_u32x4_ptr sp[T];
+#pragma unroll
+  for (int t = 0; t < T; ++t) {
+    int tl = tile_first + t;
+    tl = tl < L.n_tiles ? tl : L.n_tiles - 1;
+    tl = active ? tl : 0;
+    const int64_t tbase = (static_cast<int64_t>(tl) * G) * 64;
+#pragma unroll
+    for (int k = 0; k < B; ++k) pp[t][k] = (global_u32x4_ptr)(L.plane[k]) + tbase + lane;
+    sp[t] = (global_u32x4_ptr)((global_u32_ptr)(L.sa) + tbase + rows0);
+  }
+
+  // Per-lane LDS addressing of the B operand (bytes from xs): x of vector beta for the
+  // "diagonal" lanes; every other lane reads a block of zeros that does not advance with the
+  // group and sits 64 bytes out of phase so that the two addresses never share a bank.
+  const char* lds_c = reinterpret_cast<const char*>(xs);
+  const int zero_off = static_cast<int>(reinterpret_cast<const char*>(zeros) - lds_c) + 64;
+  int boff[SETS], bmul[SETS], cidx[SETS];
+#pragma unroll
+  for (int s = 0; s < SETS; ++s) {
+    const int bt = beta + 4 * s;
+    const bool diag = (rho == gq) && (bt < m);
+    boff[s] = diag ? bt * cg * 256 : zero_off;
+    bmul[s] = diag ? 256 : 0;
+    cidx[s] = (bt < m ? bt : m - 1) * cg;
+  }
+
+  float4_t yacc[T][SETS];
+#pragma unroll
+  for (int t = 0; t < T; ++t)
+#pragma unroll
+    for (int s = 0; s < SETS; ++s) yacc[t][s] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+  for (int c0 = 0; c0 < G; c0 += cg) {
+    const int cn = (G - c0 < cg) ? (G - c0) : cg;
+    if (c0) __syncthreads();
+    stage_activations_mfma<B, NW>(x, L.in_f, m, c0, cn, cg, xs, cs, zeros);
+    __syncthreads();
+    const int g0 = c0 + cn * ks / SPLITK, g1 = c0 + cn * (ks + 1) / SPLITK;
+    if (active && g0 < g1) {
+      u32x4 nb[T][B];
+#pragma unroll
+      for (int t = 0; t < T; ++t)
+#pragma unroll
+        for (int k = 0; k < B; ++k) nb[t][k] = __builtin_nontemporal_load(&pp[t][k][g0 * 64]);
+      for (int gc = g0; gc < g1; ++gc) {
+        u32x4 cur[T][B];
+        u32x4 csa[T];
+        const int gl = (gc + 1 < g1) ? (gc + 1) : (g1 - 1);
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+#pragma unroll
+          for (int k = 0; k < B; ++k) cur[t][k] = nb[t][k];
+          // scale/min words are needed only after the group's arithmetic: no ring for them
+          csa[t] = __builtin_nontemporal_load(&sp[t][gc * 16]);
+#pragma unroll
+          for (int k = 0; k < B; ++k) nb[t][k] = __builtin_nontemporal_load(&pp[t][k][gl * 64]);
+        }
+
+        const char* xb[SETS];
+#pragma unroll
+        for (int s = 0; s < SETS; ++s) xb[s] = lds_c + boff[s] + (gc - c0) * bmul[s];
+        float4_t dl[T][SETS], dh[T][SETS];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+          half8_t bL[2][SETS], bH[2][SETS];
+#pragma unroll
+          for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int s = 0; s < SETS; ++s) {
+              bL[q][s] = *reinterpret_cast<const half8_t*>(xb[s] + d * 64 + q * 32);
+              bH[q][s] = *reinterpret_cast<const half8_t*>(xb[s] + d * 64 + q * 32 + 16);
+            }
+#pragma unroll
+          for (int t = 0; t < T; ++t) {
+            uint32_t p[B];
+#pragma unroll
+            for (int k = 0; k < B; ++k) p[k] = word_of(cur[t][k], d);
+            uint32_t r[4][4];  // r[m][0..3] = (low v0, high v0, low v1, high v1) pairs of word m
+#pragma unroll
+            for (int mm = 0; mm < 4; ++mm) {
+              uint32_t u = merge_planes<B>(uc, p, mm);
+              uint32_t w = (mm == 0) ? u : __builtin_amdgcn_alignbit(u, u, mm);
+              uint32_t w8 = w >> 8;
+              r[mm][0] = and_or(w, maskL, magic);
+              r[mm][1] = and_or(w, maskH, magic);
+              r[mm][2] = and_or(w8, maskL, magic);
+              r[mm][3] = and_or(w8, maskH, magic);
+            }
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {  // columns 16q .. 16q+15 of the word
+              const half8_t aL = as_half8(r[2 * q][0], r[2 * q][2], r[2 * q + 1][0], r[2 * q + 1][2]);
+              const half8_t aH = as_half8(r[2 * q][1], r[2 * q][3], r[2 * q + 1][1], r[2 * q + 1][3]);
+#pragma unroll
+              for (int s = 0; s < SETS; ++s) {
+                const float4_t zero = {0.f, 0.f, 0.f, 0.f};
+                dl[t][s] = __builtin_amdgcn_mfma_f32_16x16x32_f16(aL, bL[q][s], (d == 0 && q == 0) ? zero : dl[t][s], 0, 0, 0);
+                dh[t][s] = __builtin_amdgcn_mfma_f32_16x16x32_f16(aH, bH[q][s], (d == 0 && q == 0) ? zero : dh[t][s], 0, 0, 0);
+              }
+            }
+          }
+        }
+        // scale and minimum of the lane's 4 output rows per tile, once per group
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+          const uint32_t sa4[4] = {csa[t].x, csa[t].y, csa[t].z, csa[t].w};
+#pragma unroll
+          for (int s = 0; s < SETS; ++s) {
+            const float2 c = cs[cidx[s] + (gc - c0)];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float sc = half_bits_to_float(sa4[e] & 0xffffu);
+              const float mn = half_bits_to_float(sa4[e] >> 16);
+              const float u = fmaf(dh[t][s][e], 0.0625f, dl[t][s][e]) + c.y;
+              yacc[t][s][e] = fmaf(sc, u, yacc[t][s][e]);
+              yacc[t][s][e] = fmaf(mn, c.x, yacc[t][s][e]);
+            }
+          }
+        }
+      }
+    }
+  }
+  if constexpr (SPLITK > 1) {
+#pragma unroll
+    for (int t = 0; t < T; ++t)
+#pragma unroll
+      for (int s = 0; s < SETS; ++s) red[((t * SETS + s) * NW + wave) * 64 + lane] = yacc[t][s];
+    __syncthreads();
+    if (ks == 0) {
+#pragma unroll
+      for (int t = 0; t < T; ++t)
+#pragma unroll
+        for (int s = 0; s < SETS; ++s) {
+          float4_t sum = yacc[t][s];
+#pragma unroll
+          for (int q = 1; q < SPLITK; ++q) sum += red[((t * SETS + s) * NW + wave + q) * 64 + lane];
+          yacc[t][s] = sum;
+        }
+    }
+  }
+  if (ks == 0 && active) {
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+      if (tile_first + t < L.n_tiles) {
+#pragma unroll
+        for (int s = 0; s < SETS; ++s) {
+          const int bt = beta + 4 * s;
+          if (bt < m) {
+            const int row = (tile_first + t) * 64 + rows0;
+            float* yo = y + static_cast<int64_t>(bt) * L.out_f + row;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (row + e < L.out_f) yo[e] = yacc[t][s][e];
+          }
+        }
+      }
+    }
+  }
+}
+
+template <int B, int T, int NW, int SPLITK>
+__global__ __launch_bounds__(NW * 64, 4) void pmpd_gemv_stack_mfma_kernel(const LayerDesc* __restrict__ layers,
+                                                                          const WorkItem* __restrict__ items,
+                                                                          const _Float16* __restrict__ x_base,
+                                                                          float* __restrict__ y_base) {
+  extern __shared__ uint4 lds[];
+  const WorkItem it = items[blockIdx.x];
+  const LayerDesc L = layers[it.layer];
+  run_tiles_mfma<B, 1, T, NW, SPLITK>(L, it.tile0, x_base + L.x_off, 1, y_base + L.y_off, lds);
+}
+
+template <int B, int SETS, int NW, int SPLITK>
+__global__ __launch_bounds__(NW * 64, 4) void pmpd_gemm_layer_mfma_kernel(LayerDesc L, const _Float16* __restrict__ x,
+                                                                          int m, float* __restrict__ y) {
+  extern __shared__ uint4 lds[];
+  run_tiles_mfma<B, SETS, 1, NW, SPLITK>(L, static_cast<int>(blockIdx.x) * (NW / SPLITK), x, m, y, lds);
+}
+
 template <int B, int NW, int SPLITK, int PF>
 __global__ __launch_bounds__(NW * 64, 4) void pmpd_gemv_stack_kernel(const LayerDesc* __restrict__ layers,
                                                                    const WorkItem* __restrict__ items,
@@ -330,14 +665,14 @@ __global__ __launch_bounds__(NW * 64, 4) void pmpd_gemv_stack_kernel(const Layer
   extern __shared__ uint4 lds[];
   const WorkItem it = items[blockIdx.x];
   const LayerDesc L = layers[it.layer];
-  run_tiles<B, 1, NW, SPLITK, PF>(L, it.tile0, x_base + L.x_off, y_base + L.y_off, lds);
+  run_tiles<B, 1, NW, SPLITK, PF, PMPD_X_SCALAR != 0>(L, it.tile0, x_base + L.x_off, y_base + L.y_off, lds);
 }
 
 template <int B, int M, int NW, int SPLITK, int PF>
 __global__ __launch_bounds__(NW * 64, 4) void pmpd_gemv_layer_kernel(LayerDesc L, const _Float16* __restrict__ x,
                                                                    float* __restrict__ y) {
   extern __shared__ uint4 lds[];
-  run_tiles<B, M, NW, SPLITK, PF>(L, static_cast<int>(blockIdx.x) * (NW / SPLITK), x, y, lds);
+  run_tiles<B, M, NW, SPLITK, PF, PMPD_X_SCALAR != 0>(L, static_cast<int>(blockIdx.x) * (NW / SPLITK), x, y, lds);
 }
 
 // ------------------------------------------------------------------ host side ----
@@ -407,6 +742,46 @@ static hipError_t launch_layer_b(const LayerDesc& d, const void* x, int m, float
   }
 }
 
+// ---- MFMA variant launchers ----
+static bool use_mfma_default() {
+  // PMPD_MAC=dot2 selects the all-VALU kernels, PMPD_MAC=mfma the MFMA-assisted ones.
+  static const int choice = [] {
+    const char* e = std::getenv("PMPD_MAC");
+    if (e && std::strcmp(e, "dot2") == 0) return 0;
+    if (e && std::strcmp(e, "mfma") == 0) return 1;
+    return PMPD_DEFAULT_MFMA;
+  }();
+  return choice != 0;
+}
+
+template <int B, int SETS, int NW, int SPLITK>
+static hipError_t launch_layer_mfma(const LayerDesc& d, const void* x, int m, float* y, hipStream_t s) {
+  const int tpw = NW / SPLITK;
+  const unsigned grid = static_cast<unsigned>((d.n_tiles + tpw - 1) / tpw);
+  const size_t lds = lds_bytes_mfma(chunk_groups(d.n_groups, m), m, NW, SETS);  // T = 1
+  hipLaunchKernelGGL((pmpd_gemm_layer_mfma_kernel<B, SETS, NW, SPLITK>), dim3(grid), dim3(NW * 64), lds, s, d,
+                     static_cast<const _Float16*>(x), m, y);
+  return hipGetLastError();
+}
+
+template <int B, int SETS>
+static hipError_t launch_layer_mfma_bs(const LayerDesc& d, const void* x, int m, float* y, hipStream_t s) {
+  const int cg = chunk_groups(d.n_groups, m);
+  int splitk = 1;
+  while (splitk < 8 && static_cast<int64_t>(d.n_tiles) * splitk < 2048 && cg / (splitk * 2) >= 4) splitk *= 2;
+  switch (splitk) {
+    case 1: return launch_layer_mfma<B, SETS, 4, 1>(d, x, m, y, s);
+    case 2: return launch_layer_mfma<B, SETS, 4, 2>(d, x, m, y, s);
+    case 4: return launch_layer_mfma<B, SETS, 4, 4>(d, x, m, y, s);
+    default: return launch_layer_mfma<B, SETS, 8, 8>(d, x, m, y, s);
+  }
+}
+
+template <int B>
+static hipError_t launch_layer_mfma_b(const LayerDesc& d, const void* x, int m, float* y, hipStream_t s) {
+  return m <= 4 ? launch_layer_mfma_bs<B, 1>(d, x, m, y, s) : launch_layer_mfma_bs<B, 2>(d, x, m, y, s);
+}
+
 static int32_t linear_entry(const char* who, const pmpd_layer_t* layer, int32_t b, const void* x, int32_t m, float* y,
                             void* stream) {
   int32_t rc = check_bits(b, who);
@@ -419,9 +794,16 @@ static int32_t linear_entry(const char* who, const pmpd_layer_t* layer, int32_t 
   if (reinterpret_cast<uintptr_t>(y) % 4) return fail(PMPD_EALIGN, "%s: y not 4-byte aligned", who);
   const LayerDesc d = make_desc(*layer, 0, 0);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  hipError_t e = b == 4 ? launch_layer_b<4>(d, x, m, y, s)
-                 : b == 3 ? launch_layer_b<3>(d, x, m, y, s)
-                          : launch_layer_b<2>(d, x, m, y, s);
+  hipError_t e;
+  if (use_mfma_default()) {
+    e = b == 4 ? launch_layer_mfma_b<4>(d, x, m, y, s)
+        : b == 3 ? launch_layer_mfma_b<3>(d, x, m, y, s)
+                 : launch_layer_mfma_b<2>(d, x, m, y, s);
+  } else {
+    e = b == 4 ? launch_layer_b<4>(d, x, m, y, s)
+        : b == 3 ? launch_layer_b<3>(d, x, m, y, s)
+                 : launch_layer_b<2>(d, x, m, y, s);
+  }
   if (e != hipSuccess) return hip_fail(e, who);
   return PMPD_OK;
 }
@@ -430,17 +812,18 @@ static int32_t linear_entry(const char* who, const pmpd_layer_t* layer, int32_t 
 
 using namespace pmpd;
 
+// Work lists of a stack, one per workgroup size in row tiles.
+static constexpr int kNumItemLists = 3;
+static constexpr int kStackTilesPerWg[kNumItemLists] = {4, 1, 8};
+
 struct pmpd_stack {
   std::vector<LayerDesc> layers;
-  std::vector<WorkItem> items[2];  // work lists for the two launch shapes below
+  std::vector<WorkItem> items[kNumItemLists];
   const LayerDesc* d_layers = nullptr;
-  const WorkItem* d_items[2] = {nullptr, nullptr};
+  const WorkItem* d_items[kNumItemLists] = {nullptr, nullptr, nullptr};
   int max_in = 0;
-  int shape = 0;
+  int variant[5] = {0, 0, 0, 0, 0};  // kernel variant per bit-width (index = b)
 };
-
-// Stack launch shapes: index 0 = 4 waves, one tile each, whole K; index 1 = 4 waves on one tile, K split 4 ways.
-static constexpr int kStackTilesPerWg[2] = {4, 1};
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -454,9 +837,35 @@ static void build_items(const std::vector<LayerDesc>& layers, int tiles_per_wg, 
     for (int t = 0; t < layers[li].n_tiles; t += tiles_per_wg) out.push_back(WorkItem{li, t});
 }
 
-static size_t stack_bytes(const std::vector<LayerDesc>& layers, size_t n_items0, size_t n_items1) {
-  return align_up(layers.size() * sizeof(LayerDesc), 256) + align_up(n_items0 * sizeof(WorkItem), 256) +
-         align_up(n_items1 * sizeof(WorkItem), 256);
+static size_t stack_bytes(size_t n_layers, const size_t (&n_items)[kNumItemLists]) {
+  size_t b = align_up(n_layers * sizeof(LayerDesc), 256);
+  for (int q = 0; q < kNumItemLists; ++q) b += align_up(n_items[q] * sizeof(WorkItem), 256);
+  return b;
+}
+
+// Stack kernel variants (PMPD_STACK_VARIANT="v4,v3,v2" overrides the per-bit-width defaults):
+//   0  VALU dot2, 4 waves x 1 tile, whole K         1  VALU dot2, 4 waves on 1 tile, K split 4 ways
+//   2  MFMA, 4 waves x 1 tile                       3  MFMA, 4 waves x 2 tiles
+//   4  MFMA, 2 waves x 2 tiles
+static constexpr int kNumVariants = 5;
+static constexpr int kVariantList[kNumVariants] = {0, 1, 0, 2, 0};  // which work list each variant walks
+#ifndef PMPD_STACK_DEFAULTS
+#define PMPD_STACK_DEFAULTS {0, 0, 0}  // variants for b = 4, 3, 2
+#endif
+
+static void pick_variants(int (&variant)[5]) {
+  const int defaults[3] = PMPD_STACK_DEFAULTS;
+  variant[4] = defaults[0];
+  variant[3] = defaults[1];
+  variant[2] = defaults[2];
+  const char* e = std::getenv("PMPD_STACK_VARIANT");
+  if (e) {
+    int v[3];
+    if (std::sscanf(e, "%d,%d,%d", &v[0], &v[1], &v[2]) == 3) {
+      for (int i = 0; i < 3; ++i)
+        if (v[i] >= 0 && v[i] < kNumVariants) variant[4 - i] = v[i];
+    }
+  }
 }
 
 static int32_t check_stack_args(const pmpd_layer_t* layers, int32_t n, const char* who) {
@@ -470,16 +879,33 @@ static int32_t check_stack_args(const pmpd_layer_t* layers, int32_t n, const cha
 }
 
 template <int B>
-static hipError_t launch_stack(const pmpd_stack* st, const void* x, float* y, hipStream_t s) {
-  const int q = st->shape;
+static hipError_t launch_stack(const pmpd_stack* st, const void* xv, float* y, hipStream_t s) {
+  const int v = st->variant[B];
+  const int q = kVariantList[v];
   const unsigned grid = static_cast<unsigned>(st->items[q].size());
-  const size_t lds = lds_bytes(chunk_groups(st->max_in / kGroup, 1), 1, 4);
-  if (q == 0) {
-    hipLaunchKernelGGL((pmpd_gemv_stack_kernel<B, 4, 1, PMPD_PF>), dim3(grid), dim3(256), lds, s, st->d_layers, st->d_items[0],
-                       static_cast<const _Float16*>(x), y);
-  } else {
-    hipLaunchKernelGGL((pmpd_gemv_stack_kernel<B, 4, 4, PMPD_PF>), dim3(grid), dim3(256), lds, s, st->d_layers, st->d_items[1],
-                       static_cast<const _Float16*>(x), y);
+  const _Float16* x = static_cast<const _Float16*>(xv);
+  const int cg = chunk_groups(st->max_in / kGroup, 1);
+  switch (v) {
+    case 0:
+      hipLaunchKernelGGL((pmpd_gemv_stack_kernel<B, 4, 1, PMPD_PF>), dim3(grid), dim3(256), lds_bytes(cg, 1, 4), s,
+                         st->d_layers, st->d_items[q], x, y);
+      break;
+    case 1:
+      hipLaunchKernelGGL((pmpd_gemv_stack_kernel<B, 4, 4, PMPD_PF>), dim3(grid), dim3(256), lds_bytes(cg, 1, 4), s,
+                         st->d_layers, st->d_items[q], x, y);
+      break;
+    case 2:
+      hipLaunchKernelGGL((pmpd_gemv_stack_mfma_kernel<B, 1, 4, 1>), dim3(grid), dim3(256), lds_bytes_mfma(cg, 1, 4, 1), s,
+                         st->d_layers, st->d_items[q], x, y);
+      break;
+    case 3:
+      hipLaunchKernelGGL((pmpd_gemv_stack_mfma_kernel<B, 2, 4, 1>), dim3(grid), dim3(256), lds_bytes_mfma(cg, 1, 4, 2), s,
+                         st->d_layers, st->d_items[q], x, y);
+      break;
+    default:
+      hipLaunchKernelGGL((pmpd_gemv_stack_mfma_kernel<B, 2, 2, 1>), dim3(grid), dim3(128), lds_bytes_mfma(cg, 1, 2, 2), s,
+                         st->d_layers, st->d_items[q], x, y);
+      break;
   }
   return hipGetLastError();
 }
@@ -498,13 +924,13 @@ int32_t pmpd_stack_workspace_size(const pmpd_layer_t* layers, int32_t n, size_t*
   int32_t rc = check_stack_args(layers, n, "pmpd_stack_workspace_size");
   if (rc) return rc;
   if (!bytes) return fail(PMPD_EINVAL, "pmpd_stack_workspace_size: bytes is NULL");
-  size_t items[2] = {0, 0};
+  size_t items[kNumItemLists] = {};
   for (int i = 0; i < n; ++i) {
     int64_t tiles = padded_rows(layers[i].out_features) / kTile;
-    for (int q = 0; q < 2; ++q) items[q] += static_cast<size_t>((tiles + kStackTilesPerWg[q] - 1) / kStackTilesPerWg[q]);
+    for (int q = 0; q < kNumItemLists; ++q)
+      items[q] += static_cast<size_t>((tiles + kStackTilesPerWg[q] - 1) / kStackTilesPerWg[q]);
   }
-  *bytes = align_up(static_cast<size_t>(n) * sizeof(LayerDesc), 256) + align_up(items[0] * sizeof(WorkItem), 256) +
-           align_up(items[1] * sizeof(WorkItem), 256);
+  *bytes = stack_bytes(static_cast<size_t>(n), items);
   return PMPD_OK;
 }
 
@@ -523,8 +949,12 @@ int32_t pmpd_stack_create(const pmpd_layer_t* layers, int32_t n, const int64_t* 
     st->layers.push_back(make_desc(layers[i], x_offset[i], y_offset[i]));
     st->max_in = std::max(st->max_in, layers[i].in_features);
   }
-  for (int q = 0; q < 2; ++q) build_items(st->layers, kStackTilesPerWg[q], st->items[q]);
-  const size_t need = stack_bytes(st->layers, st->items[0].size(), st->items[1].size());
+  size_t counts[kNumItemLists];
+  for (int q = 0; q < kNumItemLists; ++q) {
+    build_items(st->layers, kStackTilesPerWg[q], st->items[q]);
+    counts[q] = st->items[q].size();
+  }
+  const size_t need = stack_bytes(st->layers.size(), counts);
   if (workspace_bytes < need) {
     delete st;
     return fail(PMPD_ESIZE, "pmpd_stack_create: workspace %zu bytes, need %zu", workspace_bytes, need);
@@ -533,7 +963,7 @@ int32_t pmpd_stack_create(const pmpd_layer_t* layers, int32_t n, const int64_t* 
   hipError_t e = hipMemcpy(w, st->layers.data(), st->layers.size() * sizeof(LayerDesc), hipMemcpyHostToDevice);
   st->d_layers = reinterpret_cast<const LayerDesc*>(w);
   w += align_up(st->layers.size() * sizeof(LayerDesc), 256);
-  for (int q = 0; q < 2 && e == hipSuccess; ++q) {
+  for (int q = 0; q < kNumItemLists && e == hipSuccess; ++q) {
     e = hipMemcpy(w, st->items[q].data(), st->items[q].size() * sizeof(WorkItem), hipMemcpyHostToDevice);
     st->d_items[q] = reinterpret_cast<const WorkItem*>(w);
     w += align_up(st->items[q].size() * sizeof(WorkItem), 256);
@@ -542,9 +972,7 @@ int32_t pmpd_stack_create(const pmpd_layer_t* layers, int32_t n, const int64_t* 
     delete st;
     return hip_fail(e, "pmpd_stack_create copy");
   }
-  // PMPD_STACK_SHAPE=1 selects the split-K shape (tuning aid); default is whole-K waves.
-  const char* env = std::getenv("PMPD_STACK_SHAPE");
-  st->shape = (env && env[0] == '1') ? 1 : 0;
+  pick_variants(st->variant);
   *out = st;
   return PMPD_OK;
 }

@@ -57,7 +57,8 @@ extern "C" {
 
 #define PMPD_GROUP 128     /* input features per quantisation group */
 #define PMPD_ROW_TILE 64   /* rows per storage tile (one per lane of a wave) */
-#define PMPD_MAX_BATCH 8   /* rows of X accepted by pmpd_gemm's skinny path */
+#define PMPD_MAX_BATCH 8   /* rows of X up to which pmpd_gemm takes its skinny path */
+#define PMPD_MAX_ROWS 65536 /* rows of X accepted by pmpd_gemm / pmpd_prefill_step */
 
 /* One packed linear layer.  Plain data; the pointers are the caller's (device memory for
  * pmpd_gemv / pmpd_gemm / stacks, host memory for pmpd_unpack).  planes[k] must be 16-byte
@@ -97,7 +98,11 @@ int32_t pmpd_unpack(const pmpd_layer_t* host_layer, int32_t b, uint8_t* qb_out);
  * x: device, fp16 [in], 16-byte aligned.  y: device, fp32 [out].  b in {2,3,4}. */
 int32_t pmpd_gemv(const pmpd_layer_t* layer, int32_t b, const void* x, float* y, void* stream);
 
-/* Y[j][r] = sum_i W_b[r][i] X[j][i] for 1 <= m <= PMPD_MAX_BATCH; weights are read once.
+/* Y[j][r] = sum_i W_b[r][i] X[j][i] for 1 <= m <= PMPD_MAX_ROWS.
+ * m <= PMPD_MAX_BATCH: skinny path, the weights are read once and the codes stay exact.
+ * m >  PMPD_MAX_BATCH: the compute-bound prefill shape (Section 4.1: prefill runs at its own,
+ *   higher precision of the same store): the weights are dequantised to fp16 (one rounding) and
+ *   the contraction runs on the matrix cores with fp32 accumulation.
  * X: device, fp16 row-major [m][in], 16-byte aligned.  Y: device, fp32 row-major [m][out]. */
 int32_t pmpd_gemm(const pmpd_layer_t* layer, int32_t b, const void* X, int32_t m, float* Y, void* stream);
 
@@ -118,6 +123,12 @@ void pmpd_stack_destroy(pmpd_stack_t* stack);
 /* One decode step: every layer of the stack at bit-width b, one kernel launch. */
 int32_t pmpd_decode_step(const pmpd_stack_t* stack, int32_t b, const void* x_base, float* y_base,
                          void* stream);
+
+/* Prefill over the stack: every layer l computes Y_l[j][r] = sum_i W_b,l[r][i] X_l[j][i], j < m, in
+ * one launch (Algorithm 1 line 10 applied to the linear layers).  X_l = x_base + m*x_offset[l]
+ * (fp16 row-major [m][in_l]), Y_l = y_base + m*y_offset[l] (fp32 row-major [m][out_l]). */
+int32_t pmpd_prefill_step(const pmpd_stack_t* stack, int32_t b, const void* x_base, int32_t m, float* y_base,
+                          void* stream);
 
 /* ---- precision-switching schedule (Section 4.2, Eq. 1-3; Algorithm 1 lines 14 and 20) ----- *
  * precisions[0..n-1] strictly decreasing bit-widths; st[j] = index of the first decode step

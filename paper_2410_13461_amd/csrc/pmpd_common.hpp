@@ -4,6 +4,7 @@
 #include <cstdarg>
 #include <cstddef>
 #include <cstdint>
+#include <vector>
 
 #include "pmpd.h"
 
@@ -40,4 +41,23 @@ struct WorkItem {
   int32_t tile0;
 };
 
+// Work lists of a stack, one per workgroup size in 64-row tiles.
+constexpr int kNumItemLists = 4;
+constexpr int kStackTilesPerWg[kNumItemLists] = {4, 1, 8, 2};
+constexpr int kPrefillItemList = 3;  // the prefill kernel works on 128-row blocks
+
+int32_t check_bits(int32_t b, const char* who);  // b in {2,3,4}
+constexpr int kMaxPrefillRows = 65536;
+LayerDesc make_desc(const pmpd_layer_t& L, int64_t x_off, int64_t y_off);
+
 }  // namespace pmpd
+
+// A list of layers prepared for one-launch steps (host object; the tables live in the caller's workspace).
+struct pmpd_stack {
+  std::vector<pmpd::LayerDesc> layers;
+  std::vector<pmpd::WorkItem> items[pmpd::kNumItemLists];
+  const pmpd::LayerDesc* d_layers = nullptr;
+  const pmpd::WorkItem* d_items[pmpd::kNumItemLists] = {nullptr, nullptr, nullptr, nullptr};
+  int max_in = 0;
+  int variant[5] = {0, 0, 0, 0, 0};  // decode kernel variant per bit-width (index = b)
+};

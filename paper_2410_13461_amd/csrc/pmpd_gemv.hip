@@ -30,6 +30,7 @@
 #include <vector>
 
 #include "pmpd_common.hpp"
+#include "pmpd_device.hpp"
 
 #ifndef PMPD_PF
 #define PMPD_PF 1  // groups of plane words kept in flight ahead of the one being consumed
@@ -50,82 +51,6 @@
 #endif
 
 namespace pmpd {
-
-typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-// Pointers into device global memory that were read from a table keep the generic address space;
-// naming the global one lets the compiler emit global_load (vmcnt only) instead of flat_load.
-typedef const __attribute__((address_space(1))) u32x4* global_u32x4_ptr;
-typedef const __attribute__((address_space(1))) uint32_t* global_u32_ptr;
-// Wave-uniform reads of x go through the scalar data cache into SGPRs (s_load_dwordx16): the
-// constant address space tells the compiler that the memory does not change during the kernel.
-typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
-typedef const __attribute__((address_space(4))) u32x16* const_u32x16_ptr;
-
-__device__ __forceinline__ float dot2(uint32_t w, uint32_t x, float acc) {
-  return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, w), __builtin_bit_cast(half2_t, x), acc, false);
-}
-
-// Bit-select and mask-or use compiler-visible operations; the masks are made opaque to the optimiser
-// (an empty asm that pins them in SGPRs) so that it cannot fold them into distributed ANDs and
-// instead selects one 3-input VALU op each (v_bitop3_b32, v_and_or_b32).  No instruction is
-// emitted through inline asm, so the compiler's hazard handling sees every op.
-__device__ __forceinline__ uint32_t opaque_sgpr(uint32_t v) {
-  asm volatile("" : "+s"(v));
-  return v;
-}
-
-// (a & mask) | (b & ~mask): one v_bitop3_b32 (gfx950's 3-input boolean op).  Truth table index is
-// (a << 2) | (b << 1) | mask, so "mask ? a : b" is 0b11100100.
-__device__ __forceinline__ uint32_t bfi(uint32_t mask, uint32_t a, uint32_t b) {
-  return __builtin_amdgcn_bitop3_b32(a, b, mask, 0xE4);
-}
-
-// (a & mask) | c
-__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t c) { return (a & mask) | c; }
-
-// Constants of the unpack, held in registers for the whole kernel.
-template <int B>
-struct UnpackConsts {
-  uint32_t slot[4];   // bit positions congruent to j mod 4
-  uint32_t slot2[4];  // slot[j] | slot[j-1]
-  uint32_t maskL, maskH, magic;
-  __device__ __forceinline__ UnpackConsts() {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) slot[j] = opaque_sgpr(0x11111111u << j);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) slot2[j] = opaque_sgpr((0x11111111u << j) | (0x11111111u << ((j + 3) & 3)));
-    constexpr uint32_t keep = (0xFu << (4 - B)) & 0xFu;  // top B bits of a 4-bit field
-    maskL = opaque_sgpr(keep * 0x00010001u);
-    maskH = opaque_sgpr(keep * 0x00100010u);
-    magic = 0x64006400u;  // fp16 pair (1024, 1024)
-    asm volatile("" : "+v"(magic));
-  }
-};
-
-__device__ __forceinline__ uint32_t word_of(const u32x4& v, int d) {
-  return d == 0 ? v.x : d == 1 ? v.y : d == 2 ? v.z : v.w;
-}
-
-__device__ __forceinline__ float half_bits_to_float(uint32_t bits16) {
-  return static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(bits16)));
-}
-
-// Merge the B plane words of one 32-weight word into the word whose fields (rotated by m)
-// are the codes of pairs 4m .. 4m+3.  Plane k sits in sub-slot (3 - k + m) mod 4.
-template <int B>
-__device__ __forceinline__ uint32_t merge_planes(const UnpackConsts<B>& uc, const uint32_t (&p)[B], int m) {
-  if constexpr (B == 4) {
-    uint32_t hi = bfi(uc.slot[(3 + m) & 3], p[0], p[1]);
-    uint32_t lo = bfi(uc.slot[(1 + m) & 3], p[2], p[3]);
-    return bfi(uc.slot2[(3 + m) & 3], hi, lo);
-  } else if constexpr (B == 3) {
-    uint32_t lo = bfi(uc.slot[(2 + m) & 3], p[1], p[2]);
-    return bfi(uc.slot[(3 + m) & 3], p[0], lo);
-  } else {
-    return bfi(uc.slot[(3 + m) & 3], p[0], p[1]);
-  }
-}
 
 // Multiply-accumulate one group (128 columns) of the lane's row against M activation vectors.
 //   pl[k]: the lane's 16 bytes of plane k;  xs: the group's 16 uint4 of x in LDS for vector 0,
@@ -680,7 +605,7 @@ static int32_t hip_fail(hipError_t e, const char* what) {
   return fail(PMPD_EHIP, "%s: %s", what, hipGetErrorString(e));
 }
 
-static LayerDesc make_desc(const pmpd_layer_t& L, int64_t x_off, int64_t y_off) {
+LayerDesc make_desc(const pmpd_layer_t& L, int64_t x_off, int64_t y_off) {
   LayerDesc d;
   for (int k = 0; k < 4; ++k) d.plane[k] = L.planes[k];
   d.sa = L.scale_min;
@@ -693,7 +618,7 @@ static LayerDesc make_desc(const pmpd_layer_t& L, int64_t x_off, int64_t y_off) 
   return d;
 }
 
-static int32_t check_bits(int32_t b, const char* who) {
+int32_t check_bits(int32_t b, const char* who) {
   if (b < 2 || b > 4) return fail(PMPD_EINVAL, "%s: bit-width %d outside {2,3,4}", who, b);
   return PMPD_OK;
 }
@@ -782,20 +707,26 @@ static hipError_t launch_layer_mfma_b(const LayerDesc& d, const void* x, int m, 
   return m <= 4 ? launch_layer_mfma_bs<B, 1>(d, x, m, y, s) : launch_layer_mfma_bs<B, 2>(d, x, m, y, s);
 }
 
-static int32_t linear_entry(const char* who, const pmpd_layer_t* layer, int32_t b, const void* x, int32_t m, float* y,
-                            void* stream) {
+// defined in pmpd_prefill.hip
+hipError_t launch_prefill_layer(const LayerDesc& d, int b, const void* X, int m, float* Y, hipStream_t s);
+hipError_t launch_prefill_stack(const pmpd_stack* st, int b, const void* X, int m, float* Y, hipStream_t s);
+
+static int32_t linear_entry(const char* who, const pmpd_layer_t* layer, int32_t b, const void* x, int32_t m, int32_t max_m,
+                            float* y, void* stream) {
   int32_t rc = check_bits(b, who);
   if (rc) return rc;
   rc = check_layer(layer, b, who);
   if (rc) return rc;
-  if (m < 1 || m > PMPD_MAX_BATCH) return fail(PMPD_EINVAL, "%s: batch %d outside 1..%d", who, m, PMPD_MAX_BATCH);
+  if (m < 1 || m > max_m) return fail(PMPD_EINVAL, "%s: batch %d outside 1..%d", who, m, max_m);
   if (!x || !y) return fail(PMPD_EINVAL, "%s: x or y is NULL", who);
   if (reinterpret_cast<uintptr_t>(x) % 16) return fail(PMPD_EALIGN, "%s: x not 16-byte aligned", who);
   if (reinterpret_cast<uintptr_t>(y) % 4) return fail(PMPD_EALIGN, "%s: y not 4-byte aligned", who);
   const LayerDesc d = make_desc(*layer, 0, 0);
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
-  if (use_mfma_default()) {
+  if (m > PMPD_MAX_BATCH) {
+    e = launch_prefill_layer(d, b, x, m, y, s);
+  } else if (use_mfma_default()) {
     e = b == 4 ? launch_layer_mfma_b<4>(d, x, m, y, s)
         : b == 3 ? launch_layer_mfma_b<3>(d, x, m, y, s)
                  : launch_layer_mfma_b<2>(d, x, m, y, s);
@@ -811,19 +742,6 @@ static int32_t linear_entry(const char* who, const pmpd_layer_t* layer, int32_t 
 }  // namespace pmpd
 
 using namespace pmpd;
-
-// Work lists of a stack, one per workgroup size in row tiles.
-static constexpr int kNumItemLists = 3;
-static constexpr int kStackTilesPerWg[kNumItemLists] = {4, 1, 8};
-
-struct pmpd_stack {
-  std::vector<LayerDesc> layers;
-  std::vector<WorkItem> items[kNumItemLists];
-  const LayerDesc* d_layers = nullptr;
-  const WorkItem* d_items[kNumItemLists] = {nullptr, nullptr, nullptr};
-  int max_in = 0;
-  int variant[5] = {0, 0, 0, 0, 0};  // kernel variant per bit-width (index = b)
-};
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -913,11 +831,11 @@ static hipError_t launch_stack(const pmpd_stack* st, const void* xv, float* y, h
 extern "C" {
 
 int32_t pmpd_gemv(const pmpd_layer_t* layer, int32_t b, const void* x, float* y, void* stream) {
-  return linear_entry("pmpd_gemv", layer, b, x, 1, y, stream);
+  return linear_entry("pmpd_gemv", layer, b, x, 1, 1, y, stream);
 }
 
 int32_t pmpd_gemm(const pmpd_layer_t* layer, int32_t b, const void* X, int32_t m, float* Y, void* stream) {
-  return linear_entry("pmpd_gemm", layer, b, X, m, Y, stream);
+  return linear_entry("pmpd_gemm", layer, b, X, m, kMaxPrefillRows, Y, stream);
 }
 
 int32_t pmpd_stack_workspace_size(const pmpd_layer_t* layers, int32_t n, size_t* bytes) {
@@ -990,6 +908,19 @@ int32_t pmpd_decode_step(const pmpd_stack_t* stack, int32_t b, const void* x_bas
                  : b == 3 ? launch_stack<3>(stack, x_base, y_base, s)
                           : launch_stack<2>(stack, x_base, y_base, s);
   if (e != hipSuccess) return hip_fail(e, "pmpd_decode_step launch");
+  return PMPD_OK;
+}
+
+int32_t pmpd_prefill_step(const pmpd_stack_t* stack, int32_t b, const void* x_base, int32_t m, float* y_base,
+                          void* stream) {
+  int32_t rc = check_bits(b, "pmpd_prefill_step");
+  if (rc) return rc;
+  if (!stack || !x_base || !y_base) return fail(PMPD_EINVAL, "pmpd_prefill_step: NULL argument");
+  if (m < 1 || m > kMaxPrefillRows) return fail(PMPD_EINVAL, "pmpd_prefill_step: m %d outside 1..%d", m, kMaxPrefillRows);
+  if (reinterpret_cast<uintptr_t>(x_base) % 16) return fail(PMPD_EALIGN, "pmpd_prefill_step: x_base not 16-byte aligned");
+  if (reinterpret_cast<uintptr_t>(y_base) % 4) return fail(PMPD_EALIGN, "pmpd_prefill_step: y_base not 4-byte aligned");
+  hipError_t e = launch_prefill_stack(stack, b, x_base, m, y_base, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_fail(e, "pmpd_prefill_step launch");
   return PMPD_OK;
 }
 

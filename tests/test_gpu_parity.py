@@ -169,6 +169,45 @@ def test_gemm_skinny_matches_oracle(pmpd, b, m):
         assert_parity(Y.cpu().numpy(), y_ref, t, f"gemm {out_f}x{in_f} m={m} b={b}")
 
 
+@pytest.mark.parametrize("b", [4, 3, 2])
+@pytest.mark.parametrize("m,out_f,in_f", [(16, 200, 512), (100, 130, 2048), (512, 256, 1408), (129, 320, 5120)])
+def test_gemm_prefill_matches_oracle(pmpd, b, m, out_f, in_f):
+    """m > 8 takes the MFMA path: ragged M and N tiles, several K steps, all bit-widths."""
+    import torch
+
+    _say(f"[prefill gemm] m={m} out={out_f} in={in_f} b={b}")
+    q4, s, a = synth.draw_weights(12, out_f, m, out_f, in_f, random_min=True)
+    X = synth.draw_x(12, 0, out_f, m, in_f, m=m)
+    layer = _device_layer(pmpd, q4, s, a)
+    Y = torch.full((m, out_f), float("nan"), dtype=torch.float32, device="cuda")
+    pmpd.gemm(layer, b, torch.from_numpy(X).cuda(), Y)
+    torch.cuda.synchronize()
+    y_ref, t = oracle.linear(q4, s, a, b, X)
+    assert_parity(Y.cpu().numpy(), y_ref, t, f"prefill gemm m={m} {out_f}x{in_f} b={b}")
+
+
+@pytest.mark.parametrize("b", [4, 2])
+def test_prefill_step_over_stack_matches_oracle(pmpd, b):
+    import torch
+
+    m = 70
+    _say(f"[prefill_step] b={b} m={m}")
+    shape, layers, raw = _small_stack(pmpd, seed=8)
+    stack = pmpd.Stack(layers)
+    Xs = [synth.draw_x(8, 0, blk, pi, i, m=m) for (blk, pi, nm, o, i) in shape.layers()]
+    X = torch.from_numpy(np.concatenate([x.reshape(-1) for x in Xs])).cuda()
+    Y = torch.full((m * stack.y_elems,), float("nan"), dtype=torch.float32, device="cuda")
+    pmpd.prefill_step(stack, b, X, m, Y)
+    torch.cuda.synchronize()
+    Y = Y.cpu().numpy()
+    for li, (q4, s, a) in enumerate(raw):
+        o = m * stack.y_offsets[li]
+        y_ref, t = oracle.linear(q4, s, a, b, Xs[li])
+        got = Y[o:o + m * q4.shape[0]].reshape(m, q4.shape[0])
+        assert_parity(got, y_ref, t, f"prefill_step layer {li} b={b}")
+    stack.close()
+
+
 def _small_stack(pmpd, seed=5):
     """A two-block stack with Llama-like proportions (hidden 256, intermediate 640, ragged)."""
     shape = synth.StackShape("tiny", 2, 256, 640)

@@ -124,9 +124,15 @@ void pmpd_stack_destroy(pmpd_stack_t* stack);
 int32_t pmpd_decode_step(const pmpd_stack_t* stack, int32_t b, const void* x_base, float* y_base,
                          void* stream);
 
-/* Prefill over the stack: every layer l computes Y_l[j][r] = sum_i W_b,l[r][i] X_l[j][i], j < m, in
- * one launch (Algorithm 1 line 10 applied to the linear layers).  X_l = x_base + m*x_offset[l]
- * (fp16 row-major [m][in_l]), Y_l = y_base + m*y_offset[l] (fp32 row-major [m][out_l]). */
+/* m tokens through every layer of the stack in one launch:
+ *     Y_l[j][r] = sum_i W_b,l[r][i] X_l[j][i],  j < m,  for every layer l,
+ * X_l = x_base + m*x_offset[l] (fp16 row-major [m][in_l]), Y_l = y_base + m*y_offset[l] (fp32
+ * row-major [m][out_l]).  m == 1 is pmpd_decode_step; 2 <= m <= PMPD_MAX_BATCH reads and unpacks the
+ * weights once for all m vectors (skinny batches; the paper itself stays at batch 1, Section 5.2);
+ * larger m is the compute-bound prefill shape on the matrix cores (Algorithm 1 line 10, Section 4.1).
+ * pmpd_prefill_step is the same call under the paper's name for that phase. */
+int32_t pmpd_batch_step(const pmpd_stack_t* stack, int32_t b, const void* x_base, int32_t m, float* y_base,
+                        void* stream);
 int32_t pmpd_prefill_step(const pmpd_stack_t* stack, int32_t b, const void* x_base, int32_t m, float* y_base,
                           void* stream);
 

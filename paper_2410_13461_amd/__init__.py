@@ -7,6 +7,6 @@ used for device memory and streams.  There is no CPU fallback: importing the
 binding without the built library raises.
 """
 from .binding import (  # noqa: F401
-    PMPDError, PackedLayer, Schedule, Stack, decode_run, decode_step, gemm, gemv, lib_path, pack,
+    PMPDError, PackedLayer, Schedule, Stack, batch_step, decode_run, decode_step, gemm, gemv, lib_path, pack,
     packed_size, prefill_step, unpack, upload_layer, exported_symbols,
 )

@@ -18,7 +18,7 @@ EXPORTS = (
     "pmpd_strerror", "pmpd_last_error", "pmpd_packed_size", "pmpd_pack", "pmpd_unpack", "pmpd_gemv", "pmpd_gemm",
     "pmpd_stack_workspace_size", "pmpd_stack_create", "pmpd_stack_destroy", "pmpd_decode_step",
     "pmpd_schedule_create", "pmpd_schedule_destroy", "pmpd_schedule_bits", "pmpd_schedule_avg_bits",
-    "pmpd_decode_run", "pmpd_prefill_step",
+    "pmpd_decode_run", "pmpd_prefill_step", "pmpd_batch_step",
 )
 
 
@@ -88,6 +88,8 @@ def _load():
     L.pmpd_schedule_avg_bits.argtypes = [vp, i32]
     L.pmpd_prefill_step.restype = i32
     L.pmpd_prefill_step.argtypes = [vp, i32, vp, i32, vp, vp]
+    L.pmpd_batch_step.restype = i32
+    L.pmpd_batch_step.argtypes = [vp, i32, vp, i32, vp, vp]
     L.pmpd_decode_run.restype = i32
     L.pmpd_decode_run.argtypes = [vp, vp, i32, i32, vp, i64, vp, i64, vp]
     _lib = L
@@ -274,6 +276,12 @@ def decode_step(stack: Stack, b: int, x, y, stream=None):
     """One decode step over the stack at bit-width b.  x: fp16 [x_elems], y: fp32 [y_elems]."""
     _check(_load().pmpd_decode_step(stack._h, b, _dev_ptr(x), _dev_ptr(y), _stream_handle(stream)))
     return y
+
+
+def batch_step(stack: Stack, b: int, X, m: int, Y, stream=None):
+    """m tokens through every layer: layer l reads X[m*x_off[l]:][m, in_l] and writes Y[m*y_off[l]:][m, out_l]."""
+    _check(_load().pmpd_batch_step(stack._h, b, _dev_ptr(X), m, _dev_ptr(Y), _stream_handle(stream)))
+    return Y
 
 
 def prefill_step(stack: Stack, b: int, X, m: int, Y, stream=None):

@@ -575,6 +575,18 @@ __global__ __launch_bounds__(NW * 64, 4) void pmpd_gemv_stack_mfma_kernel(const 
   run_tiles_mfma<B, 1, T, NW, SPLITK>(L, it.tile0, x_base + L.x_off, 1, y_base + L.y_off, lds);
 }
 
+template <int B, int SETS, int NW>
+__global__ __launch_bounds__(NW * 64, 4) void pmpd_gemm_stack_mfma_kernel(const LayerDesc* __restrict__ layers,
+                                                                          const WorkItem* __restrict__ items,
+                                                                          const _Float16* __restrict__ x_base, int m,
+                                                                          float* __restrict__ y_base) {
+  extern __shared__ uint4 lds[];
+  const WorkItem it = items[blockIdx.x];
+  const LayerDesc L = layers[it.layer];
+  run_tiles_mfma<B, SETS, 1, NW, 1>(L, it.tile0, x_base + static_cast<int64_t>(m) * L.x_off, m,
+                                    y_base + static_cast<int64_t>(m) * L.y_off, lds);
+}
+
 template <int B, int SETS, int NW, int SPLITK>
 __global__ __launch_bounds__(NW * 64, 4) void pmpd_gemm_layer_mfma_kernel(LayerDesc L, const _Float16* __restrict__ x,
                                                                           int m, float* __restrict__ y) {
@@ -828,6 +840,21 @@ static hipError_t launch_stack(const pmpd_stack* st, const void* xv, float* y, h
   return hipGetLastError();
 }
 
+template <int B>
+static hipError_t launch_stack_batch(const pmpd_stack* st, const void* xv, int m, float* y, hipStream_t s) {
+  const unsigned grid = static_cast<unsigned>(st->items[0].size());
+  const _Float16* x = static_cast<const _Float16*>(xv);
+  const int cg = chunk_groups(st->max_in / kGroup, m);
+  if (m <= 4) {
+    hipLaunchKernelGGL((pmpd_gemm_stack_mfma_kernel<B, 1, 4>), dim3(grid), dim3(256), lds_bytes_mfma(cg, m, 4, 1), s,
+                       st->d_layers, st->d_items[0], x, m, y);
+  } else {
+    hipLaunchKernelGGL((pmpd_gemm_stack_mfma_kernel<B, 2, 4>), dim3(grid), dim3(256), lds_bytes_mfma(cg, m, 4, 2), s,
+                       st->d_layers, st->d_items[0], x, m, y);
+  }
+  return hipGetLastError();
+}
+
 extern "C" {
 
 int32_t pmpd_gemv(const pmpd_layer_t* layer, int32_t b, const void* x, float* y, void* stream) {
@@ -911,17 +938,32 @@ int32_t pmpd_decode_step(const pmpd_stack_t* stack, int32_t b, const void* x_bas
   return PMPD_OK;
 }
 
+int32_t pmpd_batch_step(const pmpd_stack_t* stack, int32_t b, const void* x_base, int32_t m, float* y_base,
+                        void* stream) {
+  int32_t rc = check_bits(b, "pmpd_batch_step");
+  if (rc) return rc;
+  if (!stack || !x_base || !y_base) return fail(PMPD_EINVAL, "pmpd_batch_step: NULL argument");
+  if (m < 1 || m > kMaxPrefillRows) return fail(PMPD_EINVAL, "pmpd_batch_step: m %d outside 1..%d", m, kMaxPrefillRows);
+  if (reinterpret_cast<uintptr_t>(x_base) % 16) return fail(PMPD_EALIGN, "pmpd_batch_step: x_base not 16-byte aligned");
+  if (reinterpret_cast<uintptr_t>(y_base) % 4) return fail(PMPD_EALIGN, "pmpd_batch_step: y_base not 4-byte aligned");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e;
+  if (m == 1) {
+    return pmpd_decode_step(stack, b, x_base, y_base, stream);
+  } else if (m <= PMPD_MAX_BATCH) {
+    e = b == 4 ? launch_stack_batch<4>(stack, x_base, m, y_base, s)
+        : b == 3 ? launch_stack_batch<3>(stack, x_base, m, y_base, s)
+                 : launch_stack_batch<2>(stack, x_base, m, y_base, s);
+  } else {
+    e = launch_prefill_stack(stack, b, x_base, m, y_base, s);
+  }
+  if (e != hipSuccess) return hip_fail(e, "pmpd_batch_step launch");
+  return PMPD_OK;
+}
+
 int32_t pmpd_prefill_step(const pmpd_stack_t* stack, int32_t b, const void* x_base, int32_t m, float* y_base,
                           void* stream) {
-  int32_t rc = check_bits(b, "pmpd_prefill_step");
-  if (rc) return rc;
-  if (!stack || !x_base || !y_base) return fail(PMPD_EINVAL, "pmpd_prefill_step: NULL argument");
-  if (m < 1 || m > kMaxPrefillRows) return fail(PMPD_EINVAL, "pmpd_prefill_step: m %d outside 1..%d", m, kMaxPrefillRows);
-  if (reinterpret_cast<uintptr_t>(x_base) % 16) return fail(PMPD_EALIGN, "pmpd_prefill_step: x_base not 16-byte aligned");
-  if (reinterpret_cast<uintptr_t>(y_base) % 4) return fail(PMPD_EALIGN, "pmpd_prefill_step: y_base not 4-byte aligned");
-  hipError_t e = launch_prefill_stack(stack, b, x_base, m, y_base, static_cast<hipStream_t>(stream));
-  if (e != hipSuccess) return hip_fail(e, "pmpd_prefill_step launch");
-  return PMPD_OK;
+  return pmpd_batch_step(stack, b, x_base, m, y_base, stream);
 }
 
 int32_t pmpd_decode_run(const pmpd_stack_t* stack, const pmpd_schedule_t* schedule, int32_t step0, int32_t n_steps,

@@ -208,6 +208,27 @@ def test_prefill_step_over_stack_matches_oracle(pmpd, b):
     stack.close()
 
 
+@pytest.mark.parametrize("b", [4, 3, 2])
+@pytest.mark.parametrize("m", [1, 2, 4, 5, 8])
+def test_batch_step_over_stack_matches_oracle(pmpd, b, m):
+    import torch
+
+    _say(f"[batch_step] b={b} m={m}")
+    shape, layers, raw = _small_stack(pmpd, seed=9)
+    stack = pmpd.Stack(layers)
+    Xs = [synth.draw_x(9, 0, blk, pi, i, m=m) for (blk, pi, nm, o, i) in shape.layers()]
+    X = torch.from_numpy(np.concatenate([x.reshape(-1) for x in Xs])).cuda()
+    Y = torch.full((m * stack.y_elems,), float("nan"), dtype=torch.float32, device="cuda")
+    pmpd.batch_step(stack, b, X, m, Y)
+    torch.cuda.synchronize()
+    Y = Y.cpu().numpy()
+    for li, (q4, s, a) in enumerate(raw):
+        o = m * stack.y_offsets[li]
+        y_ref, t = oracle.linear(q4, s, a, b, Xs[li])
+        assert_parity(Y[o:o + m * q4.shape[0]].reshape(m, q4.shape[0]), y_ref, t, f"batch_step layer {li} m={m} b={b}")
+    stack.close()
+
+
 def _small_stack(pmpd, seed=5):
     """A two-block stack with Llama-like proportions (hidden 256, intermediate 640, ragged)."""
     shape = synth.StackShape("tiny", 2, 256, 640)

@@ -119,6 +119,8 @@ def test_gemv_argument_validation_needs_no_gpu():
     assert L.pmpd_gemv(None, 4, x, y, None) == -1
     assert L.pmpd_gemm(ctypes.byref(_host_layer()), 4, x, 0, y, None) == -1
     assert L.pmpd_gemm(ctypes.byref(_host_layer()), 4, x, 65537, y, None) == -1
+    assert L.pmpd_batch_step(None, 4, x, 2, y, None) == -1
+    assert L.pmpd_batch_step(ctypes.c_void_p(0x1234), 4, x, 2, ctypes.c_void_p(0x40002), None) == -2
     assert L.pmpd_prefill_step(None, 4, x, 16, y, None) == -1
     assert L.pmpd_prefill_step(ctypes.c_void_p(0x1234), 4, x, 0, y, None) == -1
     assert L.pmpd_prefill_step(ctypes.c_void_p(0x1234), 1, x, 16, y, None) == -1

@@ -75,6 +75,128 @@ def measured_traffic(b: int):
     return None
 
 
+def _ramp(fn, seconds=0.5):
+    """Run fn repeatedly for `seconds` so that the GPU clocks settle before anything is timed."""
+    import torch
+
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        fn()
+        torch.cuda.synchronize()
+
+
+def _timed(fn, n):
+    """Mean milliseconds of n back-to-back calls of fn, HIP events on the current stream."""
+    import torch
+
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    stream = torch.cuda.current_stream()
+    torch.cuda.synchronize()
+    e0.record(stream)
+    for _ in range(n):
+        fn()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / n
+
+
+def secondary_workload(args) -> int:
+    """The other workloads (parity-tested elsewhere): one JSON line each, for the record in the design doc."""
+    import numpy as np
+    import torch
+
+    import pmpd_synth as synth
+    import paper_2410_13461_amd as pmpd
+    from paper_2410_13461_amd import workload
+
+    torch.cuda.set_device(0)
+    K = args.steps
+    out = {"n_gpus": 1, "data": "synthetic", "steps": K, "warmup": args.warmup}
+    if args.workload == "schedule":
+        shape = synth.LLAMA_7B
+        P, st, n_steps = synth.SCHEDULE_7B_256
+        stack, layers, _ = workload.build_stack(shape, seed=args.seed, verbose=True)
+        sch = pmpd.Schedule(P, st, n_steps)
+        xs = np.stack([workload.draw_step_activations(shape, args.seed, k) for k in range(n_steps)])
+        x = torch.from_numpy(xs).cuda()
+        y = torch.zeros(stack.y_elems, dtype=torch.float32, device="cuda")
+        run = lambda k0, n: pmpd.decode_run(stack, sch, k0, n, x[k0:], stack.x_elems, y, 0)
+        _ramp(lambda: run(0, 64))
+        phases = [(4, 0, 64), (3, 64, 96), (2, 160, 96)]
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(len(phases) + 1)]
+        reps = max(1, K // 20)
+        tot = {b: 0.0 for b, _, _ in phases}
+        for _ in range(reps):
+            ev[0].record()
+            for j, (b, k0, n) in enumerate(phases):
+                run(k0, n)
+                ev[j + 1].record()
+            torch.cuda.synchronize()
+            for j, (b, _, _) in enumerate(phases):
+                tot[b] += ev[j].elapsed_time(ev[j + 1])
+        per = {}
+        total_ms = 0.0
+        for b, k0, n in phases:
+            ms = tot[b] / reps
+            total_ms += ms
+            per[str(b)] = {"steps": n, "ms": ms, "us_per_token": ms * 1e3 / n,
+                           "GBps": stack.bytes_at(b) * n / (ms * 1e-3) / 1e9}
+        out.update({"metric": "total linear-layer time of the 256-step progressive schedule (64@4, 96@3, 96@2)",
+                    "value": total_ms, "unit": "ms", "higher_is_better": False, "avg_bits": sch.avg_bits(n_steps),
+                    "config": {"workload": "Llama-7B-shaped stack, 256 decode steps, b per step from the schedule"},
+                    "per_phase": per,
+                    "GBps_overall": sum(stack.bytes_at(b) * n for b, _, n in phases) / (total_ms * 1e-3) / 1e9})
+    elif args.workload == "mobile":
+        shape = synth.MOBILE
+        # two distinct copies of the stack, alternated, so that no step finds its weights in the 256 MB cache
+        stacks = [workload.build_stack(shape, seed=args.seed + c)[0] for c in range(2)]
+        res = {}
+        for m in (1, 2, 4, 8):
+            X = torch.randn(m * stacks[0].x_elems, device="cuda").half()
+            Y = torch.zeros(m * stacks[0].y_elems, dtype=torch.float32, device="cuda")
+            for b in (4, 3, 2):
+                def step():
+                    for stc in stacks:
+                        pmpd.batch_step(stc, b, X, m, Y)
+                _ramp(step, 0.3)
+                ms = _timed(step, K) / 2
+                res[f"m{m}_b{b}"] = {"us_per_step": ms * 1e3, "GBps": stacks[0].bytes_at(b) / (ms * 1e-3) / 1e9}
+        out.update({"metric": "mobile-scale stack (22 blocks, 2048/5632), us per step at batch 1,2,4,8", "unit": "us/step",
+                    "value": res["m1_b4"]["us_per_step"], "higher_is_better": False,
+                    "config": {"workload": "mobile-scale stack, two alternating copies, batch 1/2/4/8 x b=4/3/2"},
+                    "results": res})
+    elif args.workload == "13b":
+        shape = synth.LLAMA_13B
+        stack, layers, _ = workload.build_stack(shape, seed=args.seed, verbose=True)
+        m = 512
+        X = torch.randn(m * stack.x_elems, device="cuda").half()
+        Y = torch.zeros(m * stack.y_elems, dtype=torch.float32, device="cuda")
+        pre = lambda: pmpd.prefill_step(stack, 4, X, m, Y)
+        _ramp(pre, 0.5)
+        ms_pre = _timed(pre, max(3, K // 10))
+        flops = 2.0 * m * shape.n_weights()
+        P, st, n_steps = synth.SCHEDULE_13B_128
+        sch = pmpd.Schedule(P, st, n_steps)
+        xs = torch.randn((n_steps, stack.x_elems), device="cuda").half()
+        y = torch.zeros(stack.y_elems, dtype=torch.float32, device="cuda")
+        dec = lambda: pmpd.decode_run(stack, sch, 0, n_steps, xs, stack.x_elems, y, 0)
+        _ramp(dec, 0.5)
+        ms_dec = _timed(dec, max(2, K // 20))
+        dec_bytes = 48 * stack.bytes_at(3) + 80 * stack.bytes_at(2)
+        out.update({"metric": "13B-shaped stack: 512-token prefill at b=4 (ms) then 128 decode steps 48@3 + 80@2 (ms)",
+                    "unit": "ms", "value": ms_pre + ms_dec, "higher_is_better": False,
+                    "config": {"workload": "13B-shaped stack (40 blocks, 5120/13824)"},
+                    "prefill": {"ms": ms_pre, "TFLOPs": flops / (ms_pre * 1e-3) / 1e12,
+                                "frac_of_2500_TFLOPs": flops / (ms_pre * 1e-3) / 1e12 / 2500.0},
+                    "decode": {"ms": ms_dec, "avg_bits": sch.avg_bits(n_steps), "GBps": dec_bytes / (ms_dec * 1e-3) / 1e9,
+                               "us_per_token": ms_dec * 1e3 / n_steps}})
+    else:
+        print(f"unknown workload {args.workload}", file=sys.stderr)
+        return 2
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -83,6 +205,8 @@ def main() -> int:
     ap.add_argument("--blocks", type=int, default=None, help="debug: fewer blocks (result is then not the named workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--workload", default="7b", choices=["7b", "schedule", "mobile", "13b"],
+                    help="7b (default) is the benchmark line; the others print a line for the secondary workloads")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
@@ -98,6 +222,8 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
+    if args.workload != "7b":
+        return secondary_workload(args)
     torch.cuda.set_device(0)
     shape = synth.LLAMA_7B
     bits = (4, 3, 2)

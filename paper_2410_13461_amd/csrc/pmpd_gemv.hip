@@ -38,9 +38,6 @@
 #ifndef PMPD_X_SCALAR
 #define PMPD_X_SCALAR 1  // batch-1 dot2 kernels read x through scalar loads (1) or LDS (0)
 #endif
-#ifndef PMPD_DEFAULT_MFMA
-#define PMPD_DEFAULT_MFMA 0  // which multiply-accumulate path runs when PMPD_MAC is not set
-#endif
 #ifndef PMPD_USE_SCHED_BARRIER
 #define PMPD_USE_SCHED_BARRIER 0  // pinning the schedule made the register allocator spill
 #endif
@@ -661,36 +658,7 @@ static hipError_t launch_layer_bm(const LayerDesc& d, const void* x, float* y, h
   }
 }
 
-template <int B>
-static hipError_t launch_layer_b(const LayerDesc& d, const void* x, int m, float* y, hipStream_t s) {
-  switch (m) {
-    case 1: return launch_layer_bm<B, 1>(d, x, y, s);
-#ifndef PMPD_BUILD_BATCH1_ONLY  // (working builds that only time the batch-1 kernels compile faster)
-    case 2: return launch_layer_bm<B, 2>(d, x, y, s);
-    case 3: return launch_layer_bm<B, 3>(d, x, y, s);
-    case 4: return launch_layer_bm<B, 4>(d, x, y, s);
-    case 5: return launch_layer_bm<B, 5>(d, x, y, s);
-    case 6: return launch_layer_bm<B, 6>(d, x, y, s);
-    case 7: return launch_layer_bm<B, 7>(d, x, y, s);
-    default: return launch_layer_bm<B, 8>(d, x, y, s);
-#else
-    default: return hipErrorNotSupported;
-#endif
-  }
-}
-
 // ---- MFMA variant launchers ----
-static bool use_mfma_default() {
-  // PMPD_MAC=dot2 selects the all-VALU kernels, PMPD_MAC=mfma the MFMA-assisted ones.
-  static const int choice = [] {
-    const char* e = std::getenv("PMPD_MAC");
-    if (e && std::strcmp(e, "dot2") == 0) return 0;
-    if (e && std::strcmp(e, "mfma") == 0) return 1;
-    return PMPD_DEFAULT_MFMA;
-  }();
-  return choice != 0;
-}
-
 template <int B, int SETS, int NW, int SPLITK>
 static hipError_t launch_layer_mfma(const LayerDesc& d, const void* x, int m, float* y, hipStream_t s) {
   const int tpw = NW / SPLITK;
@@ -736,16 +704,16 @@ static int32_t linear_entry(const char* who, const pmpd_layer_t* layer, int32_t 
   const LayerDesc d = make_desc(*layer, 0, 0);
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
-  if (m > PMPD_MAX_BATCH) {
+  if (m > PMPD_MAX_BATCH) {  // compute-bound shape: MFMA tile kernel
     e = launch_prefill_layer(d, b, x, m, y, s);
-  } else if (use_mfma_default()) {
+  } else if (m > 1) {  // skinny batch: unpack once, MFMA multiply-accumulate
     e = b == 4 ? launch_layer_mfma_b<4>(d, x, m, y, s)
         : b == 3 ? launch_layer_mfma_b<3>(d, x, m, y, s)
                  : launch_layer_mfma_b<2>(d, x, m, y, s);
-  } else {
-    e = b == 4 ? launch_layer_b<4>(d, x, m, y, s)
-        : b == 3 ? launch_layer_b<3>(d, x, m, y, s)
-                 : launch_layer_b<2>(d, x, m, y, s);
+  } else {  // batch 1: VALU dot2 with x in SGPRs
+    e = b == 4 ? launch_layer_bm<4, 1>(d, x, y, s)
+        : b == 3 ? launch_layer_bm<3, 1>(d, x, y, s)
+                 : launch_layer_bm<2, 1>(d, x, y, s);
   }
   if (e != hipSuccess) return hip_fail(e, who);
   return PMPD_OK;

@@ -2,22 +2,23 @@
 //
 // Mapping.  Lane l of a wave owns row 64*T + l of a row tile T; the wave walks the
 // quantisation groups g of its K-range.  Per (tile, group) the wave issues one coalesced
-// 1 KiB global_load_dwordx4 per bit-plane (16 bytes = 128 weights of one row per lane) and one
-// 256-byte load of the (scale, min) words.  The activation vector sits in LDS; all lanes read
-// the same x words (broadcast reads, no bank conflicts) because they work on the same columns.
+// 1 KiB nontemporal global_load_dwordx4 per bit-plane (16 bytes = 128 weights of one row per
+// lane) and one 256-byte load of the (scale, min) words.  All lanes work on the same columns, so
+// the activations are wave-uniform: the batch-1 kernels read them through the scalar cache into
+// SGPR operands of v_dot2_f32_f16; the batched kernels read them from LDS as MFMA operands.
 // No cross-lane reduction exists; split-K partial sums of different waves meet in LDS in a
 // fixed order, so results are run-to-run identical.
 //
 // Unpack.  The storage format places the bit of plane k for weight u = 2p + half,
 // p = 4m + 2v + h, at bit (16 half + 8 v + 4 h + 3 - k + m) mod 32.  For each m one bit-select
-// chain (v_bfi_b32, B-1 ops) merges the B plane words into a word whose 4-bit fields, after a
+// chain (v_bitop3_b32, B-1 ops) merges the B plane words into a word whose 4-bit fields, after a
 // rotate by m, are complete codes: byte v, nibble h, 16-bit half `half`.  One v_and_or_b32
 // masks the field of both halves and ORs in the fp16 exponent 0x6400, giving the pair
 // (1024 + c*q, 1024 + c*q') with c = 1 (low nibble) or 16 (high nibble) without any shift; the
 // planes that a b-bit pass does not read are simply absent from the mask, so the field holds
-// q~ = q_b * 2^(4-b).  v_dot2_f32_f16 multiplies the pair with the matching pair of x in fp32.
-// The constant 1024 and the factor 16 are removed per group with sums of x prepared once per
-// workgroup:
+// q~ = q_b * 2^(4-b).  The pair is multiplied with the matching pair of x (products exact, fp32
+// accumulation).  The constant 1024 and the factor 16 are removed per group with sums of x
+// prepared once per workgroup:
 //     sum_i W_b[r][i] x[i] = sum_g { a_g X_g + s_g ( accL + accH/16 + F_g ) }
 //     X_g = sum of x over the group, F_g = 2^(3-b) X_g - 1024 (X_g^low + X_g^high / 16)
 // where "low"/"high" are the columns whose field is the low/high nibble (i mod 4 < 2 / >= 2).
@@ -32,110 +33,43 @@
 #include "pmpd_common.hpp"
 #include "pmpd_device.hpp"
 
-#ifndef PMPD_PF
-#define PMPD_PF 1  // groups of plane words kept in flight ahead of the one being consumed
-#endif
-#ifndef PMPD_X_SCALAR
-#define PMPD_X_SCALAR 1  // batch-1 dot2 kernels read x through scalar loads (1) or LDS (0)
-#endif
-#ifndef PMPD_USE_SCHED_BARRIER
-#define PMPD_USE_SCHED_BARRIER 0  // pinning the schedule made the register allocator spill
-#endif
-#if PMPD_USE_SCHED_BARRIER
-#define PMPD_SCHED_BARRIER() __builtin_amdgcn_sched_barrier(0)
-#else
-#define PMPD_SCHED_BARRIER()
-#endif
-
 namespace pmpd {
 
-// Multiply-accumulate one group (128 columns) of the lane's row against M activation vectors.
-//   pl[k]: the lane's 16 bytes of plane k;  xs: the group's 16 uint4 of x in LDS for vector 0,
-//   vector j lies xstride uint4 further.  The unpack runs once, the dot products M times.
-template <int B, int M>
-__device__ __forceinline__ void mac_group(const UnpackConsts<B>& uc, const u32x4 (&pl)[B],
-                                          const uint4* __restrict__ xs, int xstride, float (&accL)[M],
-                                          float (&accH)[M]) {
-  const uint32_t maskL = uc.maskL, maskH = uc.maskH, magic = uc.magic;
-  float l0[M], l1[M], h0[M], h1[M];
-#pragma unroll
-  for (int j = 0; j < M; ++j) l0[j] = l1[j] = h0[j] = h1[j] = 0.f;
-  // The scheduler barriers below pin the order "LDS reads of the next step, unpack, dot
-  // products" so that the compiler cannot hoist the unpack of the whole group above the first
-  // dot product (which would keep 64 unpacked registers alive and spill).
-  if constexpr (M == 1) {
-    uint4 xc[4];
-#pragma unroll
-    for (int m = 0; m < 4; ++m) xc[m] = xs[m];
-#pragma unroll
-    for (int d = 0; d < 4; ++d) {
-      uint4 xn[4];
-      if (d < 3) {
-#pragma unroll
-        for (int m = 0; m < 4; ++m) xn[m] = xs[(d + 1) * 4 + m];
-      }
-      uint32_t p[B];
-#pragma unroll
-      for (int k = 0; k < B; ++k) p[k] = word_of(pl[k], d);
-#pragma unroll
-      for (int m = 0; m < 4; ++m) {
-        uint32_t u = merge_planes<B>(uc, p, m);
-        uint32_t w = (m == 0) ? u : __builtin_amdgcn_alignbit(u, u, m);
-        uint32_t w8 = w >> 8;
-        l0[0] = dot2(and_or(w, maskL, magic), xc[m].x, l0[0]);
-        h0[0] = dot2(and_or(w, maskH, magic), xc[m].y, h0[0]);
-        l1[0] = dot2(and_or(w8, maskL, magic), xc[m].z, l1[0]);
-        h1[0] = dot2(and_or(w8, maskH, magic), xc[m].w, h1[0]);
-      }
-      PMPD_SCHED_BARRIER();
-      if (d < 3) {
-#pragma unroll
-        for (int m = 0; m < 4; ++m) xc[m] = xn[m];
-      }
-    }
-  } else {
-#pragma unroll
-    for (int d = 0; d < 4; ++d) {
-      uint32_t p[B];
-#pragma unroll
-      for (int k = 0; k < B; ++k) p[k] = word_of(pl[k], d);
-#pragma unroll
-      for (int m = 0; m < 4; ++m) {
-        uint4 xq[M];
-#pragma unroll
-        for (int j = 0; j < M; ++j) xq[j] = xs[j * xstride + d * 4 + m];
-        uint32_t u = merge_planes<B>(uc, p, m);
-        uint32_t w = (m == 0) ? u : __builtin_amdgcn_alignbit(u, u, m);
-        uint32_t w8 = w >> 8;
-        const uint32_t r0 = and_or(w, maskL, magic), r1 = and_or(w, maskH, magic);
-        const uint32_t r2 = and_or(w8, maskL, magic), r3 = and_or(w8, maskH, magic);
-#pragma unroll
-        for (int j = 0; j < M; ++j) {
-          l0[j] = dot2(r0, xq[j].x, l0[j]);
-          h0[j] = dot2(r1, xq[j].y, h0[j]);
-          l1[j] = dot2(r2, xq[j].z, l1[j]);
-          h1[j] = dot2(r3, xq[j].w, h1[j]);
-        }
-        PMPD_SCHED_BARRIER();
-      }
-    }
-  }
-#pragma unroll
-  for (int j = 0; j < M; ++j) {
-    accL[j] = l0[j] + l1[j];
-    accH[j] = h0[j] + h1[j];
-  }
-}
+// =====================================================================================
+// Batch 1: VALU dot products, x in SGPRs.
 
-// Same as mac_group<B, 1>, but the activations come from global memory through scalar loads:
-// every lane of the wave needs the same 16 dwords of x per 32-column word, so they are SGPR
-// operands of v_dot2_f32_f16 and cost neither LDS bandwidth nor vector registers.
-//   xg: the group's 4 x 16 dwords of x (fp16 pairs in natural column order).
+// Masks and fp16 exponents for the merged words that are used without their rotate (m = 1, 2).
 template <int B>
-__device__ __forceinline__ void mac_group_sx(const UnpackConsts<B>& uc, const u32x4 (&pl)[B], const_u32x16_ptr xg,
-                                             float& accL, float& accH) {
-  const uint32_t maskL = uc.maskL, maskH = uc.maskH, magic = uc.magic;
-  float l0 = 0.f, l1 = 0.f, h0 = 0.f, h1 = 0.f;
+struct Batch1Consts {
+  uint32_t maskL[2], maskH[2], magic[2];
+  __device__ __forceinline__ Batch1Consts() {
+    constexpr uint32_t keep = (0xFu << (4 - B)) & 0xFu;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      maskL[i] = opaque_sgpr((keep * 0x00010001u) << (i + 1));
+      maskH[i] = opaque_sgpr((keep * 0x00100010u) << (i + 1));
+      magic[i] = i == 0 ? 0x60006000u : 0x5C005C00u;  // fp16 pairs (512, 512) and (256, 256)
+      asm volatile("" : "+v"(magic[i]));
+    }
+  }
+};
+
+// Offset that the pairs of merged word m carry (see mac_group_sx).
+__device__ __forceinline__ float pair_offset(int m) { return m == 1 ? 512.0f : m == 2 ? 256.0f : 1024.0f; }
+
+// Multiply-accumulate one group (128 columns) of the lane's row.
+//   pl[k]: the lane's 16 bytes of plane k;
+//   xg:    the group's 4 x 16 dwords of x (fp16 pairs in natural column order), read with
+//          s_load_dwordx16: they cost neither LDS bandwidth nor vector registers;
+//   accL:  comes in holding F_g and leaves holding F_g + sum over low-nibble pairs,
+//   accH:  sum over high-nibble pairs (to be divided by 16).
+// The merged word of m = 1, 2 is used without the rotate by m: its fields then sit m bits
+// higher, which the fp16 exponent absorbs (0x6000 = 512 has ulp 1/2, 0x5C00 = 256 has ulp 1/4),
+// so the pair still reads offset + q~ with offset 512 / 256 instead of 1024.  F_g accounts for
+// the per-m offsets (stage_group_sums).  m = 3 would put a field across bit 10 and is rotated.
+template <int B>
+__device__ __forceinline__ void mac_group_sx(const UnpackConsts<B>& uc, const Batch1Consts<B>& bc,
+                                             const u32x4 (&pl)[B], const_u32x16_ptr xg, float& accL, float& accH) {
 #pragma unroll
   for (int d = 0; d < 4; ++d) {
     const u32x16 xv = xg[d];
@@ -144,77 +78,68 @@ __device__ __forceinline__ void mac_group_sx(const UnpackConsts<B>& uc, const u3
     for (int k = 0; k < B; ++k) p[k] = word_of(pl[k], d);
 #pragma unroll
     for (int m = 0; m < 4; ++m) {
-      uint32_t u = merge_planes<B>(uc, p, m);
-      uint32_t w = (m == 0) ? u : __builtin_amdgcn_alignbit(u, u, m);
-      uint32_t w8 = w >> 8;
-      l0 = dot2(and_or(w, maskL, magic), xv[4 * m + 0], l0);
-      h0 = dot2(and_or(w, maskH, magic), xv[4 * m + 1], h0);
-      l1 = dot2(and_or(w8, maskL, magic), xv[4 * m + 2], l1);
-      h1 = dot2(and_or(w8, maskH, magic), xv[4 * m + 3], h1);
+      const uint32_t u = merge_planes<B>(uc, p, m);
+      uint32_t w, w8, mL, mH, mg;
+      if (m == 0 || m == 3) {
+        w = (m == 0) ? u : __builtin_amdgcn_alignbit(u, u, 3);
+        w8 = w >> 8;
+        mL = uc.maskL; mH = uc.maskH; mg = uc.magic;
+      } else {
+        w = u;
+        w8 = __builtin_amdgcn_alignbit(u, u, 8);  // rotate: the top field wraps into the low bits
+        mL = bc.maskL[m - 1]; mH = bc.maskH[m - 1]; mg = bc.magic[m - 1];
+      }
+      accL = dot2(and_or(w, mL, mg), xv[4 * m + 0], accL);
+      accH = dot2(and_or(w, mH, mg), xv[4 * m + 1], accH);
+      accL = dot2(and_or(w8, mL, mg), xv[4 * m + 2], accL);
+      accH = dot2(and_or(w8, mH, mg), xv[4 * m + 3], accH);
     }
   }
-  accL = l0 + l1;
-  accH = h0 + h1;
 }
 
-// LDS image of one K-chunk of the activations: for each of the M vectors `cg` groups of x as
-// fp16 (16 uint4 per group), then (X_g, F_g) per (vector, group), then M*NW*64 floats where
-// the split-K partial sums meet.
-__host__ __device__ inline size_t lds_bytes(int cg, int m, int n_waves) {
-  return static_cast<size_t>(m) * cg * (256 + 8) + static_cast<size_t>(m) * n_waves * 64 * 4;
+// LDS of a batch-1 workgroup: (X_g, F_g) per group, then NW*64 floats where the split-K partial
+// sums meet.
+__host__ __device__ inline size_t lds_bytes(int n_groups, int n_waves) {
+  return static_cast<size_t>(n_groups) * 8 + static_cast<size_t>(n_waves) * 64 * 4;
 }
 
-// Groups per K-chunk: the whole row when it fits in about 32 KiB of LDS, else as many as fit.
-__host__ __device__ inline int chunk_groups(int n_groups, int m) {
-  const int fit = (32 * 1024) / (m * 256);
-  return n_groups < fit ? n_groups : fit;
-}
-
-// Copy groups [c0, c0+cn) of the M activation vectors into LDS and prepare the per-group sums.
-template <int B, int M, int NW>
-__device__ __forceinline__ void stage_activations(const _Float16* __restrict__ x, int in_f, int c0, int cn, int cg,
-                                                  uint4* xs, float2* cs) {
-  const int n16 = cn * 16;
-#pragma unroll 1
-  for (int j = 0; j < M; ++j) {
-    const uint4* xg = reinterpret_cast<const uint4*>(x + static_cast<int64_t>(j) * in_f) + c0 * 16;
-    for (int idx = threadIdx.x; idx < n16; idx += NW * 64) {
-      const uint4 v = xg[idx];
-      xs[j * cg * 16 + idx] = v;
-      // columns 8*idx .. 8*idx+7: (0,1) low, (2,3) high, (4,5) low, (6,7) high
-      const half2_t a = __builtin_bit_cast(half2_t, v.x), b = __builtin_bit_cast(half2_t, v.y);
-      const half2_t c = __builtin_bit_cast(half2_t, v.z), e = __builtin_bit_cast(half2_t, v.w);
-      float lo = (static_cast<float>(a.x) + static_cast<float>(a.y)) + (static_cast<float>(c.x) + static_cast<float>(c.y));
-      float hi = (static_cast<float>(b.x) + static_cast<float>(b.y)) + (static_cast<float>(e.x) + static_cast<float>(e.y));
+// Per-group sums of the activation vector, computed by the whole workgroup into LDS.
+template <int B, int NW>
+__device__ __forceinline__ void stage_group_sums(const _Float16* __restrict__ x, int in_f, float2* cs) {
+  const uint4* xg = reinterpret_cast<const uint4*>(x);
+  const int n16 = in_f / 8;  // 16 uint4 per group; 16 consecutive threads share a group
+  for (int idx = threadIdx.x; idx < n16; idx += NW * 64) {
+    const uint4 v = xg[idx];
+    // columns 8*idx .. 8*idx+7: (0,1) low, (2,3) high, (4,5) low, (6,7) high
+    const half2_t a = __builtin_bit_cast(half2_t, v.x), b = __builtin_bit_cast(half2_t, v.y);
+    const half2_t c = __builtin_bit_cast(half2_t, v.z), e = __builtin_bit_cast(half2_t, v.w);
+    float lo = (static_cast<float>(a.x) + static_cast<float>(a.y)) + (static_cast<float>(c.x) + static_cast<float>(c.y));
+    float hi = (static_cast<float>(b.x) + static_cast<float>(b.y)) + (static_cast<float>(e.x) + static_cast<float>(e.y));
+    // these 8 columns belong to merged word m = idx % 4; E collects offset * (low + high/16)
+    float X = lo + hi;
+    float E = pair_offset(idx & 3) * (lo + hi * 0.0625f);
 #pragma unroll
-      for (int off = 1; off < 16; off <<= 1) {
-        lo += __shfl_xor(lo, off, 16);
-        hi += __shfl_xor(hi, off, 16);
-      }
-      if ((idx & 15) == 0) {
-        const float X = lo + hi;
-        const float F = X * (B == 4 ? 0.5f : B == 3 ? 1.0f : 2.0f) - 1024.0f * (lo + hi * 0.0625f);
-        cs[j * cg + (idx >> 4)] = make_float2(X, F);
-      }
+    for (int off = 1; off < 16; off <<= 1) {
+      X += __shfl_xor(X, off, 16);
+      E += __shfl_xor(E, off, 16);
     }
+    if ((idx & 15) == 0) cs[idx >> 4] = make_float2(X, X * (B == 4 ? 0.5f : B == 3 ? 1.0f : 2.0f) - E);
   }
 }
 
 // One workgroup: TPW = NW / SPLITK consecutive row tiles starting at tile0, each split over
-// SPLITK waves along K; K is walked in chunks of cg groups whose activations fit in LDS.
-// x: M vectors of in_f fp16, y: M vectors of out_f fp32.
-template <int B, int M, int NW, int SPLITK, int PF, bool XS>
+// SPLITK waves along K.  x: in_f fp16, y: out_f fp32.
+template <int B, int NW, int SPLITK>
 __device__ __forceinline__ void run_tiles(const LayerDesc& L, int tile0, const _Float16* __restrict__ x,
                                           float* __restrict__ y, uint4* lds) {
   static_assert(NW % SPLITK == 0, "waves must divide evenly over the K splits");
   const UnpackConsts<B> uc;
+  const Batch1Consts<B> bc;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int G = L.n_groups;
-  const int cg = chunk_groups(G, M);
-  uint4* xs = lds;
-  float2* cs = reinterpret_cast<float2*>(lds + M * cg * 16);
-  float* red = reinterpret_cast<float*>(cs + M * cg);
+  float2* cs = reinterpret_cast<float2*>(lds);
+  float* red = reinterpret_cast<float*>(cs + G);
 
   const int tile = tile0 + wave / SPLITK;
   const int ks = wave % SPLITK;
@@ -224,86 +149,58 @@ __device__ __forceinline__ void run_tiles(const LayerDesc& L, int tile0, const _
 #pragma unroll
   for (int k = 0; k < B; ++k) pp[k] = (global_u32x4_ptr)(L.plane[k]) + base;
   global_u32_ptr sp = (global_u32_ptr)(L.sa) + base;
+  const_u32x16_ptr xc = (const_u32x16_ptr)(x);
 
-  float yacc[M];
-#pragma unroll
-  for (int j = 0; j < M; ++j) yacc[j] = 0.f;
+  stage_group_sums<B, NW>(x, L.in_f, cs);
+  __syncthreads();
 
-  for (int c0 = 0; c0 < G; c0 += cg) {
-    const int cn = (G - c0 < cg) ? (G - c0) : cg;
-    if (c0) __syncthreads();  // everyone is done with the previous chunk's image
-    stage_activations<B, M, NW>(x, L.in_f, c0, cn, cg, xs, cs);
-    __syncthreads();
-    const int g0 = c0 + cn * ks / SPLITK, g1 = c0 + cn * (ks + 1) / SPLITK;
-    if (active && g0 < g1) {
-      // Weights are read exactly once per pass: nontemporal loads keep them from displacing
-      // x in the caches (measured: the same loop without arithmetic streams 6.7 TB/s with
-      // them, 5.8 TB/s without).
-      // Register ring of PF groups in flight.  Loads are unconditional with the group index
-      // clamped to the last one of the range, so the loop body is branch-free for the loads
-      // and the ring needs no register copies; the few clamped reloads hit the cache.
-      u32x4 nb[PF][B];
-      uint32_t nsa[PF];
+  float yacc = 0.f;
+  const int g0 = G * ks / SPLITK, g1 = G * (ks + 1) / SPLITK;
+  if (active && g0 < g1) {
+    // The next group's plane words are in flight while the current group is consumed.  Weights
+    // are read exactly once per pass: nontemporal loads keep them from displacing anything in
+    // the caches (measured: the same loop without arithmetic streams 6.7 TB/s with them,
+    // 5.8 TB/s without).  The last iteration reloads the last group (a cache hit) instead of
+    // branching around the loads.
+    // Two register sets A and B alternate (the loop is unrolled by two), so nothing is copied.
+    u32x4 pa[B], pb[B];
+    uint32_t sa_a, sa_b;
+    auto load = [&](u32x4 (&dst)[B], uint32_t& dsa, int g) {
+      const int gl = g < g1 ? g : g1 - 1;
 #pragma unroll
-      for (int j = 0; j < PF; ++j) {
-        const int gl = (g0 + j < g1) ? (g0 + j) : (g1 - 1);
-#pragma unroll
-        for (int k = 0; k < B; ++k) nb[j][k] = __builtin_nontemporal_load(&pp[k][gl * 64]);
-        nsa[j] = sp[gl * 64];
-      }
-      for (int g = g0; g < g1; g += PF) {
-#pragma unroll
-        for (int j = 0; j < PF; ++j) {
-          const int gc = g + j;
-          u32x4 cur[B];
-#pragma unroll
-          for (int k = 0; k < B; ++k) cur[k] = nb[j][k];
-          const uint32_t csa = nsa[j];
-          const int gl = (gc + PF < g1) ? (gc + PF) : (g1 - 1);
-#pragma unroll
-          for (int k = 0; k < B; ++k) nb[j][k] = __builtin_nontemporal_load(&pp[k][gl * 64]);
-          nsa[j] = sp[gl * 64];
-          if (gc < g1) {
-            float accL[M], accH[M];
-            if constexpr (XS && M == 1) {
-              mac_group_sx<B>(uc, cur, (const_u32x16_ptr)(x) + gc * 4, accL[0], accH[0]);
-            } else {
-              mac_group<B, M>(uc, cur, xs + (gc - c0) * 16, cg * 16, accL, accH);
-            }
-            const float s = half_bits_to_float(csa & 0xffffu);
-            const float a = half_bits_to_float(csa >> 16);
-#pragma unroll
-            for (int j2 = 0; j2 < M; ++j2) {
-              const float2 c = cs[j2 * cg + (gc - c0)];
-              const float u = fmaf(accH[j2], 0.0625f, accL[j2]) + c.y;
-              yacc[j2] = fmaf(s, u, yacc[j2]);
-              yacc[j2] = fmaf(a, c.x, yacc[j2]);
-            }
-          }
-        }
-      }
+      for (int k = 0; k < B; ++k) dst[k] = __builtin_nontemporal_load(&pp[k][gl * 64]);
+      dsa = sp[gl * 64];
+    };
+    auto consume = [&](const u32x4 (&pl)[B], uint32_t csa, int g) {
+      const float2 c = cs[g];
+      float accL = c.y, accH = 0.f;
+      mac_group_sx<B>(uc, bc, pl, xc + g * 4, accL, accH);
+      const float s = half_bits_to_float(csa & 0xffffu);
+      const float a = half_bits_to_float(csa >> 16);
+      yacc = fmaf(s, fmaf(accH, 0.0625f, accL), yacc);
+      yacc = fmaf(a, c.x, yacc);
+    };
+    load(pa, sa_a, g0);
+    for (int gc = g0; gc < g1; gc += 2) {
+      load(pb, sa_b, gc + 1);
+      consume(pa, sa_a, gc);
+      load(pa, sa_a, gc + 2);
+      if (gc + 1 < g1) consume(pb, sa_b, gc + 1);
     }
   }
   if constexpr (SPLITK > 1) {
-#pragma unroll
-    for (int j = 0; j < M; ++j) red[(j * NW + wave) * 64 + lane] = yacc[j];
+    red[wave * 64 + lane] = yacc;
     __syncthreads();
     if (ks == 0) {
+      float sum = yacc;
 #pragma unroll
-      for (int j = 0; j < M; ++j) {
-        float sum = yacc[j];
-#pragma unroll
-        for (int q = 1; q < SPLITK; ++q) sum += red[(j * NW + wave + q) * 64 + lane];
-        yacc[j] = sum;
-      }
+      for (int q = 1; q < SPLITK; ++q) sum += red[(wave + q) * 64 + lane];
+      yacc = sum;
     }
   }
   if (ks == 0 && active) {
     const int row = tile * 64 + lane;
-    if (row < L.out_f) {
-#pragma unroll
-      for (int j = 0; j < M; ++j) y[static_cast<int64_t>(j) * L.out_f + row] = yacc[j];
-    }
+    if (row < L.out_f) y[row] = yacc;
   }
 }
 
@@ -326,6 +223,13 @@ typedef float float4_t __attribute__((ext_vector_type(4)));
 
 // LDS image for the MFMA path: per vector cg groups of x (256 B each, permuted), the (X_g, F_g)
 // pairs, 256 zero bytes, then the split-K meeting point (16 B per lane, wave and accumulator set).
+// Groups per K-chunk of the batched kernels: the whole row when the m vectors fit in about
+// 32 KiB of LDS, else as many groups as fit.
+__host__ __device__ inline int chunk_groups(int n_groups, int m) {
+  const int fit = (32 * 1024) / (m * 256);
+  return n_groups < fit ? n_groups : fit;
+}
+
 constexpr int kZeroBlockVec = 20;  // 320 zero bytes: 256 read by the off-diagonal lanes, 64 of phase shift
 __host__ __device__ inline size_t lds_bytes_mfma(int cg, int m, int n_waves, int sets_times_tiles) {
   return static_cast<size_t>(m) * cg * (256 + 8) + kZeroBlockVec * 16 +
@@ -591,7 +495,7 @@ __global__ __launch_bounds__(NW * 64, 4) void pmpd_gemm_layer_mfma_kernel(LayerD
   run_tiles_mfma<B, SETS, 1, NW, SPLITK>(L, static_cast<int>(blockIdx.x) * (NW / SPLITK), x, m, y, lds);
 }
 
-template <int B, int NW, int SPLITK, int PF>
+template <int B, int NW, int SPLITK>
 __global__ __launch_bounds__(NW * 64, 4) void pmpd_gemv_stack_kernel(const LayerDesc* __restrict__ layers,
                                                                    const WorkItem* __restrict__ items,
                                                                    const _Float16* __restrict__ x_base,
@@ -599,14 +503,14 @@ __global__ __launch_bounds__(NW * 64, 4) void pmpd_gemv_stack_kernel(const Layer
   extern __shared__ uint4 lds[];
   const WorkItem it = items[blockIdx.x];
   const LayerDesc L = layers[it.layer];
-  run_tiles<B, 1, NW, SPLITK, PF, PMPD_X_SCALAR != 0>(L, it.tile0, x_base + L.x_off, y_base + L.y_off, lds);
+  run_tiles<B, NW, SPLITK>(L, it.tile0, x_base + L.x_off, y_base + L.y_off, lds);
 }
 
-template <int B, int M, int NW, int SPLITK, int PF>
+template <int B, int NW, int SPLITK>
 __global__ __launch_bounds__(NW * 64, 4) void pmpd_gemv_layer_kernel(LayerDesc L, const _Float16* __restrict__ x,
                                                                    float* __restrict__ y) {
   extern __shared__ uint4 lds[];
-  run_tiles<B, M, NW, SPLITK, PF, PMPD_X_SCALAR != 0>(L, static_cast<int>(blockIdx.x) * (NW / SPLITK), x, y, lds);
+  run_tiles<B, NW, SPLITK>(L, static_cast<int>(blockIdx.x) * (NW / SPLITK), x, y, lds);
 }
 
 // ------------------------------------------------------------------ host side ----
@@ -634,31 +538,30 @@ int32_t check_bits(int32_t b, const char* who) {
 
 // Launch shapes.  A stack has thousands of row tiles, so whole-K waves (no split) keep x
 // staging rare; a single layer has few tiles and splits K to put more waves on the machine.
-template <int B, int M, int NW, int SPLITK>
+// Launch shapes.  A stack has thousands of row tiles, so whole-K waves (no split) are enough;
+// a single layer has few tiles and splits K to put more waves on the machine.
+template <int B, int NW, int SPLITK>
 static hipError_t launch_layer(const LayerDesc& d, const void* x, float* y, hipStream_t s) {
   const int tpw = NW / SPLITK;
   const unsigned grid = static_cast<unsigned>((d.n_tiles + tpw - 1) / tpw);
-  const size_t lds = lds_bytes(chunk_groups(d.n_groups, M), M, NW);
-  hipLaunchKernelGGL((pmpd_gemv_layer_kernel<B, M, NW, SPLITK, PMPD_PF>), dim3(grid), dim3(NW * 64), lds, s, d,
+  hipLaunchKernelGGL((pmpd_gemv_layer_kernel<B, NW, SPLITK>), dim3(grid), dim3(NW * 64), lds_bytes(d.n_groups, NW), s, d,
                      static_cast<const _Float16*>(x), y);
   return hipGetLastError();
 }
 
-template <int B, int M>
-static hipError_t launch_layer_bm(const LayerDesc& d, const void* x, float* y, hipStream_t s) {
-  // Split K until about 2048 waves exist or a wave would get fewer than 4 groups of a chunk.
-  const int cg = chunk_groups(d.n_groups, M);
+template <int B>
+static hipError_t launch_layer_b(const LayerDesc& d, const void* x, float* y, hipStream_t s) {
+  // Split K until about 2048 waves exist or a wave would get fewer than 4 groups.
   int splitk = 1;
-  while (splitk < 8 && static_cast<int64_t>(d.n_tiles) * splitk < 2048 && cg / (splitk * 2) >= 4) splitk *= 2;
+  while (splitk < 8 && static_cast<int64_t>(d.n_tiles) * splitk < 2048 && d.n_groups / (splitk * 2) >= 4) splitk *= 2;
   switch (splitk) {
-    case 1: return launch_layer<B, M, 4, 1>(d, x, y, s);
-    case 2: return launch_layer<B, M, 4, 2>(d, x, y, s);
-    case 4: return launch_layer<B, M, 4, 4>(d, x, y, s);
-    default: return launch_layer<B, M, 8, 8>(d, x, y, s);
+    case 1: return launch_layer<B, 4, 1>(d, x, y, s);
+    case 2: return launch_layer<B, 4, 2>(d, x, y, s);
+    case 4: return launch_layer<B, 4, 4>(d, x, y, s);
+    default: return launch_layer<B, 8, 8>(d, x, y, s);
   }
 }
 
-// ---- MFMA variant launchers ----
 template <int B, int SETS, int NW, int SPLITK>
 static hipError_t launch_layer_mfma(const LayerDesc& d, const void* x, int m, float* y, hipStream_t s) {
   const int tpw = NW / SPLITK;
@@ -711,9 +614,9 @@ static int32_t linear_entry(const char* who, const pmpd_layer_t* layer, int32_t 
         : b == 3 ? launch_layer_mfma_b<3>(d, x, m, y, s)
                  : launch_layer_mfma_b<2>(d, x, m, y, s);
   } else {  // batch 1: VALU dot2 with x in SGPRs
-    e = b == 4 ? launch_layer_bm<4, 1>(d, x, y, s)
-        : b == 3 ? launch_layer_bm<3, 1>(d, x, y, s)
-                 : launch_layer_bm<2, 1>(d, x, y, s);
+    e = b == 4 ? launch_layer_b<4>(d, x, y, s)
+        : b == 3 ? launch_layer_b<3>(d, x, y, s)
+                 : launch_layer_b<2>(d, x, y, s);
   }
   if (e != hipSuccess) return hip_fail(e, who);
   return PMPD_OK;
@@ -742,13 +645,16 @@ static size_t stack_bytes(size_t n_layers, const size_t (&n_items)[kNumItemLists
 }
 
 // Stack kernel variants (PMPD_STACK_VARIANT="v4,v3,v2" overrides the per-bit-width defaults):
-//   0  VALU dot2, 4 waves x 1 tile, whole K         1  VALU dot2, 4 waves on 1 tile, K split 4 ways
-//   2  MFMA, 4 waves x 1 tile                       3  MFMA, 4 waves x 2 tiles
-//   4  MFMA, 2 waves x 2 tiles
-static constexpr int kNumVariants = 5;
-static constexpr int kVariantList[kNumVariants] = {0, 1, 0, 2, 0};  // which work list each variant walks
+//   0  dot2, 4 waves x 1 tile, whole K            1  dot2, 4 waves on 1 tile, K split 4 ways
+//   2  MFMA, 4 waves x 1 tile                     3  MFMA, 4 waves x 2 tiles
+//   4  MFMA, 2 waves x 2 tiles                    5  dot2, 4 waves on 2 tiles, K split 2 ways
+//   6  dot2, 8 waves on 1 tile, K split 8 ways    7  dot2, 8 waves on 2 tiles, K split 4 ways
+//   8  dot2, 8 waves on 4 tiles, K split 2 ways   9  dot2, 2 waves on 1 tile, K split 2 ways
+static constexpr int kNumVariants = 10;
+// which work list (tiles per workgroup: list 0 = 4, 1 = 1, 2 = 8, 3 = 2) each variant walks
+static constexpr int kVariantList[kNumVariants] = {0, 1, 0, 2, 0, 3, 1, 3, 0, 1};
 #ifndef PMPD_STACK_DEFAULTS
-#define PMPD_STACK_DEFAULTS {0, 0, 0}  // variants for b = 4, 3, 2
+#define PMPD_STACK_DEFAULTS {1, 1, 0}  // variants for b = 4, 3, 2 (measured best on the 7B-shaped stack)
 #endif
 
 static void pick_variants(int (&variant)[5]) {
@@ -782,14 +688,35 @@ static hipError_t launch_stack(const pmpd_stack* st, const void* xv, float* y, h
   const int q = kVariantList[v];
   const unsigned grid = static_cast<unsigned>(st->items[q].size());
   const _Float16* x = static_cast<const _Float16*>(xv);
-  const int cg = chunk_groups(st->max_in / kGroup, 1);
+  const int max_groups = st->max_in / kGroup;
+  const int cg = chunk_groups(max_groups, 1);
   switch (v) {
     case 0:
-      hipLaunchKernelGGL((pmpd_gemv_stack_kernel<B, 4, 1, PMPD_PF>), dim3(grid), dim3(256), lds_bytes(cg, 1, 4), s,
+      hipLaunchKernelGGL((pmpd_gemv_stack_kernel<B, 4, 1>), dim3(grid), dim3(256), lds_bytes(max_groups, 4), s,
                          st->d_layers, st->d_items[q], x, y);
       break;
     case 1:
-      hipLaunchKernelGGL((pmpd_gemv_stack_kernel<B, 4, 4, PMPD_PF>), dim3(grid), dim3(256), lds_bytes(cg, 1, 4), s,
+      hipLaunchKernelGGL((pmpd_gemv_stack_kernel<B, 4, 4>), dim3(grid), dim3(256), lds_bytes(max_groups, 4), s,
+                         st->d_layers, st->d_items[q], x, y);
+      break;
+    case 5:
+      hipLaunchKernelGGL((pmpd_gemv_stack_kernel<B, 4, 2>), dim3(grid), dim3(256), lds_bytes(max_groups, 4), s,
+                         st->d_layers, st->d_items[q], x, y);
+      break;
+    case 6:
+      hipLaunchKernelGGL((pmpd_gemv_stack_kernel<B, 8, 8>), dim3(grid), dim3(512), lds_bytes(max_groups, 8), s,
+                         st->d_layers, st->d_items[q], x, y);
+      break;
+    case 7:
+      hipLaunchKernelGGL((pmpd_gemv_stack_kernel<B, 8, 4>), dim3(grid), dim3(512), lds_bytes(max_groups, 8), s,
+                         st->d_layers, st->d_items[q], x, y);
+      break;
+    case 8:
+      hipLaunchKernelGGL((pmpd_gemv_stack_kernel<B, 8, 2>), dim3(grid), dim3(512), lds_bytes(max_groups, 8), s,
+                         st->d_layers, st->d_items[q], x, y);
+      break;
+    case 9:
+      hipLaunchKernelGGL((pmpd_gemv_stack_kernel<B, 2, 2>), dim3(grid), dim3(128), lds_bytes(max_groups, 2), s,
                          st->d_layers, st->d_items[q], x, y);
       break;
     case 2:

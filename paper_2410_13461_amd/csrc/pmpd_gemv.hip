@@ -33,6 +33,13 @@
 #include "pmpd_common.hpp"
 #include "pmpd_device.hpp"
 
+#ifndef PMPD_BATCH_WIDE_WAVES
+#define PMPD_BATCH_WIDE_WAVES 3  // waves per SIMD the 8-vector, 2-tile kernel is compiled for (168 VGPRs, no spills)
+#endif
+#ifndef PMPD_BATCH_TILES
+#define PMPD_BATCH_TILES 2  // row tiles per wave in the skinny-batch stack kernel
+#endif
+
 namespace pmpd {
 
 // =====================================================================================
@@ -151,26 +158,31 @@ __device__ __forceinline__ void run_tiles(const LayerDesc& L, int tile0, const _
   global_u32_ptr sp = (global_u32_ptr)(L.sa) + base;
   const_u32x16_ptr xc = (const_u32x16_ptr)(x);
 
+  float yacc = 0.f;
+  const int g0 = G * ks / SPLITK, g1 = G * (ks + 1) / SPLITK;
+  const bool work = active && g0 < g1;
+  // The next group's plane words are in flight while the current group is consumed.  Weights
+  // are read exactly once per pass: nontemporal loads keep them from displacing anything in
+  // the caches (measured: the same loop without arithmetic streams 6.7 TB/s with them,
+  // 5.8 TB/s without).  Past the end of the range the last group is reloaded (a cache hit)
+  // instead of branching around the loads.  Two register sets A and B alternate (the loop is
+  // unrolled by two), so nothing is copied.
+  u32x4 pa[B], pb[B];
+  uint32_t sa_a = 0, sa_b = 0;
+  auto load = [&](u32x4 (&dst)[B], uint32_t& dsa, int g) {
+    const int gl = g < g1 ? g : g1 - 1;
+#pragma unroll
+    for (int k = 0; k < B; ++k) dst[k] = __builtin_nontemporal_load(&pp[k][gl * 64]);
+    dsa = sp[gl * 64];
+  };
+  // The first group's loads do not depend on the group sums: issue them before the workgroup
+  // computes the sums, so that their latency overlaps the staging and the barrier.
+  if (work) load(pa, sa_a, g0);
+
   stage_group_sums<B, NW>(x, L.in_f, cs);
   __syncthreads();
 
-  float yacc = 0.f;
-  const int g0 = G * ks / SPLITK, g1 = G * (ks + 1) / SPLITK;
-  if (active && g0 < g1) {
-    // The next group's plane words are in flight while the current group is consumed.  Weights
-    // are read exactly once per pass: nontemporal loads keep them from displacing anything in
-    // the caches (measured: the same loop without arithmetic streams 6.7 TB/s with them,
-    // 5.8 TB/s without).  The last iteration reloads the last group (a cache hit) instead of
-    // branching around the loads.
-    // Two register sets A and B alternate (the loop is unrolled by two), so nothing is copied.
-    u32x4 pa[B], pb[B];
-    uint32_t sa_a, sa_b;
-    auto load = [&](u32x4 (&dst)[B], uint32_t& dsa, int g) {
-      const int gl = g < g1 ? g : g1 - 1;
-#pragma unroll
-      for (int k = 0; k < B; ++k) dst[k] = __builtin_nontemporal_load(&pp[k][gl * 64]);
-      dsa = sp[gl * 64];
-    };
+  if (work) {
     auto consume = [&](const u32x4 (&pl)[B], uint32_t csa, int g) {
       const float2 c = cs[g];
       float accL = c.y, accH = 0.f;
@@ -180,7 +192,6 @@ __device__ __forceinline__ void run_tiles(const LayerDesc& L, int tile0, const _
       yacc = fmaf(s, fmaf(accH, 0.0625f, accL), yacc);
       yacc = fmaf(a, c.x, yacc);
     };
-    load(pa, sa_a, g0);
     for (int gc = g0; gc < g1; gc += 2) {
       load(pb, sa_b, gc + 1);
       consume(pa, sa_a, gc);
@@ -232,7 +243,7 @@ __host__ __device__ inline int chunk_groups(int n_groups, int m) {
 
 constexpr int kZeroBlockVec = 20;  // 320 zero bytes: 256 read by the off-diagonal lanes, 64 of phase shift
 __host__ __device__ inline size_t lds_bytes_mfma(int cg, int m, int n_waves, int sets_times_tiles) {
-  return static_cast<size_t>(m) * cg * (256 + 8) + kZeroBlockVec * 16 +
+  return static_cast<size_t>(m) * cg * 256 + static_cast<size_t>((m * cg + 1) & ~1) * 8 + kZeroBlockVec * 16 +
          static_cast<size_t>(sets_times_tiles) * n_waves * 64 * 16;
 }
 
@@ -292,7 +303,7 @@ __device__ __forceinline__ void run_tiles_mfma(const LayerDesc& L, int tile0, co
   const int cg = chunk_groups(G, m);
   uint32_t* xs = reinterpret_cast<uint32_t*>(lds);
   float2* cs = reinterpret_cast<float2*>(xs + m * cg * 64);
-  uint4* zeros = reinterpret_cast<uint4*>(cs + m * cg);
+  uint4* zeros = reinterpret_cast<uint4*>(cs + ((m * cg + 1) & ~1));  // keep 16-byte alignment
   float4_t* red = reinterpret_cast<float4_t*>(zeros + kZeroBlockVec);
 
   const int tile_first = tile0 + (wave / SPLITK) * T;
@@ -476,15 +487,15 @@ __global__ __launch_bounds__(NW * 64, 4) void pmpd_gemv_stack_mfma_kernel(const 
   run_tiles_mfma<B, 1, T, NW, SPLITK>(L, it.tile0, x_base + L.x_off, 1, y_base + L.y_off, lds);
 }
 
-template <int B, int SETS, int NW>
-__global__ __launch_bounds__(NW * 64, 4) void pmpd_gemm_stack_mfma_kernel(const LayerDesc* __restrict__ layers,
+template <int B, int SETS, int T, int NW>
+__global__ __launch_bounds__(NW * 64, (SETS * T > 2 ? PMPD_BATCH_WIDE_WAVES : 4)) void pmpd_gemm_stack_mfma_kernel(const LayerDesc* __restrict__ layers,
                                                                           const WorkItem* __restrict__ items,
                                                                           const _Float16* __restrict__ x_base, int m,
                                                                           float* __restrict__ y_base) {
   extern __shared__ uint4 lds[];
   const WorkItem it = items[blockIdx.x];
   const LayerDesc L = layers[it.layer];
-  run_tiles_mfma<B, SETS, 1, NW, 1>(L, it.tile0, x_base + static_cast<int64_t>(m) * L.x_off, m,
+  run_tiles_mfma<B, SETS, T, NW, 1>(L, it.tile0, x_base + static_cast<int64_t>(m) * L.x_off, m,
                                     y_base + static_cast<int64_t>(m) * L.y_off, lds);
 }
 
@@ -737,15 +748,17 @@ static hipError_t launch_stack(const pmpd_stack* st, const void* xv, float* y, h
 
 template <int B>
 static hipError_t launch_stack_batch(const pmpd_stack* st, const void* xv, int m, float* y, hipStream_t s) {
-  const unsigned grid = static_cast<unsigned>(st->items[0].size());
+  constexpr int T = PMPD_BATCH_TILES;
+  const int q = T == 2 ? 2 : 0;  // work list with 4*T tiles per workgroup
+  const unsigned grid = static_cast<unsigned>(st->items[q].size());
   const _Float16* x = static_cast<const _Float16*>(xv);
   const int cg = chunk_groups(st->max_in / kGroup, m);
   if (m <= 4) {
-    hipLaunchKernelGGL((pmpd_gemm_stack_mfma_kernel<B, 1, 4>), dim3(grid), dim3(256), lds_bytes_mfma(cg, m, 4, 1), s,
-                       st->d_layers, st->d_items[0], x, m, y);
+    hipLaunchKernelGGL((pmpd_gemm_stack_mfma_kernel<B, 1, T, 4>), dim3(grid), dim3(256), lds_bytes_mfma(cg, m, 4, T), s,
+                       st->d_layers, st->d_items[q], x, m, y);
   } else {
-    hipLaunchKernelGGL((pmpd_gemm_stack_mfma_kernel<B, 2, 4>), dim3(grid), dim3(256), lds_bytes_mfma(cg, m, 4, 2), s,
-                       st->d_layers, st->d_items[0], x, m, y);
+    hipLaunchKernelGGL((pmpd_gemm_stack_mfma_kernel<B, 2, T, 4>), dim3(grid), dim3(256), lds_bytes_mfma(cg, m, 4, 2 * T), s,
+                       st->d_layers, st->d_items[q], x, m, y);
   }
   return hipGetLastError();
 }

@@ -260,6 +260,30 @@ def test_decode_step_matches_oracle_and_single_layer_calls(pmpd, b):
     stack.close()
 
 
+@pytest.mark.parametrize("variant", list(range(10)))
+def test_every_stack_kernel_variant_matches_oracle(pmpd, variant, monkeypatch):
+    """Each launch shape / multiply-accumulate variant of the one-launch decode step (selected per
+    bit-width by default, forced here through PMPD_STACK_VARIANT) gives the same answers."""
+    import torch
+
+    _say(f"[decode_step variant] {variant}")
+    monkeypatch.setenv("PMPD_STACK_VARIANT", f"{variant},{variant},{variant}")
+    shape, layers, raw = _small_stack(pmpd, seed=10)
+    stack = pmpd.Stack(layers)  # the variant is picked when the stack is created
+    xs = [synth.draw_x(10, 0, blk, pi, i)[0] for (blk, pi, nm, o, i) in shape.layers()]
+    x = torch.from_numpy(np.concatenate(xs)).cuda()
+    for b in (4, 3, 2):
+        y = torch.full((stack.y_elems,), float("nan"), dtype=torch.float32, device="cuda")
+        pmpd.decode_step(stack, b, x, y)
+        torch.cuda.synchronize()
+        yh = y.cpu().numpy()
+        for li, (q4, s, a) in enumerate(raw):
+            o = stack.y_offsets[li]
+            y_ref, t = oracle.linear(q4, s, a, b, xs[li])
+            assert_parity(yh[o:o + q4.shape[0]], y_ref[0], t[0], f"variant {variant} layer {li} b={b}")
+    stack.close()
+
+
 def test_decode_run_follows_the_schedule(pmpd):
     import torch
 

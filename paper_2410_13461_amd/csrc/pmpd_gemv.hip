@@ -36,9 +36,6 @@
 #ifndef PMPD_BATCH_WIDE_WAVES
 #define PMPD_BATCH_WIDE_WAVES 3  // waves per SIMD the 8-vector, 2-tile kernel is compiled for (168 VGPRs, no spills)
 #endif
-#ifndef PMPD_BATCH_TILES
-#define PMPD_BATCH_TILES 2  // row tiles per wave in the skinny-batch stack kernel
-#endif
 
 namespace pmpd {
 
@@ -664,21 +661,20 @@ static size_t stack_bytes(size_t n_layers, const size_t (&n_items)[kNumItemLists
 static constexpr int kNumVariants = 10;
 // which work list (tiles per workgroup: list 0 = 4, 1 = 1, 2 = 8, 3 = 2) each variant walks
 static constexpr int kVariantList[kNumVariants] = {0, 1, 0, 2, 0, 3, 1, 3, 0, 1};
-#ifndef PMPD_STACK_DEFAULTS
-#define PMPD_STACK_DEFAULTS {1, 1, 0}  // variants for b = 4, 3, 2 (measured best on the 7B-shaped stack)
-#endif
-
-static void pick_variants(int (&variant)[5]) {
-  const int defaults[3] = PMPD_STACK_DEFAULTS;
-  variant[4] = defaults[0];
-  variant[3] = defaults[1];
-  variant[2] = defaults[2];
+// Defaults measured on the 7B-shaped and the mobile-scale stacks: at b = 4 and 3 the kernel is
+// bound by the memory system and four waves that split one tile's K stream fastest; at b = 2 the
+// VALU co-limits, so the per-workgroup staging is spread over more rows (4 tiles per workgroup)
+// when the stack has enough tiles to keep every CU busy that way, else over 2.
+static void pick_variants(pmpd_stack* st) {
+  st->variant[4] = 1;
+  st->variant[3] = 1;
+  st->variant[2] = st->items[0].size() >= 4096 ? 0 : 5;
   const char* e = std::getenv("PMPD_STACK_VARIANT");
   if (e) {
     int v[3];
     if (std::sscanf(e, "%d,%d,%d", &v[0], &v[1], &v[2]) == 3) {
       for (int i = 0; i < 3; ++i)
-        if (v[i] >= 0 && v[i] < kNumVariants) variant[4 - i] = v[i];
+        if (v[i] >= 0 && v[i] < kNumVariants) st->variant[4 - i] = v[i];
     }
   }
 }
@@ -746,12 +742,10 @@ static hipError_t launch_stack(const pmpd_stack* st, const void* xv, float* y, h
   return hipGetLastError();
 }
 
-template <int B>
-static hipError_t launch_stack_batch(const pmpd_stack* st, const void* xv, int m, float* y, hipStream_t s) {
-  constexpr int T = PMPD_BATCH_TILES;
+template <int B, int T>
+static hipError_t launch_stack_batch_t(const pmpd_stack* st, const _Float16* x, int m, float* y, hipStream_t s) {
   const int q = T == 2 ? 2 : 0;  // work list with 4*T tiles per workgroup
   const unsigned grid = static_cast<unsigned>(st->items[q].size());
-  const _Float16* x = static_cast<const _Float16*>(xv);
   const int cg = chunk_groups(st->max_in / kGroup, m);
   if (m <= 4) {
     hipLaunchKernelGGL((pmpd_gemm_stack_mfma_kernel<B, 1, T, 4>), dim3(grid), dim3(256), lds_bytes_mfma(cg, m, 4, T), s,
@@ -761,6 +755,16 @@ static hipError_t launch_stack_batch(const pmpd_stack* st, const void* xv, int m
                        st->d_layers, st->d_items[q], x, m, y);
   }
   return hipGetLastError();
+}
+
+// Two row tiles per wave halve the LDS operand traffic per weight.  With more than 4 vectors
+// (two accumulator sets) that always pays; with up to 4 it only pays when the stack has enough
+// tiles to fill the machine with 8-tile workgroups (measured on the 7B and mobile-scale stacks).
+template <int B>
+static hipError_t launch_stack_batch(const pmpd_stack* st, const void* xv, int m, float* y, hipStream_t s) {
+  const _Float16* x = static_cast<const _Float16*>(xv);
+  const bool two_tiles = m > 4 || st->items[2].size() >= 2048;
+  return two_tiles ? launch_stack_batch_t<B, 2>(st, x, m, y, s) : launch_stack_batch_t<B, 1>(st, x, m, y, s);
 }
 
 extern "C" {
@@ -825,7 +829,7 @@ int32_t pmpd_stack_create(const pmpd_layer_t* layers, int32_t n, const int64_t* 
     delete st;
     return hip_fail(e, "pmpd_stack_create copy");
   }
-  pick_variants(st->variant);
+  pick_variants(st);
   *out = st;
   return PMPD_OK;
 }

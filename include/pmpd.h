@@ -30,13 +30,19 @@
  *     the GPU fails with PMPD_EHIP when none is usable.
  *
  * Storage format ("tile-plane"), shared by pack, unpack and the kernels:
- *   rows padded to a multiple of 64; row r -> tile T = r/64, lane l = r%64;
- *   feature i -> group g = i/128, word d = (i%128)/32, u = i%32 = 2*p + half,
- *   p = 4*m + 2*v + h (m 0..3, v 0..1, h 0..1); G = in_features/128.
- *   plane k: uint32 words, weight (r,i) is bit (16*half + 8*v + 4*h + 3 - k + m) mod 32
- *            of word ((T*G + g)*64 + l)*4 + d        -> plane_bytes = padded_rows*in/8
- *   scale_min: uint32 word (T*G + g)*64 + l = fp16 scale (low half) | fp16 min (high half)
- *   A wave of 64 lanes reads one contiguous 1 KiB chunk per (tile, group, plane).
+ *   rows padded to a multiple of 64; row r -> tile T = r/64, position rr = r%64 = 16*t + j
+ *   (t 0..3, j 0..15); feature i -> group g = i/128, position e = i%128 = 32*kb + 8*v + c
+ *   (kb 0..3, v 0..3, c 0..7); n = c/2 + 4*(c%2); G = in_features/128.
+ *   plane k: uint32 words; weight (r,i) is bit
+ *              4n+1, 4n+3, 4n, 4n+2            for v = 0..3 when k is 0 or 2
+ *              4n, 4n+2, (4n+31) mod 32, 4n+1  for v = 0..3 when k is 1 or 3
+ *            of word ((T*G + g)*64 + 16*kb + j)*4 + t      -> plane_bytes = padded_rows*in/8
+ *   scale_min: uint32 word (T*G + g)*64 + 4*j + t = fp16 scale (low half) | fp16 min (high half)
+ *   A wave of 64 lanes reads one contiguous 1 KiB chunk per (tile, group, plane): lane 16*kb + j
+ *   gets, in word t, 32 columns of row 16*t + j.  Merging the words of planes (0,1) and of planes
+ *   (2,3) with one bit-select and a mask gives words of eight nibbles 00pp' (the two bits of a
+ *   pair): operands of the gfx950 fp4 matrix instruction as they stand, and two shifts away from
+ *   4-bit codes for the fp16 path.
  */
 #ifndef PMPD_H_
 #define PMPD_H_
@@ -99,7 +105,8 @@ int32_t pmpd_unpack(const pmpd_layer_t* host_layer, int32_t b, uint8_t* qb_out);
 int32_t pmpd_gemv(const pmpd_layer_t* layer, int32_t b, const void* x, float* y, void* stream);
 
 /* Y[j][r] = sum_i W_b[r][i] X[j][i] for 1 <= m <= PMPD_MAX_ROWS.
- * m <= PMPD_MAX_BATCH: skinny path, the weights are read once and the codes stay exact.
+ * m <= PMPD_MAX_BATCH: memory-bound path (the one pmpd_gemv takes), the weights are read once and
+ *   codes and activations enter the matrix cores exactly (fp32 accumulation).
  * m >  PMPD_MAX_BATCH: the compute-bound prefill shape (Section 4.1: prefill runs at its own,
  *   higher precision of the same store): the weights are dequantised to fp16 (one rounding) and
  *   the contraction runs on the matrix cores with fp32 accumulation.

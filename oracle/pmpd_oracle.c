@@ -19,15 +19,18 @@
  * Everything is plain loops in fp64: every product a + s*k*(q+0.5) is exact in
  * fp64 because s and a are fp16 values and k*(q+0.5) is a small dyadic number.
  *
- * Storage format ("tile-plane"):
- *   rows are padded to a multiple of 64; row r lives in tile T = r / 64, lane l = r % 64;
- *   input feature i lives in group g = i / 128, 32-bit word d = (i % 128) / 32, and
- *   u = i % 32 is split as  u = 2*p + half,  p = 4*m + 2*v + h   (m 0..3, v 0..1, h 0..1).
- *   Plane k (k = 0 is the most significant bit of the 4-bit code) is an array of
- *   32-bit words; the bit of weight (r, i) is bit
- *        pos = (16*half + 8*v + 4*h + 3 - k + m) mod 32
- *   of word  ((T*G + g)*64 + l)*4 + d,   G = in / 128.
- *   Scale and minimum are one 32-bit word per (row, group) at index (T*G + g)*64 + l:
+ * Storage format ("tile-plane"), an interface between pack and the kernels (the paper
+ * fixes none; each side implements this index formula on its own):
+ *   rows are padded to a multiple of 64; row r lives in tile T = r / 64 at position
+ *   rr = r % 64 = 16*t + j  (t 0..3, j 0..15);
+ *   input feature i lives in group g = i / 128 at position e = i % 128 = 32*kb + 8*v + c
+ *   (kb 0..3, v 0..3, c 0..7), and n = c/2 + 4*(c%2) is the nibble of column c.
+ *   Plane k (k = 0 is the most significant bit of the 4-bit code) is an array of 32-bit
+ *   words; the bit of weight (r, i) is bit
+ *        4*n + 1, 4*n + 3, 4*n, 4*n + 2            for v = 0, 1, 2, 3   (k = 0 or 2)
+ *        4*n, 4*n + 2, (4*n + 31) mod 32, 4*n + 1   for v = 0, 1, 2, 3   (k = 1 or 3)
+ *   of word  ((T*G + g)*64 + 16*kb + j)*4 + t,   G = in / 128.
+ *   Scale and minimum are one 32-bit word per (row, group) at index (T*G + g)*64 + 4*j + t:
  *   low 16 bits = fp16 scale, high 16 bits = fp16 minimum.
  *   A b-bit pass reads planes 0..b-1 only.
  */
@@ -66,16 +69,40 @@ static int64_t orc_padded_rows(int64_t out_f) { return (out_f + ORC_TILE - 1) / 
 int64_t orc_plane_words(int64_t out_f, int64_t in_f) { return orc_padded_rows(out_f) * (in_f / 32); }
 int64_t orc_sa_words(int64_t out_f, int64_t in_f) { return orc_padded_rows(out_f) * (in_f / ORC_GROUP); }
 
+static int64_t orc_sa_index(int64_t r, int64_t g, int64_t G) {
+  int64_t T = r / ORC_TILE;
+  int rr = (int)(r % ORC_TILE);
+  int t = rr / 16, j = rr % 16;
+  return (T * G + g) * ORC_TILE + 4 * j + t;
+}
+
 static void orc_locate(int64_t r, int64_t i, int k, int64_t in_f, int64_t* word, int* pos) {
   int64_t G = in_f / ORC_GROUP;
-  int64_t T = r / ORC_TILE, l = r % ORC_TILE;
+  int64_t T = r / ORC_TILE;
+  int rr = (int)(r % ORC_TILE);
+  int t = rr / 16, j = rr % 16;
   int64_t g = i / ORC_GROUP;
   int e = (int)(i % ORC_GROUP);
-  int d = e / 32, u = e % 32;
-  int half = u % 2, p = u / 2;
-  int m = p / 4, v = (p / 2) % 2, h = p % 2;
-  *word = ((T * G + g) * ORC_TILE + l) * 4 + d;
-  *pos = ((16 * half + 8 * v + 4 * h + 3 - k + m) % 32 + 32) % 32;
+  int kb = e / 32, v = (e % 32) / 8, c = e % 8;
+  int n = c / 2 + 4 * (c % 2);
+  int bit;
+  if (k % 2 == 0) {
+    switch (v) {
+      case 0: bit = 4 * n + 1; break;
+      case 1: bit = 4 * n + 3; break;
+      case 2: bit = 4 * n; break;
+      default: bit = 4 * n + 2; break;
+    }
+  } else {
+    switch (v) {
+      case 0: bit = 4 * n; break;
+      case 1: bit = 4 * n + 2; break;
+      case 2: bit = (4 * n + 31) % 32; break;
+      default: bit = 4 * n + 1; break;
+    }
+  }
+  *word = ((T * G + g) * ORC_TILE + 16 * kb + j) * 4 + t;
+  *pos = bit;
 }
 
 /* ---- pack: 4-bit codes -> 4 bit-planes + (scale, min) words --------------- */
@@ -99,10 +126,8 @@ int orc_pack(const uint8_t* q4, const uint16_t* s, const uint16_t* a, int64_t ou
         if (bit) planes[k][w] |= (uint32_t)1 << pos;
       }
     }
-    for (int64_t g = 0; g < G; ++g) {
-      int64_t T = r / ORC_TILE, l = r % ORC_TILE;
-      sa[(T * G + g) * ORC_TILE + l] = (uint32_t)s[r * G + g] | ((uint32_t)a[r * G + g] << 16);
-    }
+    for (int64_t g = 0; g < G; ++g)
+      sa[orc_sa_index(r, g, G)] = (uint32_t)s[r * G + g] | ((uint32_t)a[r * G + g] << 16);
   }
   return 0;
 }
@@ -130,7 +155,7 @@ void orc_unpack_sa(const uint32_t* sa, int64_t out_f, int64_t in_f, uint16_t* s,
   int64_t G = in_f / ORC_GROUP;
   for (int64_t r = 0; r < out_f; ++r)
     for (int64_t g = 0; g < G; ++g) {
-      uint32_t w = sa[((r / ORC_TILE) * G + g) * ORC_TILE + (r % ORC_TILE)];
+      uint32_t w = sa[orc_sa_index(r, g, G)];
       s[r * G + g] = (uint16_t)(w & 0xffffu);
       a[r * G + g] = (uint16_t)(w >> 16);
     }
@@ -197,7 +222,7 @@ int orc_linear_packed(const uint32_t* plane0, const uint32_t* plane1, const uint
       double acc = 0.0, tb = 0.0;
       for (int64_t i = 0; i < in_f; ++i) {
         int64_t g = i / ORC_GROUP;
-        uint32_t w32 = sa[((r / ORC_TILE) * G + g) * ORC_TILE + (r % ORC_TILE)];
+        uint32_t w32 = sa[orc_sa_index(r, g, G)];
         double sv = orc_half_to_double((uint16_t)(w32 & 0xffffu));
         double av = orc_half_to_double((uint16_t)(w32 >> 16));
         int code = 0;

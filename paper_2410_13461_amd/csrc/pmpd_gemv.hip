@@ -1,27 +1,54 @@
-// HIP kernels (gfx950, wave64) and launchers for the PMPD decode linear layers.
+// HIP kernels (gfx950, wave64) and launchers for the PMPD decode linear layers (batch 1..8).
 //
-// Mapping.  Lane l of a wave owns row 64*T + l of a row tile T; the wave walks the
-// quantisation groups g of its K-range.  Per (tile, group) the wave issues one coalesced
-// 1 KiB nontemporal global_load_dwordx4 per bit-plane (16 bytes = 128 weights of one row per
-// lane) and one 256-byte load of the (scale, min) words.  All lanes work on the same columns, so
-// the activations are wave-uniform: the batch-1 kernels read them through the scalar cache into
-// SGPR operands of v_dot2_f32_f16; the batched kernels read them from LDS as MFMA operands.
-// No cross-lane reduction exists; split-K partial sums of different waves meet in LDS in a
-// fixed order, so results are run-to-run identical.
+// The multiply-accumulate runs on the scaled fp8 x fp4 matrix instruction
+// v_mfma_scale_f32_16x16x128_f8f6f4; the VALU only interleaves and masks plane bits.
 //
-// Unpack.  The storage format places the bit of plane k for weight u = 2p + half,
-// p = 4m + 2v + h, at bit (16 half + 8 v + 4 h + 3 - k + m) mod 32.  For each m one bit-select
-// chain (v_bitop3_b32, B-1 ops) merges the B plane words into a word whose 4-bit fields, after a
-// rotate by m, are complete codes: byte v, nibble h, 16-bit half `half`.  One v_and_or_b32
-// masks the field of both halves and ORs in the fp16 exponent 0x6400, giving the pair
-// (1024 + c*q, 1024 + c*q') with c = 1 (low nibble) or 16 (high nibble) without any shift; the
-// planes that a b-bit pass does not read are simply absent from the mask, so the field holds
-// q~ = q_b * 2^(4-b).  The pair is multiplied with the matching pair of x (products exact, fp32
-// accumulation).  The constant 1024 and the factor 16 are removed per group with sums of x
-// prepared once per workgroup:
-//     sum_i W_b[r][i] x[i] = sum_g { a_g X_g + s_g ( accL + accH/16 + F_g ) }
-//     X_g = sum of x over the group, F_g = 2^(3-b) X_g - 1024 (X_g^low + X_g^high / 16)
-// where "low"/"high" are the columns whose field is the low/high nibble (i mod 4 < 2 / >= 2).
+// Weights.  A 2-bit pair of code bits (p, p') in the two low bits of a nibble IS the fp4 (e2m1)
+// number p + p'/2, so the merged plane words (pair_words) are an fp4 operand as they stand.  The
+// 4-bit aligned code is q~ = q_b 2^(4-b) = 8 (p0 + p1/2) + 2 (p2 + p3/2): one MFMA per pair, the
+// factors 8 and 2 ride on the block scale of the weight operand.  A b-bit pass leaves out the
+// planes it does not read (b = 3: the lower pair becomes the single bit p2; b = 2: no lower pair).
+//
+// Activations.  The other operand is fp8 (e4m3).  Each fp16 x is split exactly into three pieces
+//     x = 2^e0 m0 + 2^(e0-4) m1 + 2^(e0-8) m2,   m0, m1, m2 in e4m3,
+// with one exponent e0 per 32 columns, applied by the instruction as the block scale of the
+// activation operand.  (m0 = x / 2^e0 rounded to 4 significant bits; the residual is an fp16 number
+// with at most 7 significant bits, and so on.)  The pieces sit in rows of the 16-row operand, so
+// one MFMA multiplies 16 weight rows x 128 columns with all three pieces and the lane adds the
+// three partial sums.
+//
+// Magnitude classes.  The instruction sums the 32 products of one scale block in a fixed-point
+// window of 14 bits below the leading bit of the block's largest product (measured: smaller bits
+// are dropped; different blocks and the C input are added exactly).  A product here has 6
+// significant bits, so the sum is exact when the elements of a block span at most 8 binades.
+// Each 32-column block of x is therefore split into two vectors with disjoint support: class A
+// holds the elements within 8 binades of the block's largest magnitude, class B the rest, scaled
+// by its own largest magnitude.  Elements more than 16 binades below their block's largest lose
+// their low bits (below 2^-21 of the largest product of the block).  The split is done once per
+// workgroup and K-chunk while the first weight loads are in flight.
+//
+// Rows of the activation operand.  The 16 rows are four slots of four rows; slot q carries the
+// three pieces of one class of one vector in rows 4 q .. 4 q + 2 (row 4 q + 3 is not used): slot
+// 2 v + c of operand set s holds class c of vector 2 s + v.  Batch 1 fills two slots of one set,
+// a batch of m vectors fills 2 m slots of ceil(m / 2) sets; the weights are read and unpacked once
+// for all of them.
+//
+// Operand geometry (checked on gfx950): the fp8 operand's lane i + 16 kb holds row i, columns
+// 16 kb .. 16 kb + 15 and 64 + 16 kb .. 64 + 16 kb + 15; the scale of its columns 32 c .. 32 c + 31
+// is byte 0 of the scale register of lane i + 16 c.  The fp4 operand's lane j + 16 kb holds
+// column j (= weight row j of the 16-row block) for K = 32 kb .. 32 kb + 31, eight nibbles per
+// register.  D[i][j] sits in lane j + 16 (i / 4), register i % 4.
+//
+// D[i][j] sits in lane j + 16 (i / 4), register i % 4: lane l receives, from the MFMA over weight
+// rows 16 t .. 16 t + 15 of the tile, the three partial sums of slot l / 16 and weight row
+// 16 t + l % 16.  It scales them with that row's (scale, min) word, which it loaded itself (the
+// words of a (tile, group) are stored in the order [l % 16][t], 16 bytes per lane), and the two
+// classes of a vector, 16 lanes apart, are added once at the end.
+//
+// Per group (128 columns), row and class:  sum_i W_b x = s_g (D + 2^(3-b) X_g) + a_g X_g,
+// D = sum q~ x, X_g = sum of the class's x over the group: scale and minimum are applied once per
+// 128 weights.
+// No atomics and a fixed summation order: results are run-to-run identical.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -34,491 +61,375 @@
 #include "pmpd_device.hpp"
 
 #ifndef PMPD_BATCH_WIDE_WAVES
-#define PMPD_BATCH_WIDE_WAVES 3  // waves per SIMD the 8-vector, 2-tile kernel is compiled for (168 VGPRs, no spills)
+#define PMPD_BATCH_WIDE_WAVES 3  // waves per SIMD the kernels for 5..8 vectors are compiled for
 #endif
 
 namespace pmpd {
 
-// =====================================================================================
-// Batch 1: VALU dot products, x in SGPRs.
+typedef short short2_t __attribute__((ext_vector_type(2)));
+typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
 
-// Masks and fp16 exponents for the merged words that are used without their rotate (m = 1, 2).
-template <int B>
-struct Batch1Consts {
-  uint32_t maskL[2], maskH[2], magic[2];
-  __device__ __forceinline__ Batch1Consts() {
-    constexpr uint32_t keep = (0xFu << (4 - B)) & 0xFu;
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      maskL[i] = opaque_sgpr((keep * 0x00010001u) << (i + 1));
-      maskH[i] = opaque_sgpr((keep * 0x00100010u) << (i + 1));
-      magic[i] = i == 0 ? 0x60006000u : 0x5C005C00u;  // fp16 pairs (512, 512) and (256, 256)
-      asm volatile("" : "+v"(magic[i]));
-    }
+// LDS image of the split activations, per vector and group: for each of the two magnitude
+// classes 3 pieces x 128 fp8 in operand order and 16 bytes of block exponents ([piece][32-column
+// block], 12 used) and one fp32 group sum.
+constexpr int kPieceBytes = 384;   // one class
+constexpr int kScaleBytes = 16;    // one class
+constexpr int kImageBytes = 2 * (kPieceBytes + kScaleBytes + 4);
+
+// Groups per K-chunk: the whole row when the m images fit in the LDS budget (36 KiB for up to 4
+// vectors, so that four workgroups share a CU; 64 KiB above), else as many groups as fit.
+__host__ __device__ inline int chunk_groups(int n_groups, int m) {
+  const int fit = ((m <= 4 ? 36 : 64) * 1024) / (m * kImageBytes);
+  return n_groups < fit ? n_groups : fit;
+}
+
+__host__ __device__ inline size_t lds_bytes(int chunk, int m, int n_waves, int accs_per_lane) {
+  return static_cast<size_t>(m) * chunk * kImageBytes + static_cast<size_t>(n_waves) * accs_per_lane * 64 * 4;
+}
+
+// Where the parts of the image of vector j live, for a chunk capacity of cg groups and m vectors.
+struct ImageLayout {
+  char* pieces;   // [m][2][cg][384]
+  char* scales;   // [m][2][cg][16]
+  float* xsum;    // [m][2][cg]
+  float* red;     // split-K meeting point
+  int cg;
+  __device__ __forceinline__ ImageLayout(void* lds, int cg_, int m) : cg(cg_) {
+    pieces = static_cast<char*>(lds);
+    scales = pieces + m * 2 * cg * kPieceBytes;
+    xsum = reinterpret_cast<float*>(scales + m * 2 * cg * kScaleBytes);
+    red = xsum + m * 2 * cg;
   }
+  __device__ __forceinline__ int piece_off(int j, int cls) const { return (j * 2 + cls) * cg * kPieceBytes; }
+  __device__ __forceinline__ int scale_off(int j, int cls) const { return (j * 2 + cls) * cg * kScaleBytes; }
+  __device__ __forceinline__ int xsum_off(int j, int cls) const { return (j * 2 + cls) * cg; }
 };
 
-// Offset that the pairs of merged word m carry (see mac_group_sx).
-__device__ __forceinline__ float pair_offset(int m) { return m == 1 ? 512.0f : m == 2 ? 256.0f : 1024.0f; }
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+  return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xF, 0xF, true));
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+  return __builtin_bit_cast(float, dpp_u32<CTRL>(__builtin_bit_cast(uint32_t, v)));
+}
+constexpr int kQuadSwap1 = 0xB1;      // quad_perm [1,0,3,2]
+constexpr int kQuadSwap2 = 0x4E;      // quad_perm [2,3,0,1]
+constexpr int kRowHalfMirror = 0x141;
+constexpr int kRowMirror = 0x140;
 
-// Multiply-accumulate one group (128 columns) of the lane's row.
-//   pl[k]: the lane's 16 bytes of plane k;
-//   xg:    the group's 4 x 16 dwords of x (fp16 pairs in natural column order), read with
-//          s_load_dwordx16: they cost neither LDS bandwidth nor vector registers;
-//   accL:  comes in holding F_g and leaves holding F_g + sum over low-nibble pairs,
-//   accH:  sum over high-nibble pairs (to be divided by 16).
-// The merged word of m = 1, 2 is used without the rotate by m: its fields then sit m bits
-// higher, which the fp16 exponent absorbs (0x6000 = 512 has ulp 1/2, 0x5C00 = 256 has ulp 1/4),
-// so the pair still reads offset + q~ with offset 512 / 256 instead of 1024.  F_g accounts for
-// the per-m offsets (stage_group_sums).  m = 3 would put a field across bit 10 and is rotated.
-template <int B>
-__device__ __forceinline__ void mac_group_sx(const UnpackConsts<B>& uc, const Batch1Consts<B>& bc,
-                                             const u32x4 (&pl)[B], const_u32x16_ptr xg, float& accL, float& accH) {
+// Four fp16 -> four e4m3 bytes, each divided by `scale` (a power of two), round to nearest even.
+__device__ __forceinline__ uint32_t to_fp8x4(half2_t lo, half2_t hi, float scale) {
+  short2_t r = {0, 0};
+  r = __builtin_amdgcn_cvt_scalef32_pk_fp8_f16(r, lo, scale, false);
+  r = __builtin_amdgcn_cvt_scalef32_pk_fp8_f16(r, hi, scale, true);
+  return __builtin_bit_cast(uint32_t, r);
+}
+
+// Largest magnitude (fp16 bit pattern without sign) over the 32 columns a quad of threads owns.
+__device__ __forceinline__ uint32_t quad_max_magnitude(const uint32_t (&w)[4]) {
+  ushort2_t mx = __builtin_bit_cast(ushort2_t, w[0] & 0x7FFF7FFFu);
 #pragma unroll
-  for (int d = 0; d < 4; ++d) {
-    const u32x16 xv = xg[d];
-    uint32_t p[B];
+  for (int q = 1; q < 4; ++q) mx = __builtin_elementwise_max(mx, __builtin_bit_cast(ushort2_t, w[q] & 0x7FFF7FFFu));
+  uint32_t mag = mx.x > mx.y ? mx.x : mx.y;
+  uint32_t o = dpp_u32<kQuadSwap1>(mag);
+  mag = mag > o ? mag : o;
+  o = dpp_u32<kQuadSwap2>(mag);
+  return mag > o ? mag : o;
+}
+
+// Three e4m3 pieces of 8 fp16 values (4 column pairs in w) whose largest exponent field in the
+// 32-column block is E, written to dst (piece stride 128 bytes) in operand order: bytes 0..3 =
+// columns 0,2,4,6, bytes 4..7 = columns 1,3,5,7 (the order of the nibbles in the weight words).
+// Every |x| of the block is below 2^(E-14), so x / 2^(E-22) is below 256 and fits e4m3 (largest
+// finite value 448) without overflow.  The block exponents go to sdst[0], [4], [8].
+__device__ __forceinline__ void split_pieces(const uint32_t (&w)[4], uint32_t E, char* dst, char* sdst, bool write_scale) {
+  const float sc0 = __builtin_bit_cast(float, (E + 105u) << 23);  // 2^(E-22)
+  const float sc1 = __builtin_bit_cast(float, (E + 101u) << 23);  // 2^(E-26)
+  const float sc2 = __builtin_bit_cast(float, (E + 97u) << 23);   // 2^(E-30)
+  uint32_t p0[2], p1[2], p2[2];
 #pragma unroll
-    for (int k = 0; k < B; ++k) p[k] = word_of(pl[k], d);
-#pragma unroll
-    for (int m = 0; m < 4; ++m) {
-      const uint32_t u = merge_planes<B>(uc, p, m);
-      uint32_t w, w8, mL, mH, mg;
-      if (m == 0 || m == 3) {
-        w = (m == 0) ? u : __builtin_amdgcn_alignbit(u, u, 3);
-        w8 = w >> 8;
-        mL = uc.maskL; mH = uc.maskH; mg = uc.magic;
-      } else {
-        w = u;
-        w8 = __builtin_amdgcn_alignbit(u, u, 8);  // rotate: the top field wraps into the low bits
-        mL = bc.maskL[m - 1]; mH = bc.maskH[m - 1]; mg = bc.magic[m - 1];
-      }
-      accL = dot2(and_or(w, mL, mg), xv[4 * m + 0], accL);
-      accH = dot2(and_or(w, mH, mg), xv[4 * m + 1], accH);
-      accL = dot2(and_or(w8, mL, mg), xv[4 * m + 2], accL);
-      accH = dot2(and_or(w8, mH, mg), xv[4 * m + 3], accH);
-    }
+  for (int q = 0; q < 2; ++q) {  // q = 0: even columns, q = 1: odd columns
+    const uint32_t sel = q == 0 ? 0x05040100u : 0x07060302u;
+    half2_t a = __builtin_bit_cast(half2_t, __builtin_amdgcn_perm(w[1], w[0], sel));
+    half2_t b = __builtin_bit_cast(half2_t, __builtin_amdgcn_perm(w[3], w[2], sel));
+    p0[q] = to_fp8x4(a, b, sc0);
+    a -= __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(p0[q], sc0, false);  // exact
+    b -= __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(p0[q], sc0, true);
+    p1[q] = to_fp8x4(a, b, sc1);
+    a -= __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(p1[q], sc1, false);
+    b -= __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(p1[q], sc1, true);
+    p2[q] = to_fp8x4(a, b, sc2);
+  }
+  *reinterpret_cast<uint2*>(dst) = make_uint2(p0[0], p0[1]);
+  *reinterpret_cast<uint2*>(dst + 128) = make_uint2(p1[0], p1[1]);
+  *reinterpret_cast<uint2*>(dst + 256) = make_uint2(p2[0], p2[1]);
+  if (write_scale) {
+    sdst[0] = static_cast<char>(E + 105u);
+    sdst[4] = static_cast<char>(E + 101u);
+    sdst[8] = static_cast<char>(E + 97u);
   }
 }
 
-// LDS of a batch-1 workgroup: (X_g, F_g) per group, then NW*64 floats where the split-K partial
-// sums meet.
-__host__ __device__ inline size_t lds_bytes(int n_groups, int n_waves) {
-  return static_cast<size_t>(n_groups) * 8 + static_cast<size_t>(n_waves) * 64 * 4;
-}
-
-// Per-group sums of the activation vector, computed by the whole workgroup into LDS.
-template <int B, int NW>
-__device__ __forceinline__ void stage_group_sums(const _Float16* __restrict__ x, int in_f, float2* cs) {
-  const uint4* xg = reinterpret_cast<const uint4*>(x);
-  const int n16 = in_f / 8;  // 16 uint4 per group; 16 consecutive threads share a group
+// Split groups [c0, c0 + cn) of activation vector j into the two classes' pieces, block
+// exponents and group sums, by the whole workgroup.  Thread idx handles columns 8 idx ..
+// 8 idx + 7 of the range; a quad of threads owns one 32-column block, a row of 16 threads one
+// group.
+template <int NW>
+__device__ __forceinline__ void stage_x(const _Float16* __restrict__ x, int c0, int cn, const ImageLayout& im, int j) {
+  const uint4* xg = reinterpret_cast<const uint4*>(x) + c0 * 16;
+  const int n16 = cn * 16;
   for (int idx = threadIdx.x; idx < n16; idx += NW * 64) {
     const uint4 v = xg[idx];
-    // columns 8*idx .. 8*idx+7: (0,1) low, (2,3) high, (4,5) low, (6,7) high
-    const half2_t a = __builtin_bit_cast(half2_t, v.x), b = __builtin_bit_cast(half2_t, v.y);
-    const half2_t c = __builtin_bit_cast(half2_t, v.z), e = __builtin_bit_cast(half2_t, v.w);
-    float lo = (static_cast<float>(a.x) + static_cast<float>(a.y)) + (static_cast<float>(c.x) + static_cast<float>(c.y));
-    float hi = (static_cast<float>(b.x) + static_cast<float>(b.y)) + (static_cast<float>(e.x) + static_cast<float>(e.y));
-    // these 8 columns belong to merged word m = idx % 4; E collects offset * (low + high/16)
-    float X = lo + hi;
-    float E = pair_offset(idx & 3) * (lo + hi * 0.0625f);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    const uint32_t EA = quad_max_magnitude(w) >> 10;  // exponent field of the block's largest |x|
+    // class B: magnitude below 2^(EA-7-15), i.e. bit pattern below (EA-7) << 10
+    const uint32_t thr = (EA > 7u ? EA - 7u : 0u) << 10;
+    const ushort2_t thr2 = {static_cast<unsigned short>(thr), static_cast<unsigned short>(thr)};
+    uint32_t wa[4], wb[4];
+    float xsa = 0.f, xsb = 0.f;
 #pragma unroll
-    for (int off = 1; off < 16; off <<= 1) {
-      X += __shfl_xor(X, off, 16);
-      E += __shfl_xor(E, off, 16);
+    for (int q = 0; q < 4; ++q) {
+      const ushort2_t mag = __builtin_bit_cast(ushort2_t, w[q] & 0x7FFF7FFFu);
+      const short2_t below = __builtin_bit_cast(short2_t, static_cast<ushort2_t>(mag - thr2)) >> 15;  // all ones iff class B
+      const uint32_t mb = __builtin_bit_cast(uint32_t, below);
+      wa[q] = w[q] & ~mb;
+      wb[q] = w[q] & mb;
+      xsa = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, wa[q]), half2_t{1, 1}, xsa, false);
+      xsb = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, wb[q]), half2_t{1, 1}, xsb, false);
     }
-    if ((idx & 15) == 0) cs[idx >> 4] = make_float2(X, X * (B == 4 ? 0.5f : B == 3 ? 1.0f : 2.0f) - E);
+    const uint32_t EB = quad_max_magnitude(wb) >> 10;
+    const int g = idx >> 4, c8 = idx & 15;
+    const bool lead = (idx & 3) == 0;
+    split_pieces(wa, EA, im.pieces + im.piece_off(j, 0) + g * kPieceBytes + c8 * 8,
+                 im.scales + im.scale_off(j, 0) + g * kScaleBytes + (c8 >> 2), lead);
+    split_pieces(wb, EB, im.pieces + im.piece_off(j, 1) + g * kPieceBytes + c8 * 8,
+                 im.scales + im.scale_off(j, 1) + g * kScaleBytes + (c8 >> 2), lead);
+    xsa += dpp_f32<kQuadSwap1>(xsa);
+    xsb += dpp_f32<kQuadSwap1>(xsb);
+    xsa += dpp_f32<kQuadSwap2>(xsa);
+    xsb += dpp_f32<kQuadSwap2>(xsb);
+    xsa += dpp_f32<kRowHalfMirror>(xsa);
+    xsb += dpp_f32<kRowHalfMirror>(xsb);
+    xsa += dpp_f32<kRowMirror>(xsa);
+    xsb += dpp_f32<kRowMirror>(xsb);
+    if (c8 == 0) {
+      im.xsum[im.xsum_off(j, 0) + g] = xsa;
+      im.xsum[im.xsum_off(j, 1) + g] = xsb;
+    }
   }
 }
 
-// One workgroup: TPW = NW / SPLITK consecutive row tiles starting at tile0, each split over
-// SPLITK waves along K.  x: in_f fp16, y: out_f fp32.
-template <int B, int NW, int SPLITK>
-__device__ __forceinline__ void run_tiles(const LayerDesc& L, int tile0, const _Float16* __restrict__ x,
-                                          float* __restrict__ y, uint4* lds) {
+__device__ __forceinline__ i32x8 fp4_operand(const uint32_t (&w)[4]) {
+  return i32x8{static_cast<int>(w[0]), static_cast<int>(w[1]), static_cast<int>(w[2]), static_cast<int>(w[3]), 0, 0, 0, 0};
+}
+
+// One activation operand set: the fp8 registers and the block-scale register of the lane.
+struct XOperand {
+  i32x8 a;
+  int scale;
+};
+
+// X x (the weights of 16-row block t of the lane's plane words pl) for the bit-width B: sum of
+// q~ x over the group, per operand row.  wscale holds the e8m0 bytes of 2^3 (byte 0, upper
+// pair) and 2^1 (byte 1, lower pair).  SETS operand sets share the unpacked weight operand.
+template <int B, int SETS>
+__device__ __forceinline__ void mfma_block(const XOperand (&X)[SETS], const u32x4 (&pl)[B], int t, int wscale,
+                                           float4_t (&acc)[SETS]) {
+  uint32_t w[4];
+  pair_words(word_of(pl[0], t), word_of(pl[1], t), w);
+  i32x8 op = fp4_operand(w);
+  const float4_t zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int s = 0; s < SETS; ++s)
+    acc[s] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(X[s].a, op, zero, 0 /*A: e4m3*/, 4 /*B: e2m1*/, 0, X[s].scale, 0,
+                                                              wscale);
+  if constexpr (B >= 3) {
+    if constexpr (B == 4) pair_words(word_of(pl[2], t), word_of(pl[3], t), w);
+    else single_words(word_of(pl[2], t), w);
+    op = fp4_operand(w);
+#pragma unroll
+    for (int s = 0; s < SETS; ++s)
+      acc[s] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(X[s].a, op, acc[s], 0, 4, 0, X[s].scale, 1, wscale);
+  }
+}
+
+__device__ __forceinline__ i32x8 read_fp8_operand(const char* p) {
+  const u32x4 lo = *reinterpret_cast<const u32x4*>(p);
+  const u32x4 hi = *reinterpret_cast<const u32x4*>(p + 64);
+  return i32x8{static_cast<int>(lo.x), static_cast<int>(lo.y), static_cast<int>(lo.z), static_cast<int>(lo.w),
+               static_cast<int>(hi.x), static_cast<int>(hi.y), static_cast<int>(hi.z), static_cast<int>(hi.w)};
+}
+
+template <int B>
+constexpr float half_step() { return B == 4 ? 0.5f : B == 3 ? 1.0f : 2.0f; }  // 2^(3-b)
+
+// =====================================================================================
+// One workgroup: NW / SPLITK consecutive row tiles starting at tile0, each split over SPLITK waves
+// along K, for m <= 2 SETS activation vectors.  K is walked in chunks whose split activations fit
+// in LDS.  x: [m][in_f] fp16, y: [m][out_f] fp32.
+template <int B, int SETS, int NW, int SPLITK>
+__device__ __forceinline__ void run_tiles(const LayerDesc& L, int tile0, const _Float16* __restrict__ x, int m,
+                                          float* __restrict__ y, uint4* lds_raw) {
   static_assert(NW % SPLITK == 0, "waves must divide evenly over the K splits");
-  const UnpackConsts<B> uc;
-  const Batch1Consts<B> bc;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int G = L.n_groups;
-  float2* cs = reinterpret_cast<float2*>(lds);
-  float* red = reinterpret_cast<float*>(cs + G);
+  const ImageLayout im(lds_raw, chunk_groups(G, m), m);
 
   const int tile = tile0 + wave / SPLITK;
   const int ks = wave % SPLITK;
   const bool active = tile < L.n_tiles;
-  const int64_t base = (static_cast<int64_t>(active ? tile : 0) * G) * 64 + lane;  // + g*64 per group
+  const int64_t tbase = (static_cast<int64_t>(active ? tile : 0) * G) * 64 + lane;  // + g*64 per group
   global_u32x4_ptr pp[B];
 #pragma unroll
-  for (int k = 0; k < B; ++k) pp[k] = (global_u32x4_ptr)(L.plane[k]) + base;
-  global_u32_ptr sp = (global_u32_ptr)(L.sa) + base;
-  const_u32x16_ptr xc = (const_u32x16_ptr)(x);
+  for (int k = 0; k < B; ++k) pp[k] = (global_u32x4_ptr)(L.plane[k]) + tbase;
+  // (scale, min) words of rows l % 16 + 16 t, t = 0..3: the 16 bytes at [l % 16] of the group's 64 words
+  global_u32x4_ptr sp = (global_u32x4_ptr)(L.sa) + (tbase - lane) / 4 + (lane & 15);  // + g*16 per group
 
-  float yacc = 0.f;
-  const int g0 = G * ks / SPLITK, g1 = G * (ks + 1) / SPLITK;
-  const bool work = active && g0 < g1;
-  // The next group's plane words are in flight while the current group is consumed.  Weights
-  // are read exactly once per pass: nontemporal loads keep them from displacing anything in
-  // the caches (measured: the same loop without arithmetic streams 6.7 TB/s with them,
-  // 5.8 TB/s without).  Past the end of the range the last group is reloaded (a cache hit)
-  // instead of branching around the loads.  Two register sets A and B alternate (the loop is
-  // unrolled by two), so nothing is copied.
-  u32x4 pa[B], pb[B];
-  uint32_t sa_a = 0, sa_b = 0;
-  auto load = [&](u32x4 (&dst)[B], uint32_t& dsa, int g) {
-    const int gl = g < g1 ? g : g1 - 1;
-#pragma unroll
-    for (int k = 0; k < B; ++k) dst[k] = __builtin_nontemporal_load(&pp[k][gl * 64]);
-    dsa = sp[gl * 64];
-  };
-  // The first group's loads do not depend on the group sums: issue them before the workgroup
-  // computes the sums, so that their latency overlaps the staging and the barrier.
-  if (work) load(pa, sa_a, g0);
-
-  stage_group_sums<B, NW>(x, L.in_f, cs);
-  __syncthreads();
-
-  if (work) {
-    auto consume = [&](const u32x4 (&pl)[B], uint32_t csa, int g) {
-      const float2 c = cs[g];
-      float accL = c.y, accH = 0.f;
-      mac_group_sx<B>(uc, bc, pl, xc + g * 4, accL, accH);
-      const float s = half_bits_to_float(csa & 0xffffu);
-      const float a = half_bits_to_float(csa >> 16);
-      yacc = fmaf(s, fmaf(accH, 0.0625f, accL), yacc);
-      yacc = fmaf(a, c.x, yacc);
-    };
-    for (int gc = g0; gc < g1; gc += 2) {
-      load(pb, sa_b, gc + 1);
-      consume(pa, sa_a, gc);
-      load(pa, sa_a, gc + 2);
-      if (gc + 1 < g1) consume(pb, sa_b, gc + 1);
-    }
-  }
-  if constexpr (SPLITK > 1) {
-    red[wave * 64 + lane] = yacc;
-    __syncthreads();
-    if (ks == 0) {
-      float sum = yacc;
-#pragma unroll
-      for (int q = 1; q < SPLITK; ++q) sum += red[(wave + q) * 64 + lane];
-      yacc = sum;
-    }
-  }
-  if (ks == 0 && active) {
-    const int row = tile * 64 + lane;
-    if (row < L.out_f) y[row] = yacc;
-  }
-}
-
-// =====================================================================================
-// MFMA-assisted variant.  Unpack is unchanged; the multiply-accumulate and the sum over K go
-// to the matrix pipe, which is otherwise idle, so the VALU only pays for the unpack.
-//
-// v_mfma_f32_16x16x32_f16 computes D[i][j] += sum_k A[i][k] B[k][j] with lane l holding
-// A[l%16][8(l/16) .. 8(l/16)+7] and B[8(l/16) ..][l%16], and D[4(l/16)+t][l%16] in register t.
-// A lane's 8 unpacked weights belong to ROW l of the tile, not to row l%16, so the operand is
-// read as A[i][8G+t] = w[row 16G+i][t] (G = l/16).  Choosing B[8G+t][j] = x[t] for j == G and 0
-// elsewhere gives D[i][j] = sum_t w[16j+i][t] x[t]: column j < 4 of D holds the dot products of
-// rows 16j .. 16j+15.  Columns 4*beta + rho carry activation vector beta (up to 4 vectors per
-// MFMA, 8 with a second accumulator set), so batches 1..8 read and unpack the weights once.
-// The B operand comes straight from LDS with a per-lane address (x for the "diagonal" lanes,
-// a block of zeros for the rest): no VALU work.  Low-nibble and high-nibble pairs go to
-// separate accumulators DL, DH because they differ by the factor 16 (see the header comment).
-typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
-typedef float float4_t __attribute__((ext_vector_type(4)));
-
-// LDS image for the MFMA path: per vector cg groups of x (256 B each, permuted), the (X_g, F_g)
-// pairs, 256 zero bytes, then the split-K meeting point (16 B per lane, wave and accumulator set).
-// Groups per K-chunk of the batched kernels: the whole row when the m vectors fit in about
-// 32 KiB of LDS, else as many groups as fit.
-__host__ __device__ inline int chunk_groups(int n_groups, int m) {
-  const int fit = (32 * 1024) / (m * 256);
-  return n_groups < fit ? n_groups : fit;
-}
-
-constexpr int kZeroBlockVec = 20;  // 320 zero bytes: 256 read by the off-diagonal lanes, 64 of phase shift
-__host__ __device__ inline size_t lds_bytes_mfma(int cg, int m, int n_waves, int sets_times_tiles) {
-  return static_cast<size_t>(m) * cg * 256 + static_cast<size_t>((m * cg + 1) & ~1) * 8 + kZeroBlockVec * 16 +
-         static_cast<size_t>(sets_times_tiles) * n_waves * 64 * 16;
-}
-
-// Copy groups [c0, c0+cn) of the m vectors into LDS in MFMA operand order.  Within each
-// 32-column word the 16 dwords are stored as [L#1][H#1][L#2][H#2], 4 dwords each, where L
-// collects the column pairs whose code sits in a low nibble (columns 8q+0,1 and 8q+4,5) and H
-// those in a high nibble (8q+2,3 and 8q+6,7); #1 covers columns 0..15 of the word, #2 16..31.
-template <int B, int NW>
-__device__ __forceinline__ void stage_activations_mfma(const _Float16* __restrict__ x, int in_f, int m, int c0, int cn,
-                                                       int cg, uint32_t* xs, float2* cs, uint4* zeros) {
-  const int n16 = cn * 16;
-  for (int j = 0; j < m; ++j) {
-    const uint4* xg = reinterpret_cast<const uint4*>(x + static_cast<int64_t>(j) * in_f) + c0 * 16;
-    for (int idx = threadIdx.x; idx < n16; idx += NW * 64) {
-      const uint4 v = xg[idx];
-      const int q = idx & 3;  // which 8 columns of the 32-column word
-      uint32_t* dst = xs + (j * cg * 64) + (idx >> 2) * 16 + (q >> 1) * 8 + (q & 1) * 2;
-      *reinterpret_cast<uint2*>(dst) = make_uint2(v.x, v.z);
-      *reinterpret_cast<uint2*>(dst + 4) = make_uint2(v.y, v.w);
-      const half2_t a = __builtin_bit_cast(half2_t, v.x), b = __builtin_bit_cast(half2_t, v.y);
-      const half2_t c = __builtin_bit_cast(half2_t, v.z), e = __builtin_bit_cast(half2_t, v.w);
-      float lo = (static_cast<float>(a.x) + static_cast<float>(a.y)) + (static_cast<float>(c.x) + static_cast<float>(c.y));
-      float hi = (static_cast<float>(b.x) + static_cast<float>(b.y)) + (static_cast<float>(e.x) + static_cast<float>(e.y));
-#pragma unroll
-      for (int off = 1; off < 16; off <<= 1) {
-        lo += __shfl_xor(lo, off, 16);
-        hi += __shfl_xor(hi, off, 16);
-      }
-      if ((idx & 15) == 0) {
-        const float X = lo + hi;
-        const float F = X * (B == 4 ? 0.5f : B == 3 ? 1.0f : 2.0f) - 1024.0f * (lo + hi * 0.0625f);
-        cs[j * cg + (idx >> 4)] = make_float2(X, F);
-      }
-    }
-  }
-  if (threadIdx.x < kZeroBlockVec) zeros[threadIdx.x] = make_uint4(0, 0, 0, 0);
-}
-
-__device__ __forceinline__ half8_t as_half8(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
-  u32x4 v = {a, b, c, d};
-  return __builtin_bit_cast(half8_t, v);
-}
-
-// One workgroup of the MFMA variant.  SETS = 1 serves m <= 4 vectors, SETS = 2 serves m <= 8.
-// Each wave owns T consecutive row tiles and reuses every B operand it reads from LDS for all
-// of them, which divides the LDS traffic per weight by T.
-template <int B, int SETS, int T, int NW, int SPLITK>
-__device__ __forceinline__ void run_tiles_mfma(const LayerDesc& L, int tile0, const _Float16* __restrict__ x, int m,
-                                               float* __restrict__ y, uint4* lds) {
-  static_assert(NW % SPLITK == 0, "waves must divide evenly over the K splits");
-  const UnpackConsts<B> uc;
-  const uint32_t maskL = uc.maskL, maskH = uc.maskH, magic = uc.magic;
-
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int G = L.n_groups;
-  const int cg = chunk_groups(G, m);
-  uint32_t* xs = reinterpret_cast<uint32_t*>(lds);
-  float2* cs = reinterpret_cast<float2*>(xs + m * cg * 64);
-  uint4* zeros = reinterpret_cast<uint4*>(cs + ((m * cg + 1) & ~1));  // keep 16-byte alignment
-  float4_t* red = reinterpret_cast<float4_t*>(zeros + kZeroBlockVec);
-
-  const int tile_first = tile0 + (wave / SPLITK) * T;
-  const int ks = wave % SPLITK;
-  const bool active = tile_first < L.n_tiles;
-  // MFMA output geometry of this lane: column j, rows 4*gq .. 4*gq+3 of the 16-row block rho.
-  const int j = lane & 15, gq = lane >> 4;
-  const int beta = j >> 2, rho = j & 3;
-  const int rows0 = 16 * rho + 4 * gq;  // first of the lane's 4 output rows within a tile
-  // Tiles past the end of the layer are clamped to the last one (loads stay in bounds, the
-  // duplicate result is not stored).
-  global_u32x4_ptr pp[T][B];
-  global_u32x4_ptr sp[T];
-#pragma unroll
-  for (int t = 0; t < T; ++t) {
-    int tl = tile_first + t;
-    tl = tl < L.n_tiles ? tl : L.n_tiles - 1;
-    tl = active ? tl : 0;
-    const int64_t tbase = (static_cast<int64_t>(tl) * G) * 64;
-#pragma unroll
-    for (int k = 0; k < B; ++k) pp[t][k] = (global_u32x4_ptr)(L.plane[k]) + tbase + lane;
-    sp[t] = (global_u32x4_ptr)((global_u32_ptr)(L.sa) + tbase + rows0);
-  }
-
-  // Per-lane LDS addressing of the B operand (bytes from xs): x of vector beta for the
-  // "diagonal" lanes; every other lane reads a block of zeros that does not advance with the
-  // group and sits 64 bytes out of phase so that the two addresses never share a bank.
-  const char* lds_c = reinterpret_cast<const char*>(xs);
-  const int zero_off = static_cast<int>(reinterpret_cast<const char*>(zeros) - lds_c) + 64;
-  int boff[SETS], bmul[SETS], cidx[SETS];
+  // Operand addressing.  Row i = lane % 16 of the activation operand is piece i % 4 of slot i / 4;
+  // the lane receives the sums of slot lane / 16.  Slot 2 v + c = class c of vector 2 s + v.
+  const int piece = (lane & 3) == 3 ? 0 : (lane & 3);  // row 4 q + 3 is never read back
+  const int in_slot = (lane & 15) >> 2, out_slot = lane >> 4;
+  int a_off[SETS], s_off[SETS], x_off[SETS];
 #pragma unroll
   for (int s = 0; s < SETS; ++s) {
-    const int bt = beta + 4 * s;
-    const bool diag = (rho == gq) && (bt < m);
-    boff[s] = diag ? bt * cg * 256 : zero_off;
-    bmul[s] = diag ? 256 : 0;
-    cidx[s] = (bt < m ? bt : m - 1) * cg;
+    int vi = 2 * s + (in_slot >> 1);
+    vi = vi < m ? vi : m - 1;  // slots of absent vectors repeat the last one; their sums are not stored
+    a_off[s] = im.piece_off(vi, in_slot & 1) + piece * 128 + (lane >> 4) * 16;
+    s_off[s] = im.scale_off(vi, in_slot & 1) + piece * 4 + (lane >> 4);
+    int vo = 2 * s + (out_slot >> 1);
+    vo = vo < m ? vo : m - 1;
+    x_off[s] = im.xsum_off(vo, out_slot & 1);
   }
+  int wscale = 0x00008082;
+  asm volatile("" : "+v"(wscale));
 
-  float4_t yacc[T][SETS];
+  float yacc[SETS][4];
 #pragma unroll
-  for (int t = 0; t < T; ++t)
+  for (int s = 0; s < SETS; ++s)
 #pragma unroll
-    for (int s = 0; s < SETS; ++s) yacc[t][s] = float4_t{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < 4; ++t) yacc[s][t] = 0.f;
 
-  for (int c0 = 0; c0 < G; c0 += cg) {
-    const int cn = (G - c0 < cg) ? (G - c0) : cg;
-    if (c0) __syncthreads();
-    stage_activations_mfma<B, NW>(x, L.in_f, m, c0, cn, cg, xs, cs, zeros);
-    __syncthreads();
+  for (int c0 = 0; c0 < G; c0 += im.cg) {
+    const int cn = (G - c0 < im.cg) ? (G - c0) : im.cg;
     const int g0 = c0 + cn * ks / SPLITK, g1 = c0 + cn * (ks + 1) / SPLITK;
-    if (active && g0 < g1) {
-      u32x4 nb[T][B];
+    const bool work = active && g0 < g1;
+    // The next group's plane words are in flight while the current group is consumed.  Weights
+    // are read exactly once per pass: nontemporal loads keep them from displacing anything in
+    // the caches.  Past the end of the range the last group is reloaded (a cache hit) instead
+    // of branching around the loads.  Two register sets alternate (the loop is unrolled by two).
+    u32x4 pa[B], pb[B], sa_a = {0, 0, 0, 0}, sa_b = {0, 0, 0, 0};
+    auto load = [&](u32x4 (&dst)[B], u32x4& dsa, int g) {
+      const int gl = g < g1 ? g : g1 - 1;
 #pragma unroll
-      for (int t = 0; t < T; ++t)
+      for (int k = 0; k < B; ++k) dst[k] = __builtin_nontemporal_load(&pp[k][gl * 64]);
+      dsa = sp[gl * 16];
+    };
+    // The first group's loads do not depend on the activations: issue them before the workgroup
+    // splits x, so that their latency overlaps the staging and the barrier.
+    if (work) load(pa, sa_a, g0);
+    if (c0) __syncthreads();  // the previous chunk's image has been consumed
+    for (int j = 0; j < m; ++j) stage_x<NW>(x + static_cast<int64_t>(j) * L.in_f, c0, cn, im, j);
+    __syncthreads();
+    if (work) {
+      auto consume = [&](const u32x4 (&pl)[B], const u32x4& csa, int g) {
+        const int gr = g - c0;
+        XOperand X[SETS];
+        float xg[SETS];
 #pragma unroll
-        for (int k = 0; k < B; ++k) nb[t][k] = __builtin_nontemporal_load(&pp[t][k][g0 * 64]);
-      for (int gc = g0; gc < g1; ++gc) {
-        u32x4 cur[T][B];
-        u32x4 csa[T];
-        const int gl = (gc + 1 < g1) ? (gc + 1) : (g1 - 1);
-#pragma unroll
-        for (int t = 0; t < T; ++t) {
-#pragma unroll
-          for (int k = 0; k < B; ++k) cur[t][k] = nb[t][k];
-          // scale/min words are needed only after the group's arithmetic: no ring for them
-          csa[t] = __builtin_nontemporal_load(&sp[t][gc * 16]);
-#pragma unroll
-          for (int k = 0; k < B; ++k) nb[t][k] = __builtin_nontemporal_load(&pp[t][k][gl * 64]);
+        for (int s = 0; s < SETS; ++s) {
+          X[s].a = read_fp8_operand(im.pieces + a_off[s] + gr * kPieceBytes);
+          X[s].scale = static_cast<unsigned char>(im.scales[s_off[s] + gr * kScaleBytes]);
+          xg[s] = im.xsum[x_off[s] + gr];
         }
-
-        const char* xb[SETS];
 #pragma unroll
-        for (int s = 0; s < SETS; ++s) xb[s] = lds_c + boff[s] + (gc - c0) * bmul[s];
-        float4_t dl[T][SETS], dh[T][SETS];
-#pragma unroll
-        for (int d = 0; d < 4; ++d) {
-          half8_t bL[2][SETS], bH[2][SETS];
-#pragma unroll
-          for (int q = 0; q < 2; ++q)
-#pragma unroll
-            for (int s = 0; s < SETS; ++s) {
-              bL[q][s] = *reinterpret_cast<const half8_t*>(xb[s] + d * 64 + q * 32);
-              bH[q][s] = *reinterpret_cast<const half8_t*>(xb[s] + d * 64 + q * 32 + 16);
-            }
-#pragma unroll
-          for (int t = 0; t < T; ++t) {
-            uint32_t p[B];
-#pragma unroll
-            for (int k = 0; k < B; ++k) p[k] = word_of(cur[t][k], d);
-            uint32_t r[4][4];  // r[m][0..3] = (low v0, high v0, low v1, high v1) pairs of word m
-#pragma unroll
-            for (int mm = 0; mm < 4; ++mm) {
-              uint32_t u = merge_planes<B>(uc, p, mm);
-              uint32_t w = (mm == 0) ? u : __builtin_amdgcn_alignbit(u, u, mm);
-              uint32_t w8 = w >> 8;
-              r[mm][0] = and_or(w, maskL, magic);
-              r[mm][1] = and_or(w, maskH, magic);
-              r[mm][2] = and_or(w8, maskL, magic);
-              r[mm][3] = and_or(w8, maskH, magic);
-            }
-#pragma unroll
-            for (int q = 0; q < 2; ++q) {  // columns 16q .. 16q+15 of the word
-              const half8_t aL = as_half8(r[2 * q][0], r[2 * q][2], r[2 * q + 1][0], r[2 * q + 1][2]);
-              const half8_t aH = as_half8(r[2 * q][1], r[2 * q][3], r[2 * q + 1][1], r[2 * q + 1][3]);
-#pragma unroll
-              for (int s = 0; s < SETS; ++s) {
-                const float4_t zero = {0.f, 0.f, 0.f, 0.f};
-                dl[t][s] = __builtin_amdgcn_mfma_f32_16x16x32_f16(aL, bL[q][s], (d == 0 && q == 0) ? zero : dl[t][s], 0, 0, 0);
-                dh[t][s] = __builtin_amdgcn_mfma_f32_16x16x32_f16(aH, bH[q][s], (d == 0 && q == 0) ? zero : dh[t][s], 0, 0, 0);
-              }
-            }
-          }
-        }
-        // scale and minimum of the lane's 4 output rows per tile, once per group
-#pragma unroll
-        for (int t = 0; t < T; ++t) {
-          const uint32_t sa4[4] = {csa[t].x, csa[t].y, csa[t].z, csa[t].w};
+        for (int t = 0; t < 4; ++t) {
+          float4_t acc[SETS];
+          mfma_block<B, SETS>(X, pl, t, wscale, acc);
+          const uint32_t w = word_of(csa, t);
+          const float sc = half_bits_to_float(w & 0xffffu);
+          const float off = fmaf(sc, half_step<B>(), half_bits_to_float(w >> 16));
 #pragma unroll
           for (int s = 0; s < SETS; ++s) {
-            const float2 c = cs[cidx[s] + (gc - c0)];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const float sc = half_bits_to_float(sa4[e] & 0xffffu);
-              const float mn = half_bits_to_float(sa4[e] >> 16);
-              const float u = fmaf(dh[t][s][e], 0.0625f, dl[t][s][e]) + c.y;
-              yacc[t][s][e] = fmaf(sc, u, yacc[t][s][e]);
-              yacc[t][s][e] = fmaf(mn, c.x, yacc[t][s][e]);
-            }
+            const float d = (acc[s][0] + acc[s][1]) + acc[s][2];
+            yacc[s][t] = fmaf(sc, d, yacc[s][t]);
+            yacc[s][t] = fmaf(off, xg[s], yacc[s][t]);
           }
         }
+      };
+      for (int gc = g0; gc < g1; gc += 2) {
+        load(pb, sa_b, gc + 1);
+        consume(pa, sa_a, gc);
+        load(pa, sa_a, gc + 2);
+        if (gc + 1 < g1) consume(pb, sa_b, gc + 1);
       }
     }
   }
+  // the two classes of a vector sit 16 lanes apart: add them (fixed order: A + B)
+#pragma unroll
+  for (int s = 0; s < SETS; ++s)
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const float other = __shfl_xor(yacc[s][t], 16);
+      yacc[s][t] = (out_slot & 1) ? other + yacc[s][t] : yacc[s][t] + other;
+    }
   if constexpr (SPLITK > 1) {
+    __syncthreads();
 #pragma unroll
-    for (int t = 0; t < T; ++t)
+    for (int s = 0; s < SETS; ++s)
 #pragma unroll
-      for (int s = 0; s < SETS; ++s) red[((t * SETS + s) * NW + wave) * 64 + lane] = yacc[t][s];
+      for (int t = 0; t < 4; ++t) im.red[((s * 4 + t) * NW + wave) * 64 + lane] = yacc[s][t];
     __syncthreads();
     if (ks == 0) {
 #pragma unroll
-      for (int t = 0; t < T; ++t)
+      for (int s = 0; s < SETS; ++s)
 #pragma unroll
-        for (int s = 0; s < SETS; ++s) {
-          float4_t sum = yacc[t][s];
+        for (int t = 0; t < 4; ++t) {
+          float sum = yacc[s][t];
 #pragma unroll
-          for (int q = 1; q < SPLITK; ++q) sum += red[((t * SETS + s) * NW + wave + q) * 64 + lane];
-          yacc[t][s] = sum;
+          for (int q = 1; q < SPLITK; ++q) sum += im.red[((s * 4 + t) * NW + wave + q) * 64 + lane];
+          yacc[s][t] = sum;
         }
     }
   }
-  if (ks == 0 && active) {
+  if (ks == 0 && active && (out_slot & 1) == 0) {
 #pragma unroll
-    for (int t = 0; t < T; ++t) {
-      if (tile_first + t < L.n_tiles) {
+    for (int s = 0; s < SETS; ++s) {
+      const int vo = 2 * s + (out_slot >> 1);
+      if (vo < m) {
+        float* yo = y + static_cast<int64_t>(vo) * L.out_f;
 #pragma unroll
-        for (int s = 0; s < SETS; ++s) {
-          const int bt = beta + 4 * s;
-          if (bt < m) {
-            const int row = (tile_first + t) * 64 + rows0;
-            float* yo = y + static_cast<int64_t>(bt) * L.out_f + row;
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (row + e < L.out_f) yo[e] = yacc[t][s][e];
-          }
+        for (int t = 0; t < 4; ++t) {
+          const int row = tile * 64 + 16 * t + (lane & 15);
+          if (row < L.out_f) yo[row] = yacc[s][t];
         }
       }
     }
   }
 }
 
-template <int B, int T, int NW, int SPLITK>
-__global__ __launch_bounds__(NW * 64, 4) void pmpd_gemv_stack_mfma_kernel(const LayerDesc* __restrict__ layers,
-                                                                          const WorkItem* __restrict__ items,
-                                                                          const _Float16* __restrict__ x_base,
-                                                                          float* __restrict__ y_base) {
-  extern __shared__ uint4 lds[];
-  const WorkItem it = items[blockIdx.x];
-  const LayerDesc L = layers[it.layer];
-  run_tiles_mfma<B, 1, T, NW, SPLITK>(L, it.tile0, x_base + L.x_off, 1, y_base + L.y_off, lds);
-}
+// Waves per SIMD the kernels are compiled for: 4 for one or two operand sets, fewer above.
+template <int SETS>
+constexpr int waves_per_simd() { return SETS <= 2 ? 4 : PMPD_BATCH_WIDE_WAVES; }
 
-template <int B, int SETS, int T, int NW>
-__global__ __launch_bounds__(NW * 64, (SETS * T > 2 ? PMPD_BATCH_WIDE_WAVES : 4)) void pmpd_gemm_stack_mfma_kernel(const LayerDesc* __restrict__ layers,
-                                                                          const WorkItem* __restrict__ items,
-                                                                          const _Float16* __restrict__ x_base, int m,
-                                                                          float* __restrict__ y_base) {
+template <int B, int SETS, int NW, int SPLITK>
+__global__ __launch_bounds__(NW * 64, waves_per_simd<SETS>()) void pmpd_stack_kernel(
+    const LayerDesc* __restrict__ layers, const WorkItem* __restrict__ items, const _Float16* __restrict__ x_base, int m,
+    float* __restrict__ y_base) {
   extern __shared__ uint4 lds[];
   const WorkItem it = items[blockIdx.x];
   const LayerDesc L = layers[it.layer];
-  run_tiles_mfma<B, SETS, T, NW, 1>(L, it.tile0, x_base + static_cast<int64_t>(m) * L.x_off, m,
-                                    y_base + static_cast<int64_t>(m) * L.y_off, lds);
+  run_tiles<B, SETS, NW, SPLITK>(L, it.tile0, x_base + static_cast<int64_t>(m) * L.x_off, m,
+                                 y_base + static_cast<int64_t>(m) * L.y_off, lds);
 }
 
 template <int B, int SETS, int NW, int SPLITK>
-__global__ __launch_bounds__(NW * 64, 4) void pmpd_gemm_layer_mfma_kernel(LayerDesc L, const _Float16* __restrict__ x,
-                                                                          int m, float* __restrict__ y) {
+__global__ __launch_bounds__(NW * 64, waves_per_simd<SETS>()) void pmpd_layer_kernel(LayerDesc L,
+                                                                                    const _Float16* __restrict__ x, int m,
+                                                                                    float* __restrict__ y) {
   extern __shared__ uint4 lds[];
-  run_tiles_mfma<B, SETS, 1, NW, SPLITK>(L, static_cast<int>(blockIdx.x) * (NW / SPLITK), x, m, y, lds);
-}
-
-template <int B, int NW, int SPLITK>
-__global__ __launch_bounds__(NW * 64, 4) void pmpd_gemv_stack_kernel(const LayerDesc* __restrict__ layers,
-                                                                   const WorkItem* __restrict__ items,
-                                                                   const _Float16* __restrict__ x_base,
-                                                                   float* __restrict__ y_base) {
-  extern __shared__ uint4 lds[];
-  const WorkItem it = items[blockIdx.x];
-  const LayerDesc L = layers[it.layer];
-  run_tiles<B, NW, SPLITK>(L, it.tile0, x_base + L.x_off, y_base + L.y_off, lds);
-}
-
-template <int B, int NW, int SPLITK>
-__global__ __launch_bounds__(NW * 64, 4) void pmpd_gemv_layer_kernel(LayerDesc L, const _Float16* __restrict__ x,
-                                                                   float* __restrict__ y) {
-  extern __shared__ uint4 lds[];
-  run_tiles<B, NW, SPLITK>(L, static_cast<int>(blockIdx.x) * (NW / SPLITK), x, y, lds);
+  run_tiles<B, SETS, NW, SPLITK>(L, static_cast<int>(blockIdx.x) * (NW / SPLITK), x, m, y, lds);
 }
 
 // ------------------------------------------------------------------ host side ----
@@ -544,58 +455,43 @@ int32_t check_bits(int32_t b, const char* who) {
   return PMPD_OK;
 }
 
-// Launch shapes.  A stack has thousands of row tiles, so whole-K waves (no split) keep x
-// staging rare; a single layer has few tiles and splits K to put more waves on the machine.
-// Launch shapes.  A stack has thousands of row tiles, so whole-K waves (no split) are enough;
-// a single layer has few tiles and splits K to put more waves on the machine.
-template <int B, int NW, int SPLITK>
-static hipError_t launch_layer(const LayerDesc& d, const void* x, float* y, hipStream_t s) {
-  const int tpw = NW / SPLITK;
-  const unsigned grid = static_cast<unsigned>((d.n_tiles + tpw - 1) / tpw);
-  hipLaunchKernelGGL((pmpd_gemv_layer_kernel<B, NW, SPLITK>), dim3(grid), dim3(NW * 64), lds_bytes(d.n_groups, NW), s, d,
-                     static_cast<const _Float16*>(x), y);
-  return hipGetLastError();
-}
-
-template <int B>
-static hipError_t launch_layer_b(const LayerDesc& d, const void* x, float* y, hipStream_t s) {
+// Launch shapes.  A stack has thousands of row tiles; a single layer has few and splits K over
+// the waves of a workgroup to put more waves on the machine.
+static int pick_splitk(int n_tiles, int groups_per_pass) {
   // Split K until about 2048 waves exist or a wave would get fewer than 4 groups.
   int splitk = 1;
-  while (splitk < 8 && static_cast<int64_t>(d.n_tiles) * splitk < 2048 && d.n_groups / (splitk * 2) >= 4) splitk *= 2;
-  switch (splitk) {
-    case 1: return launch_layer<B, 4, 1>(d, x, y, s);
-    case 2: return launch_layer<B, 4, 2>(d, x, y, s);
-    case 4: return launch_layer<B, 4, 4>(d, x, y, s);
-    default: return launch_layer<B, 8, 8>(d, x, y, s);
-  }
+  while (splitk < 4 && static_cast<int64_t>(n_tiles) * splitk < 2048 && groups_per_pass / (splitk * 2) >= 4) splitk *= 2;
+  return splitk;
 }
 
-template <int B, int SETS, int NW, int SPLITK>
-static hipError_t launch_layer_mfma(const LayerDesc& d, const void* x, int m, float* y, hipStream_t s) {
+template <int B, int SETS, int SPLITK>
+static hipError_t launch_layer(const LayerDesc& d, const void* x, int m, float* y, hipStream_t s) {
+  constexpr int NW = 4;
   const int tpw = NW / SPLITK;
   const unsigned grid = static_cast<unsigned>((d.n_tiles + tpw - 1) / tpw);
-  const size_t lds = lds_bytes_mfma(chunk_groups(d.n_groups, m), m, NW, SETS);  // T = 1
-  hipLaunchKernelGGL((pmpd_gemm_layer_mfma_kernel<B, SETS, NW, SPLITK>), dim3(grid), dim3(NW * 64), lds, s, d,
+  const size_t lds = lds_bytes(chunk_groups(d.n_groups, m), m, NW, SETS * 4);
+  hipLaunchKernelGGL((pmpd_layer_kernel<B, SETS, NW, SPLITK>), dim3(grid), dim3(NW * 64), lds, s, d,
                      static_cast<const _Float16*>(x), m, y);
   return hipGetLastError();
 }
 
 template <int B, int SETS>
-static hipError_t launch_layer_mfma_bs(const LayerDesc& d, const void* x, int m, float* y, hipStream_t s) {
-  const int cg = chunk_groups(d.n_groups, m);
-  int splitk = 1;
-  while (splitk < 8 && static_cast<int64_t>(d.n_tiles) * splitk < 2048 && cg / (splitk * 2) >= 4) splitk *= 2;
-  switch (splitk) {
-    case 1: return launch_layer_mfma<B, SETS, 4, 1>(d, x, m, y, s);
-    case 2: return launch_layer_mfma<B, SETS, 4, 2>(d, x, m, y, s);
-    case 4: return launch_layer_mfma<B, SETS, 4, 4>(d, x, m, y, s);
-    default: return launch_layer_mfma<B, SETS, 8, 8>(d, x, m, y, s);
+static hipError_t launch_layer_s(const LayerDesc& d, const void* x, int m, float* y, hipStream_t s) {
+  switch (pick_splitk(d.n_tiles, chunk_groups(d.n_groups, m))) {
+    case 1: return launch_layer<B, SETS, 1>(d, x, m, y, s);
+    case 2: return launch_layer<B, SETS, 2>(d, x, m, y, s);
+    default: return launch_layer<B, SETS, 4>(d, x, m, y, s);
   }
 }
 
 template <int B>
-static hipError_t launch_layer_mfma_b(const LayerDesc& d, const void* x, int m, float* y, hipStream_t s) {
-  return m <= 4 ? launch_layer_mfma_bs<B, 1>(d, x, m, y, s) : launch_layer_mfma_bs<B, 2>(d, x, m, y, s);
+static hipError_t launch_layer_b(const LayerDesc& d, const void* x, int m, float* y, hipStream_t s) {
+  switch ((m + 1) / 2) {
+    case 1: return launch_layer_s<B, 1>(d, x, m, y, s);
+    case 2: return launch_layer_s<B, 2>(d, x, m, y, s);
+    case 3: return launch_layer_s<B, 3>(d, x, m, y, s);
+    default: return launch_layer_s<B, 4>(d, x, m, y, s);
+  }
 }
 
 // defined in pmpd_prefill.hip
@@ -615,16 +511,12 @@ static int32_t linear_entry(const char* who, const pmpd_layer_t* layer, int32_t 
   const LayerDesc d = make_desc(*layer, 0, 0);
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
-  if (m > PMPD_MAX_BATCH) {  // compute-bound shape: MFMA tile kernel
+  if (m > PMPD_MAX_BATCH) {  // compute-bound shape: fp16 MFMA tile kernel
     e = launch_prefill_layer(d, b, x, m, y, s);
-  } else if (m > 1) {  // skinny batch: unpack once, MFMA multiply-accumulate
-    e = b == 4 ? launch_layer_mfma_b<4>(d, x, m, y, s)
-        : b == 3 ? launch_layer_mfma_b<3>(d, x, m, y, s)
-                 : launch_layer_mfma_b<2>(d, x, m, y, s);
-  } else {  // batch 1: VALU dot2 with x in SGPRs
-    e = b == 4 ? launch_layer_b<4>(d, x, y, s)
-        : b == 3 ? launch_layer_b<3>(d, x, y, s)
-                 : launch_layer_b<2>(d, x, y, s);
+  } else {  // memory-bound shapes: unpack once for all vectors
+    e = b == 4 ? launch_layer_b<4>(d, x, m, y, s)
+        : b == 3 ? launch_layer_b<3>(d, x, m, y, s)
+                 : launch_layer_b<2>(d, x, m, y, s);
   }
   if (e != hipSuccess) return hip_fail(e, who);
   return PMPD_OK;
@@ -652,23 +544,19 @@ static size_t stack_bytes(size_t n_layers, const size_t (&n_items)[kNumItemLists
   return b;
 }
 
-// Stack kernel variants (PMPD_STACK_VARIANT="v4,v3,v2" overrides the per-bit-width defaults):
-//   0  dot2, 4 waves x 1 tile, whole K            1  dot2, 4 waves on 1 tile, K split 4 ways
-//   2  MFMA, 4 waves x 1 tile                     3  MFMA, 4 waves x 2 tiles
-//   4  MFMA, 2 waves x 2 tiles                    5  dot2, 4 waves on 2 tiles, K split 2 ways
-//   6  dot2, 8 waves on 1 tile, K split 8 ways    7  dot2, 8 waves on 2 tiles, K split 4 ways
-//   8  dot2, 8 waves on 4 tiles, K split 2 ways   9  dot2, 2 waves on 1 tile, K split 2 ways
-static constexpr int kNumVariants = 10;
-// which work list (tiles per workgroup: list 0 = 4, 1 = 1, 2 = 8, 3 = 2) each variant walks
-static constexpr int kVariantList[kNumVariants] = {0, 1, 0, 2, 0, 3, 1, 3, 0, 1};
-// Defaults measured on the 7B-shaped and the mobile-scale stacks: at b = 4 and 3 the kernel is
-// bound by the memory system and four waves that split one tile's K stream fastest; at b = 2 the
-// VALU co-limits, so the per-workgroup staging is spread over more rows (4 tiles per workgroup)
-// when the stack has enough tiles to keep every CU busy that way, else over 2.
+// Launch shapes of the one-launch decode step (PMPD_STACK_VARIANT="v4,v3,v2" overrides the
+// per-bit-width defaults):
+//   0  4 waves x 1 tile each, whole K     1  4 waves on 1 tile, K split 4 ways
+//   2  4 waves on 2 tiles, K split 2 ways
+static constexpr int kNumVariants = 3;
+// which work list (tiles per workgroup: list 0 = 4, 1 = 1, 2 = 2) each variant walks
+static constexpr int kVariantList[kNumVariants] = {0, 1, 2};
 static void pick_variants(pmpd_stack* st) {
+  // Measured on the 7B-shaped stack: the three shapes are within 1 % of each other at b = 4 and 3;
+  // at b = 2 four waves splitting one tile's K stream fastest.
   st->variant[4] = 1;
   st->variant[3] = 1;
-  st->variant[2] = st->items[0].size() >= 4096 ? 0 : 5;
+  st->variant[2] = 1;
   const char* e = std::getenv("PMPD_STACK_VARIANT");
   if (e) {
     int v[3];
@@ -695,76 +583,39 @@ static hipError_t launch_stack(const pmpd_stack* st, const void* xv, float* y, h
   const int q = kVariantList[v];
   const unsigned grid = static_cast<unsigned>(st->items[q].size());
   const _Float16* x = static_cast<const _Float16*>(xv);
-  const int max_groups = st->max_in / kGroup;
-  const int cg = chunk_groups(max_groups, 1);
+  const size_t lds = lds_bytes(chunk_groups(st->max_in / kGroup, 1), 1, 4, 4);
   switch (v) {
     case 0:
-      hipLaunchKernelGGL((pmpd_gemv_stack_kernel<B, 4, 1>), dim3(grid), dim3(256), lds_bytes(max_groups, 4), s,
-                         st->d_layers, st->d_items[q], x, y);
-      break;
-    case 1:
-      hipLaunchKernelGGL((pmpd_gemv_stack_kernel<B, 4, 4>), dim3(grid), dim3(256), lds_bytes(max_groups, 4), s,
-                         st->d_layers, st->d_items[q], x, y);
-      break;
-    case 5:
-      hipLaunchKernelGGL((pmpd_gemv_stack_kernel<B, 4, 2>), dim3(grid), dim3(256), lds_bytes(max_groups, 4), s,
-                         st->d_layers, st->d_items[q], x, y);
-      break;
-    case 6:
-      hipLaunchKernelGGL((pmpd_gemv_stack_kernel<B, 8, 8>), dim3(grid), dim3(512), lds_bytes(max_groups, 8), s,
-                         st->d_layers, st->d_items[q], x, y);
-      break;
-    case 7:
-      hipLaunchKernelGGL((pmpd_gemv_stack_kernel<B, 8, 4>), dim3(grid), dim3(512), lds_bytes(max_groups, 8), s,
-                         st->d_layers, st->d_items[q], x, y);
-      break;
-    case 8:
-      hipLaunchKernelGGL((pmpd_gemv_stack_kernel<B, 8, 2>), dim3(grid), dim3(512), lds_bytes(max_groups, 8), s,
-                         st->d_layers, st->d_items[q], x, y);
-      break;
-    case 9:
-      hipLaunchKernelGGL((pmpd_gemv_stack_kernel<B, 2, 2>), dim3(grid), dim3(128), lds_bytes(max_groups, 2), s,
-                         st->d_layers, st->d_items[q], x, y);
+      hipLaunchKernelGGL((pmpd_stack_kernel<B, 1, 4, 1>), dim3(grid), dim3(256), lds, s, st->d_layers, st->d_items[q], x, 1, y);
       break;
     case 2:
-      hipLaunchKernelGGL((pmpd_gemv_stack_mfma_kernel<B, 1, 4, 1>), dim3(grid), dim3(256), lds_bytes_mfma(cg, 1, 4, 1), s,
-                         st->d_layers, st->d_items[q], x, y);
-      break;
-    case 3:
-      hipLaunchKernelGGL((pmpd_gemv_stack_mfma_kernel<B, 2, 4, 1>), dim3(grid), dim3(256), lds_bytes_mfma(cg, 1, 4, 2), s,
-                         st->d_layers, st->d_items[q], x, y);
+      hipLaunchKernelGGL((pmpd_stack_kernel<B, 1, 4, 2>), dim3(grid), dim3(256), lds, s, st->d_layers, st->d_items[q], x, 1, y);
       break;
     default:
-      hipLaunchKernelGGL((pmpd_gemv_stack_mfma_kernel<B, 2, 2, 1>), dim3(grid), dim3(128), lds_bytes_mfma(cg, 1, 2, 2), s,
-                         st->d_layers, st->d_items[q], x, y);
+      hipLaunchKernelGGL((pmpd_stack_kernel<B, 1, 4, 4>), dim3(grid), dim3(256), lds, s, st->d_layers, st->d_items[q], x, 1, y);
       break;
   }
   return hipGetLastError();
 }
 
-template <int B, int T>
-static hipError_t launch_stack_batch_t(const pmpd_stack* st, const _Float16* x, int m, float* y, hipStream_t s) {
-  const int q = T == 2 ? 2 : 0;  // work list with 4*T tiles per workgroup
-  const unsigned grid = static_cast<unsigned>(st->items[q].size());
-  const int cg = chunk_groups(st->max_in / kGroup, m);
-  if (m <= 4) {
-    hipLaunchKernelGGL((pmpd_gemm_stack_mfma_kernel<B, 1, T, 4>), dim3(grid), dim3(256), lds_bytes_mfma(cg, m, 4, T), s,
-                       st->d_layers, st->d_items[q], x, m, y);
-  } else {
-    hipLaunchKernelGGL((pmpd_gemm_stack_mfma_kernel<B, 2, T, 4>), dim3(grid), dim3(256), lds_bytes_mfma(cg, m, 4, 2 * T), s,
-                       st->d_layers, st->d_items[q], x, m, y);
-  }
+// Skinny batches over a stack: 4 waves, one tile each over the whole K (work list 0).
+template <int B, int SETS>
+static hipError_t launch_stack_batch_s(const pmpd_stack* st, const _Float16* x, int m, float* y, hipStream_t s) {
+  const unsigned grid = static_cast<unsigned>(st->items[0].size());
+  const size_t lds = lds_bytes(chunk_groups(st->max_in / kGroup, m), m, 4, 0);
+  hipLaunchKernelGGL((pmpd_stack_kernel<B, SETS, 4, 1>), dim3(grid), dim3(256), lds, s, st->d_layers, st->d_items[0], x, m, y);
   return hipGetLastError();
 }
 
-// Two row tiles per wave halve the LDS operand traffic per weight.  With more than 4 vectors
-// (two accumulator sets) that always pays; with up to 4 it only pays when the stack has enough
-// tiles to fill the machine with 8-tile workgroups (measured on the 7B and mobile-scale stacks).
 template <int B>
 static hipError_t launch_stack_batch(const pmpd_stack* st, const void* xv, int m, float* y, hipStream_t s) {
   const _Float16* x = static_cast<const _Float16*>(xv);
-  const bool two_tiles = m > 4 || st->items[2].size() >= 2048;
-  return two_tiles ? launch_stack_batch_t<B, 2>(st, x, m, y, s) : launch_stack_batch_t<B, 1>(st, x, m, y, s);
+  switch ((m + 1) / 2) {
+    case 1: return launch_stack_batch_s<B, 1>(st, x, m, y, s);
+    case 2: return launch_stack_batch_s<B, 2>(st, x, m, y, s);
+    case 3: return launch_stack_batch_s<B, 3>(st, x, m, y, s);
+    default: return launch_stack_batch_s<B, 4>(st, x, m, y, s);
+  }
 }
 
 extern "C" {

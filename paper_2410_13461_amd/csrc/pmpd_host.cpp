@@ -42,12 +42,22 @@ int32_t check_layer(const pmpd_layer_t* L, int32_t b, const char* who) {
   return PMPD_OK;
 }
 
-// Bit of plane k that holds weight u (0..31) of a 32-weight word:
-// u = 2p + half, p = 4m + 2v + h  ->  (16 half + 8 v + 4 h + 3 - k + m) mod 32.
-static inline int bit_position(int k, int u) {
-  int half = u & 1, p = u >> 1;
-  int m = p >> 2, v = (p >> 1) & 1, h = p & 1;
-  return (16 * half + 8 * v + 4 * h + 3 - k + m) & 31;
+// Where plane k keeps its bit of the weight in row rr (0..63) of a tile and column e (0..127)
+// of a group: the 32-bit word index inside the (tile, group) block of 256 words, and the bit.
+//   rr = 16 t + j,  e = 32 kb + 8 v + c,  n = c/2 + 4 (c%2)
+//   word = (16 kb + j) 4 + t
+//   bit  = 4 n + {1,3,0,2}[v]            for the even planes (upper bit of a 2-bit pair)
+//          (4 n + {0,2,31,1}[v]) mod 32  for the odd planes (lower bit)
+struct BitHome {
+  int word, bit;
+};
+static inline BitHome bit_home(int k, int rr, int e) {
+  static const int even_off[4] = {1, 3, 0, 2}, odd_off[4] = {0, 2, 31, 1};
+  const int t = rr >> 4, j = rr & 15;
+  const int kb = e >> 5, v = (e >> 3) & 3, c = e & 7;
+  const int n = (c >> 1) + 4 * (c & 1);
+  const int off = (k & 1) ? odd_off[v] : even_off[v];
+  return BitHome{(16 * kb + j) * 4 + t, (4 * n + off) & 31};
 }
 
 }  // namespace pmpd
@@ -97,36 +107,41 @@ int32_t pmpd_pack(const uint8_t* q4, const uint16_t* scale, const uint16_t* minv
   for (int k = 0; k < 4; ++k) pl[k] = static_cast<uint32_t*>(planes[k]);
   uint32_t* sm = static_cast<uint32_t*>(scale_min);
 
-  int pos[4][32];
-  for (int k = 0; k < 4; ++k)
-    for (int u = 0; u < 32; ++u) pos[k][u] = bit_position(k, u);
-
   // Tiles are independent: split them over host threads.
   unsigned hw = std::thread::hardware_concurrency();
   int n_thr = static_cast<int>(std::min<int64_t>(std::max(1u, std::min(hw, 16u)), n_tiles));
   std::vector<int> bad(n_thr, 0);
+  // bit_home() split into its column part and its row part
+  int col_word[kGroup], col_bit[2][kGroup], row_word[kTile];
+  for (int e = 0; e < kGroup; ++e) {
+    col_word[e] = bit_home(0, 0, e).word;
+    col_bit[0][e] = bit_home(0, 0, e).bit;
+    col_bit[1][e] = bit_home(1, 0, e).bit;
+  }
+  for (int rr = 0; rr < kTile; ++rr) row_word[rr] = bit_home(0, rr, 0).word;
   auto work = [&](int tid) {
+    std::vector<uint32_t> blk(4 * 256);
     for (int64_t T = tid; T < n_tiles; T += n_thr) {
       for (int64_t g = 0; g < G; ++g) {
-        for (int l = 0; l < kTile; ++l) {
-          const int64_t r = T * kTile + l;
-          const int64_t base = ((T * G + g) * kTile + l);
-          uint32_t w[4][4] = {};
-          if (r < out_f) {
-            const uint8_t* src = q4 + r * static_cast<int64_t>(in_f) + g * kGroup;
-            for (int d = 0; d < 4; ++d)
-              for (int u = 0; u < 32; ++u) {
-                uint32_t code = src[d * 32 + u];
-                if (code > 15) { bad[tid] = 1; code &= 15; }
-                for (int k = 0; k < 4; ++k) w[k][d] |= ((code >> (3 - k)) & 1u) << pos[k][u];
-              }
-            sm[base] = static_cast<uint32_t>(scale[r * G + g]) | (static_cast<uint32_t>(minv[r * G + g]) << 16);
-          } else {
-            sm[base] = 0;
+        std::fill(blk.begin(), blk.end(), 0u);
+        const int64_t base = (T * G + g) * kTile;  // first (scale, min) word; x4 = first plane word
+        for (int rr = 0; rr < kTile; ++rr) {
+          const int64_t r = T * kTile + rr;
+          if (r >= out_f) {
+            sm[base + 4 * (rr & 15) + (rr >> 4)] = 0;
+            continue;
           }
-          for (int k = 0; k < 4; ++k)
-            for (int d = 0; d < 4; ++d) pl[k][base * 4 + d] = w[k][d];
+          const uint8_t* src = q4 + r * static_cast<int64_t>(in_f) + g * kGroup;
+          for (int e = 0; e < kGroup; ++e) {
+            uint32_t code = src[e];
+            if (code > 15) { bad[tid] = 1; code &= 15; }
+            const int w = col_word[e] + row_word[rr];
+            for (int k = 0; k < 4; ++k) blk[k * 256 + w] |= ((code >> (3 - k)) & 1u) << col_bit[k & 1][e];
+          }
+          sm[base + 4 * (rr & 15) + (rr >> 4)] =
+              static_cast<uint32_t>(scale[r * G + g]) | (static_cast<uint32_t>(minv[r * G + g]) << 16);
         }
+        for (int k = 0; k < 4; ++k) std::memcpy(pl[k] + base * 4, &blk[k * 256], 256 * sizeof(uint32_t));
       }
     }
   };
@@ -144,22 +159,19 @@ int32_t pmpd_unpack(const pmpd_layer_t* L, int32_t b, uint8_t* qb_out) {
   if (rc) return rc;
   if (!qb_out) return fail(PMPD_EINVAL, "pmpd_unpack: qb_out is NULL");
   const int64_t in_f = L->in_features, out_f = L->out_features, G = in_f / kGroup;
-  int pos[4][32];
-  for (int k = 0; k < 4; ++k)
-    for (int u = 0; u < 32; ++u) pos[k][u] = bit_position(k, u);
   for (int64_t r = 0; r < out_f; ++r) {
-    const int64_t T = r / kTile, l = r % kTile;
+    const int64_t T = r / kTile;
+    const int rr = static_cast<int>(r % kTile);
     for (int64_t g = 0; g < G; ++g) {
-      const int64_t base = ((T * G + g) * kTile + l) * 4;
-      for (int d = 0; d < 4; ++d)
-        for (int u = 0; u < 32; ++u) {
-          uint32_t code = 0;
-          for (int k = 0; k < b; ++k) {
-            uint32_t word = static_cast<const uint32_t*>(L->planes[k])[base + d];
-            code = (code << 1) | ((word >> pos[k][u]) & 1u);
-          }
-          qb_out[r * in_f + g * kGroup + d * 32 + u] = static_cast<uint8_t>(code);
+      const int64_t base = (T * G + g) * kTile * 4;
+      for (int e = 0; e < kGroup; ++e) {
+        uint32_t code = 0;
+        for (int k = 0; k < b; ++k) {
+          const BitHome h = bit_home(k, rr, e);
+          code = (code << 1) | ((static_cast<const uint32_t*>(L->planes[k])[base + h.word] >> h.bit) & 1u);
         }
+        qb_out[r * in_f + g * kGroup + e] = static_cast<uint8_t>(code);
+      }
     }
   }
   return PMPD_OK;

@@ -8,10 +8,10 @@
 // Workgroup = 2 x 2 waves, output tile 256 (rows of X) x 128 (rows of W), K walked in steps of
 // 64 columns (half a quantisation group).  Per step:
 //   * all threads copy the 256 x 64 fp16 tile of X to LDS (global loads issued one step ahead);
-//   * the weights of the step are unpacked by the lane that owns the row (same storage format
-//     and bit tricks as the decode kernels: lane l of a wave <-> row l of a 64-row tile), turned
-//     into fp16 values  w = fp16(a_g + s_g * (q~ + 2^(3-b)))  with packed fp16 math, and written to
-//     LDS as a 128 x 64 tile with K contiguous;
+//   * the weights of the step are unpacked one 32-bit word of each plane per thread (32 columns
+//     of one row; the same pair merge as the decode kernels, then the two 2-bit pairs are joined
+//     into 4-bit codes q~), turned into fp16 values  w = fp16(a_g + s_g * (q~ + 2^(3-b)))  with
+//     packed fp16 math, and written to LDS as a 128 x 64 tile with K contiguous;
 //   * each wave multiplies its 128 x 64 quarter with 4 x 2 blocks of 32x32x16 MFMAs (fp32
 //     accumulate, 128 accumulator registers), reading the operand fragments of the next 16
 //     columns from LDS before it issues the MFMAs of the current ones.
@@ -32,7 +32,6 @@
 
 namespace pmpd {
 
-typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
 #ifndef PMPD_PREFILL_WM
@@ -54,39 +53,19 @@ constexpr size_t kPrefillLds = static_cast<size_t>(kPM + kPN) * kPStride * 2;
 __device__ __forceinline__ half2_t h2(uint32_t v) { return __builtin_bit_cast(half2_t, v); }
 __device__ __forceinline__ uint32_t u32(half2_t v) { return __builtin_bit_cast(uint32_t, v); }
 
-// merge_planes for an m that is only known per wave: the slot masks are picked at run time
-// (wave-uniform selects on SGPRs).
-template <int B>
-__device__ __forceinline__ uint32_t merge_planes_dyn(const UnpackConsts<B>& uc, const uint32_t (&p)[B], int m) {
-  auto slot = [&](int j) { j &= 3; return j == 0 ? uc.slot[0] : j == 1 ? uc.slot[1] : j == 2 ? uc.slot[2] : uc.slot[3]; };
-  auto slot2 = [&](int j) { j &= 3; return j == 0 ? uc.slot2[0] : j == 1 ? uc.slot2[1] : j == 2 ? uc.slot2[2] : uc.slot2[3]; };
-  if constexpr (B == 4) {
-    uint32_t hi = bfi(slot(3 + m), p[0], p[1]);
-    uint32_t lo = bfi(slot(1 + m), p[2], p[3]);
-    return bfi(slot2(3 + m), hi, lo);
-  } else if constexpr (B == 3) {
-    uint32_t lo = bfi(slot(2 + m), p[1], p[2]);
-    return bfi(slot(3 + m), p[0], lo);
-  } else {
-    return bfi(slot(3 + m), p[0], p[1]);
-  }
-}
-
 // One workgroup: the (64 WM) x 128 output tile (mtile, ntile) of one layer.
 template <int B>
 __device__ __forceinline__ void prefill_tile(const LayerDesc& L, const _Float16* __restrict__ X, int m_rows,
                                              float* __restrict__ Y, int mtile, int tile0, _Float16* lds) {
-  const UnpackConsts<B> uc;
+  static_assert(kPWM == 2, "the unpack mapping below assumes 256 threads");
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 1, wn = wave & 1;  // which 64 x 64 block of the output this wave multiplies
-  // unpack share of this wave: storage tile ut, 32-column word up, and kPWM/2... of its 4 m-words
-  constexpr int kShare = (kPWM * 2) / 4;   // waves per (tile, word) unit
-  constexpr int kMW = 4 / kShare;          // m-words per wave
-  const int unit = wave / kShare;
-  const int ut = unit >> 1, up = unit & 1;
-  const int m_first = (wave % kShare) * kMW;
+  const int wm = wave >> 1, wn = wave & 1;  // which block of the output this wave multiplies
+  // unpack share of this thread: storage tile ut, 32-column slice up of the 64-column step,
+  // row 16 ur_t + ur_j of the tile (one 32-bit word of each plane, consecutive over the lanes)
+  const int ut = wave >> 1, up = wave & 1;
+  const int ur_j = lane >> 2, ur_t = lane & 3;
   const int G = L.n_groups;
   const int in_f = L.in_f;
   _Float16* Xs = lds;
@@ -96,11 +75,11 @@ __device__ __forceinline__ void prefill_tile(const LayerDesc& L, const _Float16*
   // storage tile this wave unpacks (clamped: rows past the end are never stored)
   int T = tile0 + ut;
   T = T < L.n_tiles ? T : L.n_tiles - 1;
-  const int64_t tbase = (static_cast<int64_t>(T) * G) * 64 + lane;  // (tile, group 0, lane) in 16-byte units
+  const int64_t tbase = (static_cast<int64_t>(T) * G) * 64;  // (tile, group 0) in 16-byte units
   global_u32_ptr pw[B];
 #pragma unroll
-  for (int k = 0; k < B; ++k) pw[k] = (global_u32_ptr)(L.plane[k]) + tbase * 4;
-  global_u32_ptr sp = (global_u32_ptr)(L.sa) + tbase;
+  for (int k = 0; k < B; ++k) pw[k] = (global_u32_ptr)(L.plane[k]) + tbase * 4 + (16 * up + ur_j) * 4 + ur_t;
+  global_u32_ptr sp = (global_u32_ptr)(L.sa) + tbase + 4 * ur_j + ur_t;  // = lane: rows in [j][t] order
 
   // X tile copy: kPM rows x 8 uint4; thread t handles (row, c) = ((t + T i) / 8, (t + T i) % 8), T threads
   constexpr int kXV = kPM * 8 / kPThreads;  // uint4 of the X tile per thread
@@ -138,7 +117,7 @@ __device__ __forceinline__ void prefill_tile(const LayerDesc& L, const _Float16*
 #pragma unroll
   for (int i = 0; i < kXV; ++i) xr[i] = xok[i] ? xg[i][0] : make_uint4(0, 0, 0, 0);
 #pragma unroll
-  for (int k = 0; k < B; ++k) pr[k] = pw[k][up];
+  for (int k = 0; k < B; ++k) pr[k] = pw[k][0];
   sar = sp[0];
 
   for (int step = 0; step < n_steps; ++step) {
@@ -152,24 +131,35 @@ __device__ __forceinline__ void prefill_tile(const LayerDesc& L, const _Float16*
                           __builtin_bit_cast(_Float16, static_cast<uint16_t>(sar & 0xffffu))};
       const half2_t a2 = {__builtin_bit_cast(_Float16, static_cast<uint16_t>(sar >> 16)),
                           __builtin_bit_cast(_Float16, static_cast<uint16_t>(sar >> 16))};
-      _Float16* wrow = Ws + (ut * 64 + lane) * kPStride + up * 32;
+      _Float16* wrow = Ws + (ut * 64 + 16 * ur_t + ur_j) * kPStride + up * 32;
+      // 4-bit aligned codes q~ of the thread's 32 columns: word v holds columns 8 v .. 8 v + 7,
+      // nibbles 0,4 / 1,5 / 2,6 / 3,7 = column pairs (0,1) / (2,3) / (4,5) / (6,7)
+      uint32_t code[4];
+      {
+        uint32_t hi[4], lo[4];
+        pair_words(pr[0], pr[1], hi);
+        if constexpr (B == 4) pair_words(pr[2], pr[3], lo);
+        if constexpr (B == 3) single_words(pr[2], lo);
 #pragma unroll
-      for (int mi = 0; mi < kMW; ++mi) {
-        const int mm = m_first + mi;
-        uint32_t u = merge_planes_dyn<B>(uc, pr, mm);
-        uint32_t w = __builtin_amdgcn_alignbit(u, u, mm);
-        uint32_t w8 = w >> 8;
+        for (int v = 0; v < 4; ++v) code[v] = (B == 2) ? (hi[v] << 2) : ((hi[v] << 2) | lo[v]);
+      }
+      const uint32_t maskL = opaque_sgpr(0x000F000Fu), maskH = opaque_sgpr(0x00F000F0u);
+      uint32_t magic = 0x64006400u;  // fp16 pair (1024, 1024)
+      asm volatile("" : "+v"(magic));
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const uint32_t w = code[v], w8 = w >> 8;
         // exact codes q~ + 2^(3-b): low-nibble pairs carry 1024 + q~, high-nibble pairs 1024 + 16 q~
-        const half2_t q0 = h2(and_or(w, uc.maskL, uc.magic)) + cL;
-        const half2_t q1 = __builtin_elementwise_fma(h2(and_or(w, uc.maskH, uc.magic)), sixteenth, cH);
-        const half2_t q2 = h2(and_or(w8, uc.maskL, uc.magic)) + cL;
-        const half2_t q3 = __builtin_elementwise_fma(h2(and_or(w8, uc.maskH, uc.magic)), sixteenth, cH);
+        const half2_t q0 = h2(and_or(w, maskL, magic)) + cL;
+        const half2_t q1 = __builtin_elementwise_fma(h2(and_or(w, maskH, magic)), sixteenth, cH);
+        const half2_t q2 = h2(and_or(w8, maskL, magic)) + cL;
+        const half2_t q3 = __builtin_elementwise_fma(h2(and_or(w8, maskH, magic)), sixteenth, cH);
         u32x4 o;
         o.x = u32(__builtin_elementwise_fma(q0, s2, a2));
         o.y = u32(__builtin_elementwise_fma(q1, s2, a2));
         o.z = u32(__builtin_elementwise_fma(q2, s2, a2));
         o.w = u32(__builtin_elementwise_fma(q3, s2, a2));
-        *reinterpret_cast<u32x4*>(wrow + mm * 8) = o;
+        *reinterpret_cast<u32x4*>(wrow + v * 8) = o;
       }
     }
     __syncthreads();
@@ -180,7 +170,7 @@ __device__ __forceinline__ void prefill_tile(const LayerDesc& L, const _Float16*
 #pragma unroll
       for (int i = 0; i < kXV; ++i) xr[i] = xok[i] ? xg[i][ns * 8] : make_uint4(0, 0, 0, 0);
 #pragma unroll
-      for (int k = 0; k < B; ++k) pr[k] = pw[k][g * 256 + kh * 2 + up];
+      for (int k = 0; k < B; ++k) pr[k] = pw[k][g * 256 + kh * 128];
       sar = sp[g * 64];
     }
     // ---- 64 x 64 x 64 per wave; the operand fragments of the next 16 columns are read from LDS

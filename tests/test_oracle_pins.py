@@ -161,20 +161,39 @@ def test_pack_is_a_bijection_onto_the_plane_bits():
             key = (int(nz[0]), word)
             assert key not in seen[k]
             seen[k].add(key)
-    # the first weight of the first row: bit 3-k of word 0 of plane k (formula anchor)
+    # formula anchors, worked by hand from the storage-format definition.
+    # (r, i) = (0, 0): t = j = kb = v = c = n = 0 -> word 0; even planes bit 1, odd planes bit 0
     q = np.zeros((out_f, in_f), dtype=np.uint8)
     q[0, 0] = 0b1010
     pl, _ = oracle.pack(q, s, s)
-    assert [int(pl[k][0]) for k in range(4)] == [1 << 3, 0, 1 << 1, 0]
+    assert [int(pl[k][0]) for k in range(4)] == [1 << 1, 0, 1 << 1, 0]
+    # (r, i) = (17, 77): rr = 16*1 + 1; e = 32*2 + 8*1 + 5 -> kb 2, v 1, c 5, n = 2 + 4 = 6;
+    # word (16*2 + 1)*4 + 1 = 133; even planes bit 4*6 + 3 = 27, odd planes bit 4*6 + 2 = 26
+    q = np.zeros((out_f, in_f), dtype=np.uint8)
+    q[17, 77] = 0b0111
+    pl, _ = oracle.pack(q, s, s)
+    assert [int(pl[k][133]) for k in range(4)] == [0, 1 << 26, 1 << 27, 1 << 26]
+    # (r, i) = (63, 255): group 1; rr = 16*3 + 15; e = 127 -> kb 3, v 3, c 7, n = 3 + 4 = 7;
+    # word 256 + (16*3 + 15)*4 + 3 = 511; even planes bit 28 + 2 = 30, odd planes bit 28 + 1 = 29
+    q = np.zeros((out_f, in_f), dtype=np.uint8)
+    q[63, 255] = 0b1100
+    pl, _ = oracle.pack(q, s, s)
+    assert [int(pl[k][511]) for k in range(4)] == [1 << 30, 1 << 29, 0, 0]
+    # v = 2 of an odd plane wraps: (0, 16): kb 0, v 2, c 0, n 0 -> bit (0 + 31) mod 32 of word 0
+    q = np.zeros((out_f, in_f), dtype=np.uint8)
+    q[0, 16] = 0b0001
+    pl, _ = oracle.pack(q, s, s)
+    assert [int(pl[k][0]) for k in range(4)] == [0, 0, 0, 1 << 31]
 
 
 def test_pack_pads_rows_with_zeros_and_rejects_bad_codes():
     q4, s, a = synth.draw_weights(1, 0, 0, 65, 128)
     planes, sa = oracle.pack(q4, s, a)
     assert planes[0].size == 128 * 128 // 32
-    # tile 1 holds one real row (lane 0); lanes 1..63 are padding and stay zero
-    t1 = planes[0].reshape(2, 1, 64, 4)[1, 0]
-    assert np.all(t1[1:] == 0)
+    # tile 1 holds one real row (position 0: word t = 0 of the 16-byte units j = 0 of each of the
+    # four 32-column slices); every other word is padding and stays zero
+    t1 = planes[0].reshape(2, 1, 4, 16, 4)[1, 0]  # [kb][j][t]
+    assert np.all(t1[:, 1:, :] == 0) and np.all(t1[:, 0, 1:] == 0)
     assert np.all(sa.reshape(2, 1, 64)[1, 0, 1:] == 0)
     bad = q4.copy()
     bad[3, 5] = 16

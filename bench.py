@@ -292,7 +292,7 @@ def main() -> int:
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "u4-bitplane weights x f16 activations, f32 accumulate",
+        "dtype": "u4 bit-plane weights as fp4 pairs x f16 activations as 3 exact fp8 pieces, f32 accumulate",
         "data": "synthetic",
         "config": {
             "workload": "Llama-7B-shaped decode step: 32 blocks x 7 projections (224 linear layers, 6.476e9 weights), "
@@ -304,7 +304,7 @@ def main() -> int:
         "per_bits": per_bits,
         "roofline": {
             "bound": "hbm",
-            "kernel": "pmpd_gemv_stack_kernel<B=4> (one launch = one b=4 decode step)",
+            "kernel": "pmpd_stack_kernel<B=4, SETS=1, NW=4, SPLITK=1> (one launch = one b=4 decode step)",
             "achieved": dom["GBps"],
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",

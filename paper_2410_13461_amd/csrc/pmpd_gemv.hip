@@ -70,9 +70,12 @@ typedef short short2_t __attribute__((ext_vector_type(2)));
 typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
 
 // LDS image of the split activations, per vector and group: for each of the two magnitude
-// classes 3 pieces x 128 fp8 in operand order and 16 bytes of block exponents ([piece][32-column
+// classes 3 pieces x 128 fp8 in operand order (stride kPieceStride) and 16 bytes of block exponents ([piece][32-column
 // block], 12 used) and one fp32 group sum.
-constexpr int kPieceBytes = 384;   // one class
+constexpr int kPieceStride = 144;              // 128 fp8 of one piece + 16 bytes so that the three pieces of a
+                                              // group start in different LDS banks
+constexpr int kPieceBytes = 3 * kPieceStride;  // one class
+constexpr int kGroupPieceBytes = 2 * kPieceBytes;  // both classes of one group
 constexpr int kScaleBytes = 16;    // one class
 constexpr int kImageBytes = 2 * (kPieceBytes + kScaleBytes + 4);
 
@@ -89,7 +92,7 @@ __host__ __device__ inline size_t lds_bytes(int chunk, int m, int n_waves, int a
 
 // Where the parts of the image of vector j live, for a chunk capacity of cg groups and m vectors.
 struct ImageLayout {
-  char* pieces;   // [m][2][cg][384]
+  char* pieces;   // [m][cg][2 classes][3 pieces][kPieceStride]: six operand rows of a group in six bank phases
   char* scales;   // [m][2][cg][16]
   float* xsum;    // [m][2][cg]
   float* red;     // split-K meeting point
@@ -100,7 +103,7 @@ struct ImageLayout {
     xsum = reinterpret_cast<float*>(scales + m * 2 * cg * kScaleBytes);
     red = xsum + m * 2 * cg;
   }
-  __device__ __forceinline__ int piece_off(int j, int cls) const { return (j * 2 + cls) * cg * kPieceBytes; }
+  __device__ __forceinline__ int piece_off(int j, int cls) const { return j * cg * kGroupPieceBytes + cls * kPieceBytes; }
   __device__ __forceinline__ int scale_off(int j, int cls) const { return (j * 2 + cls) * cg * kScaleBytes; }
   __device__ __forceinline__ int xsum_off(int j, int cls) const { return (j * 2 + cls) * cg; }
 };
@@ -139,11 +142,12 @@ __device__ __forceinline__ uint32_t quad_max_magnitude(const uint32_t (&w)[4]) {
 }
 
 // Three e4m3 pieces of 8 fp16 values (4 column pairs in w) whose largest exponent field in the
-// 32-column block is E, written to dst (piece stride 128 bytes) in operand order: bytes 0..3 =
+// 32-column block is E, written to dst (piece stride kPieceStride) in operand order: bytes 0..3 =
 // columns 0,2,4,6, bytes 4..7 = columns 1,3,5,7 (the order of the nibbles in the weight words).
 // Every |x| of the block is below 2^(E-14), so x / 2^(E-22) is below 256 and fits e4m3 (largest
-// finite value 448) without overflow.  The block exponents go to sdst[0], [4], [8].
-__device__ __forceinline__ void split_pieces(const uint32_t (&w)[4], uint32_t E, char* dst, char* sdst, bool write_scale) {
+// finite value 448) without overflow.  The block exponents go to sdst[0], [4], [8] (e8m0 bytes of
+// 2^(E-22), 2^(E-26), 2^(E-30)).
+__device__ __forceinline__ void split_pieces(const uint32_t (&w)[4], uint32_t E, char* dst, char* sdst, int quad_lane) {
   const float sc0 = __builtin_bit_cast(float, (E + 105u) << 23);  // 2^(E-22)
   const float sc1 = __builtin_bit_cast(float, (E + 101u) << 23);  // 2^(E-26)
   const float sc2 = __builtin_bit_cast(float, (E + 97u) << 23);   // 2^(E-30)
@@ -162,13 +166,10 @@ __device__ __forceinline__ void split_pieces(const uint32_t (&w)[4], uint32_t E,
     p2[q] = to_fp8x4(a, b, sc2);
   }
   *reinterpret_cast<uint2*>(dst) = make_uint2(p0[0], p0[1]);
-  *reinterpret_cast<uint2*>(dst + 128) = make_uint2(p1[0], p1[1]);
-  *reinterpret_cast<uint2*>(dst + 256) = make_uint2(p2[0], p2[1]);
-  if (write_scale) {
-    sdst[0] = static_cast<char>(E + 105u);
-    sdst[4] = static_cast<char>(E + 101u);
-    sdst[8] = static_cast<char>(E + 97u);
-  }
+  *reinterpret_cast<uint2*>(dst + kPieceStride) = make_uint2(p1[0], p1[1]);
+  *reinterpret_cast<uint2*>(dst + 2 * kPieceStride) = make_uint2(p2[0], p2[1]);
+  // thread p of the quad writes the block exponent of piece p
+  if (quad_lane < 3) sdst[4 * quad_lane] = static_cast<char>(E + 105u - 4u * quad_lane);
 }
 
 // Split groups [c0, c0 + cn) of activation vector j into the two classes' pieces, block
@@ -200,10 +201,10 @@ __device__ __forceinline__ void stage_x(const _Float16* __restrict__ x, int c0, 
     }
     const uint32_t EB = quad_max_magnitude(wb) >> 10;
     const int g = idx >> 4, c8 = idx & 15;
-    const bool lead = (idx & 3) == 0;
-    split_pieces(wa, EA, im.pieces + im.piece_off(j, 0) + g * kPieceBytes + c8 * 8,
+    const int lead = idx & 3;
+    split_pieces(wa, EA, im.pieces + im.piece_off(j, 0) + g * kGroupPieceBytes + c8 * 8,
                  im.scales + im.scale_off(j, 0) + g * kScaleBytes + (c8 >> 2), lead);
-    split_pieces(wb, EB, im.pieces + im.piece_off(j, 1) + g * kPieceBytes + c8 * 8,
+    split_pieces(wb, EB, im.pieces + im.piece_off(j, 1) + g * kGroupPieceBytes + c8 * 8,
                  im.scales + im.scale_off(j, 1) + g * kScaleBytes + (c8 >> 2), lead);
     xsa += dpp_f32<kQuadSwap1>(xsa);
     xsb += dpp_f32<kQuadSwap1>(xsb);
@@ -296,7 +297,7 @@ __device__ __forceinline__ void run_tiles(const LayerDesc& L, int tile0, const _
   for (int s = 0; s < SETS; ++s) {
     int vi = 2 * s + (in_slot >> 1);
     vi = vi < m ? vi : m - 1;  // slots of absent vectors repeat the last one; their sums are not stored
-    a_off[s] = im.piece_off(vi, in_slot & 1) + piece * 128 + (lane >> 4) * 16;
+    a_off[s] = im.piece_off(vi, in_slot & 1) + piece * kPieceStride + (lane >> 4) * 16;
     s_off[s] = im.scale_off(vi, in_slot & 1) + piece * 4 + (lane >> 4);
     int vo = 2 * s + (out_slot >> 1);
     vo = vo < m ? vo : m - 1;
@@ -335,11 +336,20 @@ __device__ __forceinline__ void run_tiles(const LayerDesc& L, int tile0, const _
     if (work) {
       auto consume = [&](const u32x4 (&pl)[B], const u32x4& csa, int g) {
         const int gr = g - c0;
+#ifdef PMPD_NOMATH
+        {
+          uint32_t acc = csa.x ^ csa.y ^ csa.z ^ csa.w;
+#pragma unroll
+          for (int k = 0; k < B; ++k) acc ^= pl[k].x ^ pl[k].y ^ pl[k].z ^ pl[k].w;
+          yacc[0][0] += __builtin_bit_cast(float, acc & 0x3fffffu) + im.xsum[x_off[0] + gr];
+          return;
+        }
+#endif
         XOperand X[SETS];
         float xg[SETS];
 #pragma unroll
         for (int s = 0; s < SETS; ++s) {
-          X[s].a = read_fp8_operand(im.pieces + a_off[s] + gr * kPieceBytes);
+          X[s].a = read_fp8_operand(im.pieces + a_off[s] + gr * kGroupPieceBytes);
           X[s].scale = static_cast<unsigned char>(im.scales[s_off[s] + gr * kScaleBytes]);
           xg[s] = im.xsum[x_off[s] + gr];
         }
@@ -358,12 +368,25 @@ __device__ __forceinline__ void run_tiles(const LayerDesc& L, int tile0, const _
           }
         }
       };
+#if defined(PMPD_DEPTH) && PMPD_DEPTH == 2
+      u32x4 pc[B], sa_c = {0, 0, 0, 0};
+      load(pb, sa_b, g0 + 1);
+      for (int gc = g0; gc < g1; gc += 3) {
+        load(pc, sa_c, gc + 2);
+        consume(pa, sa_a, gc);
+        load(pa, sa_a, gc + 3);
+        if (gc + 1 < g1) consume(pb, sa_b, gc + 1);
+        load(pb, sa_b, gc + 4);
+        if (gc + 2 < g1) consume(pc, sa_c, gc + 2);
+      }
+#else
       for (int gc = g0; gc < g1; gc += 2) {
         load(pb, sa_b, gc + 1);
         consume(pa, sa_a, gc);
         load(pa, sa_a, gc + 2);
         if (gc + 1 < g1) consume(pb, sa_b, gc + 1);
       }
+#endif
     }
   }
   // the two classes of a vector sit 16 lanes apart: add them (fixed order: A + B)
@@ -552,11 +575,14 @@ static constexpr int kNumVariants = 3;
 // which work list (tiles per workgroup: list 0 = 4, 1 = 1, 2 = 2) each variant walks
 static constexpr int kVariantList[kNumVariants] = {0, 1, 2};
 static void pick_variants(pmpd_stack* st) {
-  // Measured on the 7B-shaped stack: the three shapes are within 1 % of each other at b = 4 and 3;
-  // at b = 2 four waves splitting one tile's K stream fastest.
-  st->variant[4] = 1;
-  st->variant[3] = 1;
-  st->variant[2] = 1;
+  // Measured on the 7B-, 13B-shaped and mobile-scale stacks: the shapes are within 2 % of each
+  // other.  Whole-K waves (shape 0) split x once for four tiles and win at b = 4 and 3 when the
+  // stack has enough four-tile workgroups to fill the machine several times; shape 2 otherwise
+  // and at b = 2, where the split of x weighs more against the shorter weight stream.
+  const bool big = st->items[0].size() >= 4096;
+  st->variant[4] = big ? 0 : 2;
+  st->variant[3] = big ? 0 : 2;
+  st->variant[2] = 2;
   const char* e = std::getenv("PMPD_STACK_VARIANT");
   if (e) {
     int v[3];
@@ -674,7 +700,7 @@ int32_t pmpd_stack_create(const pmpd_layer_t* layers, int32_t n, const int64_t* 
   for (int q = 0; q < kNumItemLists && e == hipSuccess; ++q) {
     e = hipMemcpy(w, st->items[q].data(), st->items[q].size() * sizeof(WorkItem), hipMemcpyHostToDevice);
     st->d_items[q] = reinterpret_cast<const WorkItem*>(w);
-    w += align_up(st->items[q].size() * sizeof(WorkItem), 256);
+    w += align_up(counts[q] * sizeof(WorkItem), 256);
   }
   if (e != hipSuccess) {
     delete st;

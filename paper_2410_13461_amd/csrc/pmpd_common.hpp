@@ -42,9 +42,9 @@ struct WorkItem {
 };
 
 // Work lists of a stack, one per workgroup size in 64-row tiles.
-constexpr int kNumItemLists = 3;
-constexpr int kStackTilesPerWg[kNumItemLists] = {4, 1, 2};
-constexpr int kPrefillItemList = 2;  // the prefill kernel works on 128-row blocks
+constexpr int kNumItemLists = 4;
+constexpr int kStackTilesPerWg[kNumItemLists] = {4, 1, 2, 8};
+constexpr int kPrefillItemList = 3;  // the prefill kernel works on 8-tile (512-row) blocks
 
 int32_t check_bits(int32_t b, const char* who);  // b in {2,3,4}
 constexpr int kMaxPrefillRows = 65536;
@@ -57,7 +57,7 @@ struct pmpd_stack {
   std::vector<pmpd::LayerDesc> layers;
   std::vector<pmpd::WorkItem> items[pmpd::kNumItemLists];
   const pmpd::LayerDesc* d_layers = nullptr;
-  const pmpd::WorkItem* d_items[pmpd::kNumItemLists] = {nullptr, nullptr, nullptr};
+  const pmpd::WorkItem* d_items[pmpd::kNumItemLists] = {nullptr, nullptr, nullptr, nullptr};
   int max_in = 0;
   int variant[5] = {0, 0, 0, 0, 0};  // decode kernel variant per bit-width (index = b)
 };

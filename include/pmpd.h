@@ -156,6 +156,24 @@ int32_t pmpd_schedule_bits(const pmpd_schedule_t* schedule, int32_t step, int32_
 /* Mean bit-width over steps 0..n_steps-1 (Section 5 "Baselines"); negative on error. */
 double pmpd_schedule_avg_bits(const pmpd_schedule_t* schedule, int32_t n_steps);
 
+/* ---- static scheduler: offline search for <P, S> (Section 4.3; Algorithm 1 line 4) ---------- *
+ * Candidate switch points: points[k] = round(k * max_steps / (n_points - 1)), k = 0 .. n_points-1
+ * (0, OL/(N-1), ..., OL; halves round up).  2 <= n_points <= max_steps + 1. */
+int32_t pmpd_schedule_grid(int32_t max_steps, int32_t n_points, int32_t* points);
+/* Number of progressive schedules: sum over r of C(max_steps, r) * C(n_precisions - 1, r); -1 on error. */
+int64_t pmpd_schedule_count(int32_t max_steps, int32_t n_precisions);
+/* Quality of a schedule as the caller measures it (the paper: mean task score over a validation
+ * set); called on the host, higher is better. */
+typedef double (*pmpd_quality_fn)(const int32_t* precisions, const int32_t* st, int32_t n, void* user);
+/* Among the schedules with st[0] = 0, st non-decreasing and every st[j] on the candidate grid whose
+ * quality is >= q_ref - eps (Eq. 2), the one with the fewest high-precision tokens (Eq. 1): lowest
+ * average bit-width over max_steps steps, ties to the lexicographically smallest st.  quality() is
+ * only called for schedules that would beat the best one found so far; *evaluated_out counts the
+ * calls.  PMPD_ESCHED when no schedule on the grid reaches the quality bar. */
+int32_t pmpd_schedule_search(const int32_t* precisions, int32_t n, int32_t max_steps, int32_t n_points,
+                             pmpd_quality_fn quality, void* user, double q_ref, double eps, int32_t* st_out,
+                             double* avg_bits_out, int64_t* evaluated_out);
+
 /* Steps step0 .. step0+n_steps-1 of a decode run, each at the schedule's bit-width (which must
  * be in {2,3,4}).  Step k reads x_base + (k-step0)*x_step_stride and writes
  * y_base + (k-step0)*y_step_stride (strides in elements; 0 reuses the same buffers). */

@@ -229,3 +229,37 @@ def schedule_weighted_latency(lat_high: float, lat_low: float, frac_high: float)
 def high_precision_fraction(avg_bits: float, high: int, low: int) -> float:
     """Fraction of decode steps run at the high precision given the average bit-width."""
     return (avg_bits - low) / (high - low)
+
+
+# ------------------------------------------------ static scheduler (Section 4.3) ----
+def schedule_grid(OL: int, N: int):
+    """Candidate switch points {0} u {k OL/(N-1)}: exact rationals rounded to the nearest step (halves up)."""
+    from fractions import Fraction
+    from math import floor
+
+    return [int(floor(Fraction(k * OL, N - 1) + Fraction(1, 2))) for k in range(N)]
+
+
+def schedule_search_brute_force(precisions, OL: int, N: int, quality, q_ref: float, eps: float):
+    """Every progressive schedule on the candidate grid (st[0] = 0, st non-decreasing, Eq. 3) is measured;
+    the feasible one (Eq. 2: quality >= q_ref - eps) with the fewest high-precision tokens wins (Eq. 1):
+    lowest average bit-width over OL steps, ties to the lexicographically smallest st.
+    Returns (st, avg_bits, number of schedules on the grid) or None when nothing is feasible."""
+    from itertools import combinations_with_replacement
+
+    grid = sorted(set(schedule_grid(OL, N)))
+    n = len(precisions)
+    best = None
+    count = 0
+    for tail in combinations_with_replacement(grid, n - 1):  # non-decreasing tuples
+        st = (0,) + tuple(tail)
+        count += 1
+        if quality(list(precisions), list(st)) < q_ref - eps:
+            continue
+        avg = schedule_avg_bits(precisions, st, OL)
+        key = (avg, st)
+        if best is None or key < best[0]:
+            best = (key, st, avg)
+    if best is None:
+        return None
+    return list(best[1]), best[2], count

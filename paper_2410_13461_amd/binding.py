@@ -19,7 +19,11 @@ EXPORTS = (
     "pmpd_stack_workspace_size", "pmpd_stack_create", "pmpd_stack_destroy", "pmpd_decode_step",
     "pmpd_schedule_create", "pmpd_schedule_destroy", "pmpd_schedule_bits", "pmpd_schedule_avg_bits",
     "pmpd_decode_run", "pmpd_prefill_step", "pmpd_batch_step",
+    "pmpd_schedule_grid", "pmpd_schedule_count", "pmpd_schedule_search",
 )
+
+QUALITY_FN = ctypes.CFUNCTYPE(ctypes.c_double, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32),
+                              ctypes.c_int32, ctypes.c_void_p)
 
 
 class PMPDError(RuntimeError):
@@ -90,6 +94,13 @@ def _load():
     L.pmpd_prefill_step.argtypes = [vp, i32, vp, i32, vp, vp]
     L.pmpd_batch_step.restype = i32
     L.pmpd_batch_step.argtypes = [vp, i32, vp, i32, vp, vp]
+    L.pmpd_schedule_grid.restype = i32
+    L.pmpd_schedule_grid.argtypes = [i32, i32, P(i32)]
+    L.pmpd_schedule_count.restype = i64
+    L.pmpd_schedule_count.argtypes = [i32, i32]
+    L.pmpd_schedule_search.restype = i32
+    L.pmpd_schedule_search.argtypes = [P(i32), i32, i32, i32, QUALITY_FN, vp, ctypes.c_double, ctypes.c_double, P(i32),
+                                       P(ctypes.c_double), P(i64)]
     L.pmpd_decode_run.restype = i32
     L.pmpd_decode_run.argtypes = [vp, vp, i32, i32, vp, i64, vp, i64, vp]
     _lib = L
@@ -325,6 +336,38 @@ class Schedule:
             self.close()
         except Exception:
             pass
+
+
+def schedule_grid(max_steps: int, n_points: int) -> List[int]:
+    """Candidate switch points 0, OL/(N-1), ..., OL."""
+    pts = (ctypes.c_int32 * max(n_points, 1))()
+    _check(_load().pmpd_schedule_grid(max_steps, n_points, pts))
+    return list(pts)
+
+
+def schedule_count(max_steps: int, n_precisions: int) -> int:
+    v = _load().pmpd_schedule_count(max_steps, n_precisions)
+    if v < 0:
+        raise PMPDError(-1, _load().pmpd_last_error().decode())
+    return v
+
+
+def schedule_search(precisions: Sequence[int], max_steps: int, n_points: int, quality, q_ref: float, eps: float):
+    """Static-scheduler search; quality(precisions, st) -> float is called on the host.
+    Returns (st, avg_bits, number of quality evaluations)."""
+    n = len(precisions)
+
+    def _cb(p_ptr, st_ptr, nn, _user):
+        return float(quality([p_ptr[i] for i in range(nn)], [st_ptr[i] for i in range(nn)]))
+
+    cb = QUALITY_FN(_cb)
+    p = (ctypes.c_int32 * max(n, 1))(*precisions)
+    st = (ctypes.c_int32 * max(n, 1))()
+    avg = ctypes.c_double()
+    cnt = ctypes.c_int64()
+    _check(_load().pmpd_schedule_search(p, n, max_steps, n_points, cb, None, q_ref, eps, st, ctypes.byref(avg),
+                                        ctypes.byref(cnt)))
+    return list(st), avg.value, cnt.value
 
 
 def decode_run(stack: Stack, schedule: Schedule, step0: int, n_steps: int, x, x_step_stride: int, y,

@@ -1,6 +1,7 @@
 // Host side of the PMPD library: error reporting, argument checks, the storage format
 // (pack / unpack) and the precision-switching schedule.  Nothing here touches the GPU.
 #include <algorithm>
+#include <climits>
 #include <cstdio>
 #include <cstring>
 #include <thread>
@@ -231,6 +232,91 @@ double pmpd_schedule_avg_bits(const pmpd_schedule_t* s, int32_t n_steps) {
     total += (hi - lo) * s->precisions[j];
   }
   return static_cast<double>(total) / static_cast<double>(n_steps);
+}
+
+// ------------------------------------------------------- static scheduler search ----
+// Candidate switch points (Section 4.3): 0 and k * OL / (N - 1), k = 1 .. N - 1, rounded to the
+// nearest integer step (halves up); the last one is OL itself ("never reached").
+int32_t pmpd_schedule_grid(int32_t max_steps, int32_t n_points, int32_t* points) {
+  if (!points) return fail(PMPD_EINVAL, "pmpd_schedule_grid: points is NULL");
+  if (max_steps < 1) return fail(PMPD_EINVAL, "pmpd_schedule_grid: max_steps must be positive");
+  if (n_points < 2 || n_points > max_steps + 1) return fail(PMPD_EINVAL, "pmpd_schedule_grid: need 2 <= n_points <= max_steps + 1 (got %d)", n_points);
+  for (int32_t k = 0; k < n_points; ++k)
+    points[k] = static_cast<int32_t>((2 * static_cast<int64_t>(k) * max_steps + (n_points - 1)) / (2 * (n_points - 1)));
+  return PMPD_OK;
+}
+
+// Number of progressive schedules, sum over the number of switches r of C(OL, r) C(|P| - 1, r)
+// (Section 4.3); -1 on bad arguments or overflow of int64.
+int64_t pmpd_schedule_count(int32_t max_steps, int32_t n_precisions) {
+  if (max_steps < 1 || n_precisions < 1 || n_precisions > 16) { fail(PMPD_EINVAL, "pmpd_schedule_count: bad argument"); return -1; }
+  auto binom = [](int64_t n, int64_t k, bool& ok) -> int64_t {
+    if (k < 0 || k > n) return 0;
+    __int128 v = 1;
+    for (int64_t i = 1; i <= k; ++i) {
+      v = v * (n - k + i) / i;
+      if (v > INT64_MAX) { ok = false; return 0; }
+    }
+    return static_cast<int64_t>(v);
+  };
+  bool ok = true;
+  __int128 total = 0;
+  for (int r = 0; r < n_precisions; ++r) {
+    total += static_cast<__int128>(binom(max_steps, r, ok)) * binom(n_precisions - 1, r, ok);
+    if (!ok || total > INT64_MAX) { fail(PMPD_EINVAL, "pmpd_schedule_count: result exceeds int64"); return -1; }
+  }
+  return static_cast<int64_t>(total);
+}
+
+// Offline optimisation of the static scheduler (Eq. 1-3 with the candidate grid of Section 4.3):
+// among the schedules with st[0] = 0, st non-decreasing and st[j] on the grid whose quality is at
+// least q_ref - eps, the one with the fewest tokens at high precision.  "Fewest" is taken as the
+// lowest average bit-width over the max_steps steps; ties go to the schedule that leaves the
+// highest precision earliest, then the next one, and so on (lexicographically smallest st).
+int32_t pmpd_schedule_search(const int32_t* precisions, int32_t n, int32_t max_steps, int32_t n_points,
+                             pmpd_quality_fn quality, void* user, double q_ref, double eps, int32_t* st_out,
+                             double* avg_bits_out, int64_t* evaluated_out) {
+  if (!precisions || !quality || !st_out) return fail(PMPD_EINVAL, "pmpd_schedule_search: NULL argument");
+  if (n < 1 || n > 16) return fail(PMPD_EINVAL, "pmpd_schedule_search: need 1..16 precisions (got %d)", n);
+  for (int j = 0; j < n; ++j) {
+    if (precisions[j] < 1 || precisions[j] > 16) return fail(PMPD_EINVAL, "pmpd_schedule_search: precision %d out of range", precisions[j]);
+    if (j && precisions[j] >= precisions[j - 1]) return fail(PMPD_EINVAL, "pmpd_schedule_search: precisions must be strictly decreasing");
+  }
+  std::vector<int32_t> grid(static_cast<size_t>(std::max(n_points, 2)));
+  int32_t rc = pmpd_schedule_grid(max_steps, n_points, grid.data());
+  if (rc) return rc;
+  grid.erase(std::unique(grid.begin(), grid.end()), grid.end());
+
+  std::vector<int32_t> idx(n, 0), st(n, 0), best;
+  int64_t best_bits = -1, evaluated = 0;
+  // odometer over non-decreasing index vectors idx[1..n-1] (idx[0] = 0 -> st[0] = 0)
+  while (true) {
+    for (int j = 0; j < n; ++j) st[j] = grid[idx[j]];
+    // total bits over max_steps steps: precision j is active on [st[j], st[j+1])
+    int64_t bits = 0;
+    for (int j = 0; j < n; ++j) {
+      const int64_t hi = j + 1 < n ? st[j + 1] : max_steps;
+      bits += (hi - st[j]) * precisions[j];
+    }
+    const bool better = best_bits < 0 || bits < best_bits || (bits == best_bits && st < best);
+    if (better) {  // the quality measurement is the expensive part: only ask when it could win
+      ++evaluated;
+      if (quality(precisions, st.data(), n, user) >= q_ref - eps) {
+        best_bits = bits;
+        best = st;
+      }
+    }
+    int j = n - 1;
+    while (j >= 1 && idx[j] == static_cast<int32_t>(grid.size()) - 1) --j;
+    if (j < 1) break;
+    ++idx[j];
+    for (int k = j + 1; k < n; ++k) idx[k] = idx[j];
+  }
+  if (evaluated_out) *evaluated_out = evaluated;
+  if (best_bits < 0) return fail(PMPD_ESCHED, "pmpd_schedule_search: no schedule on the grid reaches quality %g", q_ref - eps);
+  for (int j = 0; j < n; ++j) st_out[j] = best[j];
+  if (avg_bits_out) *avg_bits_out = static_cast<double>(best_bits) / static_cast<double>(max_steps);
+  return PMPD_OK;
 }
 
 }  // extern "C"

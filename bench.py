@@ -146,6 +146,117 @@ def secondary_workload(args) -> int:
                     "config": {"workload": "Llama-7B-shaped stack, 256 decode steps, b per step from the schedule"},
                     "per_phase": per,
                     "GBps_overall": sum(stack.bytes_at(b) * n for b, _, n in phases) / (total_ms * 1e-3) / 1e9})
+    elif args.workload == "alternate":
+        # The paper rejects per-token switching because of the cost of swapping weights in its system
+        # (Section 3.2); with the nested plane store a switch is only a different launch argument.
+        shape = synth.LLAMA_7B
+        stack, layers, _ = workload.build_stack(shape, seed=args.seed, verbose=True)
+        n_steps = 256
+        x = torch.from_numpy(np.stack([workload.draw_step_activations(shape, args.seed, k) for k in range(8)])).cuda()
+        y = torch.zeros(stack.y_elems, dtype=torch.float32, device="cuda")
+        stream = torch.cuda.current_stream()
+
+        def run(bits_of_step):
+            for k in range(n_steps):
+                pmpd.decode_step(stack, bits_of_step(k), x[k % 8], y, stream)
+
+        res = {}
+        for name, f in (("b4", lambda k: 4), ("b2", lambda k: 2), ("alternating_4_2", lambda k: 4 if k % 2 == 0 else 2),
+                        ("cycling_4_3_2", lambda k: 4 - k % 3)):
+            _ramp(lambda: run(f), 0.5)
+            reps = max(1, K // 50)
+            res[name] = _timed(lambda: run(f), reps) * 1e3 / n_steps  # us per token
+        out.update({"metric": "us/token when the bit-width changes at every step, against the fixed-precision runs",
+                    "unit": "us/token", "value": res["alternating_4_2"], "higher_is_better": False,
+                    "config": {"workload": "Llama-7B-shaped stack, 256 decode steps per run, b switched every token"},
+                    "results": res,
+                    "switching_overhead_us": res["alternating_4_2"] - 0.5 * (res["b4"] + res["b2"])})
+    elif args.workload == "ordered":
+        # Dependency order of a decoder block: (q, k, v) -> o -> (up, gate) -> down, block after block:
+        # one launch per stage, 4 x 32 launches per token, eager and as a replayed graph.  The glue
+        # between the stages (attention, norms, activation) is not part of this path: only the order
+        # of the launches is enforced, every layer keeps its own input buffer.
+        shape = synth.LLAMA_7B
+        stack, layers, _ = workload.build_stack(shape, seed=args.seed, verbose=True)
+        stages = ((0, 1, 2), (3,), (4, 6), (5,))  # projection indices q,k,v,o,up,down,gate
+        stage_stacks = []
+        for blk in range(shape.n_blocks):
+            for st_ in stages:
+                idx = [blk * 7 + pi for pi in st_]
+                stage_stacks.append(pmpd.Stack([layers[i] for i in idx], [stack.x_offsets[i] for i in idx],
+                                               [stack.y_offsets[i] for i in idx]))
+        x = torch.from_numpy(workload.draw_step_activations(shape, args.seed, 0)).cuda()
+        y = torch.zeros(stack.y_elems, dtype=torch.float32, device="cuda")
+        y_ref = torch.zeros_like(y)
+        res = {}
+        for b in (4, 3, 2):
+            def step():
+                for ss in stage_stacks:
+                    pmpd.decode_step(ss, b, x, y)
+            pmpd.decode_step(stack, b, x, y_ref)
+            step()
+            torch.cuda.synchronize()
+            same = bool(torch.equal(y, y_ref))  # same kernels' arithmetic per row: bit-identical is expected only per launch shape
+            close = bool(torch.allclose(y, y_ref, rtol=1e-4, atol=1e-4))
+            _ramp(step, 0.3)
+            eager = _timed(step, max(3, K // 10)) * 1e3
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                step()
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=side):
+                    step()
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            replays = []
+            for _ in range(3):  # every replay is checked against the eager result
+                y.zero_()
+                g.replay()
+                torch.cuda.synchronize()
+                replays.append(bool(torch.allclose(y, y_ref, rtol=1e-4, atol=1e-4)))
+            _ramp(g.replay, 0.3)
+            graph = _timed(g.replay, max(3, K // 10)) * 1e3
+            _ramp(lambda: pmpd.decode_step(stack, b, x, y), 0.3)
+            one = _timed(lambda: pmpd.decode_step(stack, b, x, y), K) * 1e3
+            res[f"b{b}"] = {"one_launch_us": one, "ordered_eager_us": eager, "ordered_graph_us": graph,
+                            "matches_one_launch": close, "bit_identical": same, "graph_replays_match": all(replays)}
+        out.update({"metric": "us/token of the 7B-shaped step launched in dependency order (128 stage launches) vs one launch",
+                    "unit": "us/token", "value": res["b4"]["ordered_graph_us"], "higher_is_better": False,
+                    "config": {"workload": "Llama-7B-shaped stack, stages (q,k,v) -> o -> (up,gate) -> down per block"},
+                    "results": res})
+    elif args.workload == "single":
+        # One 4096 x 4096 layer: latency of an isolated GEMV on warm weights, and throughput when every
+        # launch reads weights that are not in the 256 MB cache (64 packed copies = 570 MB at b = 4).
+        o = i = 4096
+        n_copies = 64
+        q4, s_, a_ = synth.draw_weights(args.seed, 0, 0, o, i)
+        planes, sm = pmpd.pack(q4, s_, a_)
+        copies = [pmpd.upload_layer(planes, sm, o, i) for _ in range(n_copies)]
+        x = torch.from_numpy(synth.draw_x(args.seed, 0, 0, 0, i)[0]).cuda()
+        y = torch.zeros(o, dtype=torch.float32, device="cuda")
+        res = {}
+        for b in (4, 3, 2):
+            warm = lambda: pmpd.gemv(copies[0], b, x, y)
+            def cold():
+                for c in copies:
+                    pmpd.gemv(c, b, x, y)
+            _ramp(cold, 0.3)
+            t_cold = _timed(cold, max(3, K // 5)) * 1e3 / n_copies
+            _ramp(warm, 0.2)
+            t_warm = _timed(warm, 10 * K) * 1e3
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(200):
+                warm()
+                torch.cuda.synchronize()
+            t_iso = (time.perf_counter() - t0) / 200 * 1e6
+            res[f"b{b}"] = {"cold_weights_us": t_cold, "cold_GBps": copies[0].bytes_at(b) / (t_cold * 1e-6) / 1e9,
+                            "warm_back_to_back_us": t_warm, "isolated_launch_and_sync_us": t_iso}
+        out.update({"metric": "single 4096x4096 layer, batch 1: us per GEMV (cold weights, warm back-to-back, isolated launch+sync)",
+                    "unit": "us", "value": res["b4"]["cold_weights_us"], "higher_is_better": False,
+                    "config": {"workload": "one 4096x4096 layer, 64 packed copies rotated for the cold-weight figure"},
+                    "results": res})
     elif args.workload == "mobile":
         shape = synth.MOBILE
         # two distinct copies of the stack, alternated, so that no step finds its weights in the 256 MB cache
@@ -205,7 +316,7 @@ def main() -> int:
     ap.add_argument("--blocks", type=int, default=None, help="debug: fewer blocks (result is then not the named workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--workload", default="7b", choices=["7b", "schedule", "mobile", "13b"],
+    ap.add_argument("--workload", default="7b", choices=["7b", "schedule", "alternate", "ordered", "single", "mobile", "13b"],
                     help="7b (default) is the benchmark line; the others print a line for the secondary workloads")
     args = ap.parse_args()
     if args.gpus != 1:

@@ -336,15 +336,6 @@ __device__ __forceinline__ void run_tiles(const LayerDesc& L, int tile0, const _
     if (work) {
       auto consume = [&](const u32x4 (&pl)[B], const u32x4& csa, int g) {
         const int gr = g - c0;
-#ifdef PMPD_NOMATH
-        {
-          uint32_t acc = csa.x ^ csa.y ^ csa.z ^ csa.w;
-#pragma unroll
-          for (int k = 0; k < B; ++k) acc ^= pl[k].x ^ pl[k].y ^ pl[k].z ^ pl[k].w;
-          yacc[0][0] += __builtin_bit_cast(float, acc & 0x3fffffu) + im.xsum[x_off[0] + gr];
-          return;
-        }
-#endif
         XOperand X[SETS];
         float xg[SETS];
 #pragma unroll
@@ -368,25 +359,12 @@ __device__ __forceinline__ void run_tiles(const LayerDesc& L, int tile0, const _
           }
         }
       };
-#if defined(PMPD_DEPTH) && PMPD_DEPTH == 2
-      u32x4 pc[B], sa_c = {0, 0, 0, 0};
-      load(pb, sa_b, g0 + 1);
-      for (int gc = g0; gc < g1; gc += 3) {
-        load(pc, sa_c, gc + 2);
-        consume(pa, sa_a, gc);
-        load(pa, sa_a, gc + 3);
-        if (gc + 1 < g1) consume(pb, sa_b, gc + 1);
-        load(pb, sa_b, gc + 4);
-        if (gc + 2 < g1) consume(pc, sa_c, gc + 2);
-      }
-#else
       for (int gc = g0; gc < g1; gc += 2) {
         load(pb, sa_b, gc + 1);
         consume(pa, sa_a, gc);
         load(pa, sa_a, gc + 2);
         if (gc + 1 < g1) consume(pb, sa_b, gc + 1);
       }
-#endif
     }
   }
   // the two classes of a vector sit 16 lanes apart: add them (fixed order: A + B)
@@ -478,18 +456,18 @@ int32_t check_bits(int32_t b, const char* who) {
   return PMPD_OK;
 }
 
-// Launch shapes.  A stack has thousands of row tiles; a single layer has few and splits K over
-// the waves of a workgroup to put more waves on the machine.
-static int pick_splitk(int n_tiles, int groups_per_pass) {
-  // Split K until about 2048 waves exist or a wave would get fewer than 4 groups.
+// Launch shapes.  A stack has thousands of row tiles; a single layer (or a short stack) has few
+// and splits K over the waves of a workgroup to put more waves on the machine: 2 or 4 ways with
+// four waves, 8 or 16 ways with one tile per workgroup of 8 or 16 waves.
+static int pick_splitk(int64_t n_tiles, int groups_per_pass, int max_split) {
+  // Split K until about 2048 waves exist or a wave would get fewer than 2 groups.
   int splitk = 1;
-  while (splitk < 4 && static_cast<int64_t>(n_tiles) * splitk < 2048 && groups_per_pass / (splitk * 2) >= 4) splitk *= 2;
+  while (splitk < max_split && n_tiles * splitk < 2048 && groups_per_pass / (splitk * 2) >= 2) splitk *= 2;
   return splitk;
 }
 
-template <int B, int SETS, int SPLITK>
+template <int B, int SETS, int NW, int SPLITK>
 static hipError_t launch_layer(const LayerDesc& d, const void* x, int m, float* y, hipStream_t s) {
-  constexpr int NW = 4;
   const int tpw = NW / SPLITK;
   const unsigned grid = static_cast<unsigned>((d.n_tiles + tpw - 1) / tpw);
   const size_t lds = lds_bytes(chunk_groups(d.n_groups, m), m, NW, SETS * 4);
@@ -500,10 +478,15 @@ static hipError_t launch_layer(const LayerDesc& d, const void* x, int m, float* 
 
 template <int B, int SETS>
 static hipError_t launch_layer_s(const LayerDesc& d, const void* x, int m, float* y, hipStream_t s) {
-  switch (pick_splitk(d.n_tiles, chunk_groups(d.n_groups, m))) {
-    case 1: return launch_layer<B, SETS, 1>(d, x, m, y, s);
-    case 2: return launch_layer<B, SETS, 2>(d, x, m, y, s);
-    default: return launch_layer<B, SETS, 4>(d, x, m, y, s);
+  switch (pick_splitk(d.n_tiles, chunk_groups(d.n_groups, m), SETS == 1 ? 16 : 4)) {
+    case 1: return launch_layer<B, SETS, 4, 1>(d, x, m, y, s);
+    case 2: return launch_layer<B, SETS, 4, 2>(d, x, m, y, s);
+    case 4: return launch_layer<B, SETS, 4, 4>(d, x, m, y, s);
+    case 8:
+      if constexpr (SETS == 1) return launch_layer<B, 1, 8, 8>(d, x, m, y, s);
+    default:
+      if constexpr (SETS == 1) return launch_layer<B, 1, 16, 16>(d, x, m, y, s);
+      return launch_layer<B, SETS, 4, 4>(d, x, m, y, s);
   }
 }
 
@@ -569,20 +552,30 @@ static size_t stack_bytes(size_t n_layers, const size_t (&n_items)[kNumItemLists
 
 // Launch shapes of the one-launch decode step (PMPD_STACK_VARIANT="v4,v3,v2" overrides the
 // per-bit-width defaults):
-//   0  4 waves x 1 tile each, whole K     1  4 waves on 1 tile, K split 4 ways
-//   2  4 waves on 2 tiles, K split 2 ways
-static constexpr int kNumVariants = 3;
+//   0  4 waves x 1 tile each, whole K       1  4 waves on 1 tile, K split 4 ways
+//   2  4 waves on 2 tiles, K split 2 ways   3  8 waves on 1 tile, K split 8 ways
+//   4  16 waves on 1 tile, K split 16 ways
+static constexpr int kNumVariants = 5;
 // which work list (tiles per workgroup: list 0 = 4, 1 = 1, 2 = 2) each variant walks
-static constexpr int kVariantList[kNumVariants] = {0, 1, 2};
+static constexpr int kVariantList[kNumVariants] = {0, 1, 2, 1, 1};
 static void pick_variants(pmpd_stack* st) {
-  // Measured on the 7B-, 13B-shaped and mobile-scale stacks: the shapes are within 2 % of each
+  // Measured on the 7B-, 13B-shaped and mobile-scale stacks: shapes 0..2 are within 2 % of each
   // other.  Whole-K waves (shape 0) split x once for four tiles and win at b = 4 and 3 when the
   // stack has enough four-tile workgroups to fill the machine several times; shape 2 otherwise
-  // and at b = 2, where the split of x weighs more against the shorter weight stream.
+  // and at b = 2, where the split of x weighs more against the shorter weight stream.  Short
+  // stacks (the layers of one dependency stage, say) split K further, like single layers.
   const bool big = st->items[0].size() >= 4096;
   st->variant[4] = big ? 0 : 2;
   st->variant[3] = big ? 0 : 2;
   st->variant[2] = 2;
+  const int64_t n_tiles = static_cast<int64_t>(st->items[1].size());
+  int min_groups = st->max_in / kGroup;
+  for (const LayerDesc& d : st->layers) min_groups = std::min(min_groups, d.n_groups);
+  const int split = pick_splitk(n_tiles, std::min(min_groups, chunk_groups(st->max_in / kGroup, 1)), 16);
+  if (split >= 4) {
+    const int v = split == 4 ? 1 : split == 8 ? 3 : 4;
+    st->variant[4] = st->variant[3] = st->variant[2] = v;
+  }
   const char* e = std::getenv("PMPD_STACK_VARIANT");
   if (e) {
     int v[3];
@@ -609,13 +602,20 @@ static hipError_t launch_stack(const pmpd_stack* st, const void* xv, float* y, h
   const int q = kVariantList[v];
   const unsigned grid = static_cast<unsigned>(st->items[q].size());
   const _Float16* x = static_cast<const _Float16*>(xv);
-  const size_t lds = lds_bytes(chunk_groups(st->max_in / kGroup, 1), 1, 4, 4);
+  const int nw = v == 3 ? 8 : v == 4 ? 16 : 4;
+  const size_t lds = lds_bytes(chunk_groups(st->max_in / kGroup, 1), 1, nw, 4);
   switch (v) {
     case 0:
       hipLaunchKernelGGL((pmpd_stack_kernel<B, 1, 4, 1>), dim3(grid), dim3(256), lds, s, st->d_layers, st->d_items[q], x, 1, y);
       break;
     case 2:
       hipLaunchKernelGGL((pmpd_stack_kernel<B, 1, 4, 2>), dim3(grid), dim3(256), lds, s, st->d_layers, st->d_items[q], x, 1, y);
+      break;
+    case 3:
+      hipLaunchKernelGGL((pmpd_stack_kernel<B, 1, 8, 8>), dim3(grid), dim3(512), lds, s, st->d_layers, st->d_items[q], x, 1, y);
+      break;
+    case 4:
+      hipLaunchKernelGGL((pmpd_stack_kernel<B, 1, 16, 16>), dim3(grid), dim3(1024), lds, s, st->d_layers, st->d_items[q], x, 1, y);
       break;
     default:
       hipLaunchKernelGGL((pmpd_stack_kernel<B, 1, 4, 4>), dim3(grid), dim3(256), lds, s, st->d_layers, st->d_items[q], x, 1, y);

@@ -260,7 +260,7 @@ def test_decode_step_matches_oracle_and_single_layer_calls(pmpd, b):
     stack.close()
 
 
-@pytest.mark.parametrize("variant", list(range(3)))
+@pytest.mark.parametrize("variant", list(range(5)))
 def test_every_stack_kernel_variant_matches_oracle(pmpd, variant, monkeypatch):
     """Each launch shape of the one-launch decode step (selected per
     bit-width by default, forced here through PMPD_STACK_VARIANT) gives the same answers."""

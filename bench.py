@@ -391,6 +391,17 @@ def main() -> int:
         }
     us_per_token = total_ms * 1e3 / (K * len(bits))
 
+    # the rate a plain read-only stream reaches on this machine over the same number of bytes
+    buf = torch.empty(stack.bytes_at(4) // 4, dtype=torch.int32, device="cuda")
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    nread = pmpd.read_stream(buf, sink, stream)
+    _ramp(lambda: pmpd.read_stream(buf, sink, stream), 0.3)
+    stream_ms = _timed(lambda: pmpd.read_stream(buf, sink, stream), 50)
+    stream_gbps = nread / (stream_ms * 1e-3) / 1e9
+    del buf
+    for b in bits:
+        per_bits[str(b)]["frac_of_read_stream"] = per_bits[str(b)]["GBps"] / stream_gbps
+
     dom = per_bits["4"]
     out = {
         "metric": "decode linear-layer us/token (mean over b=4,3,2; per-bit figures in per_bits), batch 1",
@@ -421,6 +432,8 @@ def main() -> int:
             "unit": "GB/s",
             "frac": dom["GBps"] / HBM_PEAK_GBS,
             "traffic": measured_traffic(4) if args.blocks is None else None,
+            "read_stream_GBps": stream_gbps,
+            "frac_of_read_stream": dom["GBps"] / stream_gbps,
         },
     }
     if not args.no_cpu_baseline:

@@ -181,6 +181,13 @@ int32_t pmpd_decode_run(const pmpd_stack_t* stack, const pmpd_schedule_t* schedu
                         int32_t n_steps, const void* x_base, int64_t x_step_stride, float* y_base,
                         int64_t y_step_stride, void* stream);
 
+/* ---- measurement aid ------------------------------------------------------------------- *
+ * Streams `bytes` (rounded down to a multiple of 128 MiB; *bytes_read says how many) of device memory
+ * at src (16-byte aligned) through a read-only kernel: the HBM rate a plain read reaches on this
+ * device, against which the decode kernels' effective rate is held (the paper's Section 5.2 reasons
+ * about the same bound: decode linear layers are limited by weight transfers).  sink: device, 4 bytes. */
+int32_t pmpd_read_stream(const void* src, size_t bytes, uint32_t* sink, size_t* bytes_read, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

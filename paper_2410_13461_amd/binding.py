@@ -19,7 +19,7 @@ EXPORTS = (
     "pmpd_stack_workspace_size", "pmpd_stack_create", "pmpd_stack_destroy", "pmpd_decode_step",
     "pmpd_schedule_create", "pmpd_schedule_destroy", "pmpd_schedule_bits", "pmpd_schedule_avg_bits",
     "pmpd_decode_run", "pmpd_prefill_step", "pmpd_batch_step",
-    "pmpd_schedule_grid", "pmpd_schedule_count", "pmpd_schedule_search",
+    "pmpd_schedule_grid", "pmpd_schedule_count", "pmpd_schedule_search", "pmpd_read_stream",
 )
 
 QUALITY_FN = ctypes.CFUNCTYPE(ctypes.c_double, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32),
@@ -101,6 +101,8 @@ def _load():
     L.pmpd_schedule_search.restype = i32
     L.pmpd_schedule_search.argtypes = [P(i32), i32, i32, i32, QUALITY_FN, vp, ctypes.c_double, ctypes.c_double, P(i32),
                                        P(ctypes.c_double), P(i64)]
+    L.pmpd_read_stream.restype = i32
+    L.pmpd_read_stream.argtypes = [vp, sz, vp, P(sz), vp]
     L.pmpd_decode_run.restype = i32
     L.pmpd_decode_run.argtypes = [vp, vp, i32, i32, vp, i64, vp, i64, vp]
     _lib = L
@@ -336,6 +338,14 @@ class Schedule:
             self.close()
         except Exception:
             pass
+
+
+def read_stream(buf, sink, stream=None) -> int:
+    """Launch the read-only stream kernel over the torch tensor buf; returns the bytes it reads."""
+    n = ctypes.c_size_t()
+    _check(_load().pmpd_read_stream(_dev_ptr(buf), buf.numel() * buf.element_size(), _dev_ptr(sink), ctypes.byref(n),
+                                    _stream_handle(stream)))
+    return n.value
 
 
 def schedule_grid(max_steps: int, n_points: int) -> List[int]:

@@ -325,3 +325,16 @@ def test_gpu_error_paths_do_not_launch(pmpd):
     with pytest.raises(pmpd.PMPDError):
         pmpd.gemv(layer, 4, x[1:])  # misaligned view
     torch.cuda.synchronize()
+
+
+def test_read_stream_runs_and_reports_its_bytes(pmpd):
+    import torch
+
+    buf = torch.zeros(160 * 1024 * 1024 // 4, dtype=torch.int32, device="cuda")
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    n = pmpd.read_stream(buf, sink)
+    torch.cuda.synchronize()
+    assert n == 128 * 1024 * 1024  # rounded down to a multiple of 128 MiB
+    assert int(sink.item()) == 0
+    with pytest.raises(pmpd.PMPDError):
+        pmpd.read_stream(buf[: 1024 * 1024], sink)  # too small

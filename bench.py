@@ -185,6 +185,20 @@ def secondary_workload(args) -> int:
                 idx = [blk * 7 + pi for pi in st_]
                 stage_stacks.append(pmpd.Stack([layers[i] for i in idx], [stack.x_offsets[i] for i in idx],
                                                [stack.y_offsets[i] for i in idx]))
+        # the same order inside one cooperative launch, first with every layer on its own input (the
+        # same arithmetic as the launches above), then with the data really flowing from layer to
+        # layer: o <- q, (up, gate) <- o, down <- up, next block <- down, x = fp16(gain * y)
+        n_layers = len(layers)
+        stage_of = [4 * (li // 7) + {0: 0, 1: 0, 2: 0, 3: 1, 4: 2, 6: 2, 5: 3}[li % 7] for li in range(n_layers)]
+        src_of = []
+        for li in range(n_layers):
+            blk, pi = divmod(li, 7)
+            src_of.append({0: 7 * blk - 2, 1: 7 * blk - 2, 2: 7 * blk - 2, 3: 7 * blk, 4: 7 * blk + 3, 6: 7 * blk + 3,
+                           5: 7 * blk + 4}[pi] if (blk or pi > 2) else -1)
+        # y has std sqrt(in) * 0.028 for unit-variance x (a = -8 s, uniform codes): the gain undoes it
+        gain_of = [1.0 if k < 0 else 1.0 / (0.028 * layers[li].in_features ** 0.5) for li, k in enumerate(src_of)]
+        persistent_free = pmpd.Ordered(stack, stage_of, [-1] * n_layers, [1.0] * n_layers)
+        persistent_chain = pmpd.Ordered(stack, stage_of, src_of, gain_of)
         x = torch.from_numpy(workload.draw_step_activations(shape, args.seed, 0)).cuda()
         y = torch.zeros(stack.y_elems, dtype=torch.float32, device="cuda")
         y_ref = torch.zeros_like(y)
@@ -219,10 +233,22 @@ def secondary_workload(args) -> int:
             graph = _timed(g.replay, max(3, K // 10)) * 1e3
             _ramp(lambda: pmpd.decode_step(stack, b, x, y), 0.3)
             one = _timed(lambda: pmpd.decode_step(stack, b, x, y), K) * 1e3
+            y.zero_()
+            persistent_free.step(b, x, y)
+            torch.cuda.synchronize()
+            pers_ok = bool(torch.allclose(y, y_ref, rtol=1e-4, atol=1e-4)) and not persistent_free.timed_out()
+            _ramp(lambda: persistent_free.step(b, x, y), 0.3)
+            pers = _timed(lambda: persistent_free.step(b, x, y), K) * 1e3
+            _ramp(lambda: persistent_chain.step(b, x, y), 0.3)
+            chain = _timed(lambda: persistent_chain.step(b, x, y), K) * 1e3
+            torch.cuda.synchronize()
+            chain_ok = bool(torch.isfinite(y).all()) and not persistent_chain.timed_out()
             res[f"b{b}"] = {"one_launch_us": one, "ordered_eager_us": eager, "ordered_graph_us": graph,
-                            "matches_one_launch": close, "bit_identical": same, "graph_replays_match": all(replays)}
+                            "ordered_one_cooperative_launch_us": pers, "ordered_chained_inputs_us": chain,
+                            "matches_one_launch": close, "bit_identical": same, "graph_replays_match": all(replays),
+                            "cooperative_matches_one_launch": pers_ok, "chained_finite_and_no_timeout": chain_ok}
         out.update({"metric": "us/token of the 7B-shaped step launched in dependency order (128 stage launches) vs one launch",
-                    "unit": "us/token", "value": res["b4"]["ordered_graph_us"], "higher_is_better": False,
+                    "unit": "us/token", "value": res["b4"]["ordered_chained_inputs_us"], "higher_is_better": False,
                     "config": {"workload": "Llama-7B-shaped stack, stages (q,k,v) -> o -> (up,gate) -> down per block"},
                     "results": res})
     elif args.workload == "single":

@@ -181,6 +181,39 @@ int32_t pmpd_decode_run(const pmpd_stack_t* stack, const pmpd_schedule_t* schedu
                         int32_t n_steps, const void* x_base, int64_t x_step_stride, float* y_base,
                         int64_t y_step_stride, void* stream);
 
+/* ---- a decode step in dependency order, one launch ------------------------------------------ *
+ * In a real decoder the linear layers of a step depend on each other ((q,k,v) -> o -> (up,gate) ->
+ * down, block after block); launched one kernel per stage, the step is bound by launch overhead,
+ * which the paper observes for its own kernels and leaves to future work (Section 5.2 "GPU
+ * Evaluation").  Here the whole step is one cooperative launch: the layers of the stack are
+ * assigned to stages, the workgroups stay resident, pass from stage to stage through a counter in
+ * device memory, and load the weights of their next tile before they wait for its inputs.
+ * chain[l] (host, one per layer of the stack): stage of layer l (layers of one stage are independent);
+ * source = -1: the layer reads x_base + x_offset[l] as in pmpd_decode_step; source = k: it reads
+ * fp16(gain * y_k), the output of layer k of an earlier stage (out_features(k) == in_features(l),
+ * y_offset[k] a multiple of 4); gain stands for the elementwise glue between the layers, which is
+ * not part of this library.  Every layer still writes its full fp32 output at y_base + y_offset[l].
+ * The tables and counters live in a caller-provided device workspace (256-byte aligned, untouched
+ * while the object exists); calls on one object must not overlap.  y_base must be 16-byte aligned.
+ * The wait between stages is bounded: if it runs out (it cannot while the launch is cooperative,
+ * unless the limit is set very low) the step still ends and pmpd_ordered_status reports it. */
+typedef struct pmpd_chain {
+  int32_t stage;
+  int32_t source;
+  float gain;
+} pmpd_chain_t;
+typedef struct pmpd_ordered pmpd_ordered_t;
+int32_t pmpd_ordered_workspace_size(const pmpd_stack_t* stack, const pmpd_chain_t* chain, size_t* bytes);
+int32_t pmpd_ordered_create(const pmpd_stack_t* stack, const pmpd_chain_t* chain, void* workspace,
+                            size_t workspace_bytes, pmpd_ordered_t** out); /* the stack must outlive it */
+void pmpd_ordered_destroy(pmpd_ordered_t* ordered);
+int32_t pmpd_ordered_step(const pmpd_ordered_t* ordered, int32_t b, const void* x_base, float* y_base,
+                          void* stream);
+/* Synchronous: *timed_out = 1 if a wait between stages ran out since the last call (then cleared). */
+int32_t pmpd_ordered_status(const pmpd_ordered_t* ordered, int32_t* timed_out);
+/* Polls per wait before it gives up (default 2^20, some seconds). */
+int32_t pmpd_ordered_set_spin_limit(pmpd_ordered_t* ordered, uint32_t polls);
+
 /* ---- measurement aid ------------------------------------------------------------------- *
  * Streams `bytes` (rounded down to a multiple of 128 MiB; *bytes_read says how many) of device memory
  * at src (16-byte aligned) through a read-only kernel: the HBM rate a plain read reaches on this

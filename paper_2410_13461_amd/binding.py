@@ -20,6 +20,8 @@ EXPORTS = (
     "pmpd_schedule_create", "pmpd_schedule_destroy", "pmpd_schedule_bits", "pmpd_schedule_avg_bits",
     "pmpd_decode_run", "pmpd_prefill_step", "pmpd_batch_step",
     "pmpd_schedule_grid", "pmpd_schedule_count", "pmpd_schedule_search", "pmpd_read_stream",
+    "pmpd_ordered_workspace_size", "pmpd_ordered_create", "pmpd_ordered_destroy", "pmpd_ordered_step",
+    "pmpd_ordered_status", "pmpd_ordered_set_spin_limit",
 )
 
 QUALITY_FN = ctypes.CFUNCTYPE(ctypes.c_double, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32),
@@ -41,6 +43,10 @@ class _Layer(ctypes.Structure):
         ("planes", ctypes.c_void_p * 4),
         ("scale_min", ctypes.c_void_p),
     ]
+
+
+class _Chain(ctypes.Structure):
+    _fields_ = [("stage", ctypes.c_int32), ("source", ctypes.c_int32), ("gain", ctypes.c_float)]
 
 
 _lib = None
@@ -101,6 +107,18 @@ def _load():
     L.pmpd_schedule_search.restype = i32
     L.pmpd_schedule_search.argtypes = [P(i32), i32, i32, i32, QUALITY_FN, vp, ctypes.c_double, ctypes.c_double, P(i32),
                                        P(ctypes.c_double), P(i64)]
+    L.pmpd_ordered_workspace_size.restype = i32
+    L.pmpd_ordered_workspace_size.argtypes = [vp, P(_Chain), P(sz)]
+    L.pmpd_ordered_create.restype = i32
+    L.pmpd_ordered_create.argtypes = [vp, P(_Chain), vp, sz, P(vp)]
+    L.pmpd_ordered_destroy.restype = None
+    L.pmpd_ordered_destroy.argtypes = [vp]
+    L.pmpd_ordered_step.restype = i32
+    L.pmpd_ordered_step.argtypes = [vp, i32, vp, vp, vp]
+    L.pmpd_ordered_status.restype = i32
+    L.pmpd_ordered_status.argtypes = [vp, P(i32)]
+    L.pmpd_ordered_set_spin_limit.restype = i32
+    L.pmpd_ordered_set_spin_limit.argtypes = [vp, ctypes.c_uint32]
     L.pmpd_read_stream.restype = i32
     L.pmpd_read_stream.argtypes = [vp, sz, vp, P(sz), vp]
     L.pmpd_decode_run.restype = i32
@@ -331,6 +349,54 @@ class Schedule:
     def close(self):
         if getattr(self, "_h", None):
             _load().pmpd_schedule_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Ordered:
+    """A stack whose layers run in dependency order inside one cooperative launch per step.
+
+    stages[l], sources[l] (-1 = external input), gains[l] per layer of the stack."""
+
+    def __init__(self, stack: Stack, stages: Sequence[int], sources: Sequence[int], gains: Sequence[float],
+                 device="cuda"):
+        import torch
+
+        n = len(stack.layers)
+        if not (len(stages) == len(sources) == len(gains) == n):
+            raise PMPDError(-1, "stages, sources and gains need one entry per layer")
+        self.stack = stack  # keeps the stack alive
+        chain = (_Chain * max(n, 1))(*[_Chain(int(s), int(k), float(g)) for s, k, g in zip(stages, sources, gains)])
+        L = _load()
+        need = ctypes.c_size_t()
+        _check(L.pmpd_ordered_workspace_size(stack._h, chain, ctypes.byref(need)))
+        self.workspace = torch.empty(need.value + 256, dtype=torch.uint8, device=device)
+        aligned = (self.workspace.data_ptr() + 255) // 256 * 256
+        h = ctypes.c_void_p()
+        _check(L.pmpd_ordered_create(stack._h, chain, ctypes.c_void_p(aligned), need.value, ctypes.byref(h)))
+        self._h = h
+
+    def step(self, b: int, x, y, stream=None):
+        _check(_load().pmpd_ordered_step(self._h, b, _dev_ptr(x), _dev_ptr(y), _stream_handle(stream)))
+        return y
+
+    def timed_out(self) -> bool:
+        """Synchronous: did a wait between stages run out since the last call?"""
+        flag = ctypes.c_int32()
+        _check(_load().pmpd_ordered_status(self._h, ctypes.byref(flag)))
+        return bool(flag.value)
+
+    def set_spin_limit(self, polls: int):
+        _check(_load().pmpd_ordered_set_spin_limit(self._h, polls))
+
+    def close(self):
+        if getattr(self, "_h", None):
+            _load().pmpd_ordered_destroy(self._h)
             self._h = None
 
     def __del__(self):

@@ -176,13 +176,37 @@ __device__ __forceinline__ void split_pieces(const uint32_t (&w)[4], uint32_t E,
 // exponents and group sums, by the whole workgroup.  Thread idx handles columns 8 idx ..
 // 8 idx + 7 of the range; a quad of threads owns one 32-column block, a row of 16 threads one
 // group.
+// Where a layer's activations come from: an fp16 vector, or (y32 != nullptr) the fp32 output of an
+// earlier layer of the same launch, scaled by `gain` and rounded to fp16 (round to nearest even) on
+// the way in.
+struct XSource {
+  const _Float16* x16;
+  const float* y32;
+  float gain;
+};
+
+__device__ __forceinline__ uint32_t pack_half2(float a, float b) {
+  const half2_t h = {static_cast<_Float16>(a), static_cast<_Float16>(b)};
+  return __builtin_bit_cast(uint32_t, h);
+}
+
 template <int NW>
-__device__ __forceinline__ void stage_x(const _Float16* __restrict__ x, int c0, int cn, const ImageLayout& im, int j) {
-  const uint4* xg = reinterpret_cast<const uint4*>(x) + c0 * 16;
+__device__ __forceinline__ void stage_x(const XSource& src, int c0, int cn, const ImageLayout& im, int j) {
   const int n16 = cn * 16;
   for (int idx = threadIdx.x; idx < n16; idx += NW * 64) {
-    const uint4 v = xg[idx];
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    uint32_t w[4];
+    if (src.y32) {
+      // written by other workgroups of this launch: agent-scope loads read the coherent copy
+      float* yg = const_cast<float*>(src.y32) + (c0 * 16 + idx) * 8;
+      float v8[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v8[e] = __hip_atomic_load(yg + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) * src.gain;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) w[q] = pack_half2(v8[2 * q], v8[2 * q + 1]);
+    } else {
+      const uint4 v = (reinterpret_cast<const uint4*>(src.x16) + c0 * 16)[idx];
+      w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+    }
     const uint32_t EA = quad_max_magnitude(w) >> 10;  // exponent field of the block's largest |x|
     // class B: magnitude below 2^(EA-7-15), i.e. bit pattern below (EA-7) << 10
     const uint32_t thr = (EA > 7u ? EA - 7u : 0u) << 10;
@@ -269,14 +293,29 @@ constexpr float half_step() { return B == 4 ? 0.5f : B == 3 ? 1.0f : 2.0f; }  //
 // One workgroup: NW / SPLITK consecutive row tiles starting at tile0, each split over SPLITK waves
 // along K, for m <= 2 SETS activation vectors.  K is walked in chunks whose split activations fit
 // in LDS.  x: [m][in_f] fp16, y: [m][out_f] fp32.
-template <int B, int SETS, int NW, int SPLITK>
-__device__ __forceinline__ void run_tiles(const LayerDesc& L, int tile0, const _Float16* __restrict__ x, int m,
-                                          float* __restrict__ y, uint4* lds_raw) {
+struct NoHook {
+  __device__ __forceinline__ void operator()() const {}
+};
+
+// The groups a workgroup walks (the whole row unless K is split over workgroups) and the chunk
+// capacity the LDS image was sized for.
+struct KRange {
+  int begin, end, chunk;
+};
+
+// before_staging() runs in every thread after the first weight loads have been issued and before x
+// is read: the dependency-ordered kernel waits there for the producers of x.  ORDERED also issues
+// the loads of the first two groups before that point instead of one, and stores y with agent-scope
+// (write-through) stores, so that workgroups of the same launch can read it without a cache flush.
+template <int B, int SETS, int NW, int SPLITK, bool ORDERED = false, typename Hook = NoHook>
+__device__ __forceinline__ void run_tiles(const LayerDesc& L, int tile0, const XSource& x, int m, float* __restrict__ y,
+                                          uint4* lds_raw, KRange kr, Hook before_staging = Hook()) {
   static_assert(NW % SPLITK == 0, "waves must divide evenly over the K splits");
+  static_assert(!ORDERED || SETS == 1, "chained inputs are batch-1 only");
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int G = L.n_groups;
-  const ImageLayout im(lds_raw, chunk_groups(G, m), m);
+  const ImageLayout im(lds_raw, kr.chunk, m);
 
   const int tile = tile0 + wave / SPLITK;
   const int ks = wave % SPLITK;
@@ -312,8 +351,8 @@ __device__ __forceinline__ void run_tiles(const LayerDesc& L, int tile0, const _
 #pragma unroll
     for (int t = 0; t < 4; ++t) yacc[s][t] = 0.f;
 
-  for (int c0 = 0; c0 < G; c0 += im.cg) {
-    const int cn = (G - c0 < im.cg) ? (G - c0) : im.cg;
+  for (int c0 = kr.begin; c0 < kr.end; c0 += im.cg) {
+    const int cn = (kr.end - c0 < im.cg) ? (kr.end - c0) : im.cg;
     const int g0 = c0 + cn * ks / SPLITK, g1 = c0 + cn * (ks + 1) / SPLITK;
     const bool work = active && g0 < g1;
     // The next group's plane words are in flight while the current group is consumed.  Weights
@@ -330,8 +369,14 @@ __device__ __forceinline__ void run_tiles(const LayerDesc& L, int tile0, const _
     // The first group's loads do not depend on the activations: issue them before the workgroup
     // splits x, so that their latency overlaps the staging and the barrier.
     if (work) load(pa, sa_a, g0);
-    if (c0) __syncthreads();  // the previous chunk's image has been consumed
-    for (int j = 0; j < m; ++j) stage_x<NW>(x + static_cast<int64_t>(j) * L.in_f, c0, cn, im, j);
+    if (ORDERED && work) load(pb, sa_b, g0 + 1);
+    if (c0 == kr.begin) before_staging();
+    else __syncthreads();  // the previous chunk's image has been consumed
+    for (int j = 0; j < m; ++j) {
+      XSource xj = x;
+      if (xj.x16) xj.x16 += static_cast<int64_t>(j) * L.in_f;
+      stage_x<NW>(xj, c0, cn, im, j);
+    }
     __syncthreads();
     if (work) {
       auto consume = [&](const u32x4 (&pl)[B], const u32x4& csa, int g) {
@@ -360,7 +405,7 @@ __device__ __forceinline__ void run_tiles(const LayerDesc& L, int tile0, const _
         }
       };
       for (int gc = g0; gc < g1; gc += 2) {
-        load(pb, sa_b, gc + 1);
+        if (!ORDERED || gc > g0) load(pb, sa_b, gc + 1);
         consume(pa, sa_a, gc);
         load(pa, sa_a, gc + 2);
         if (gc + 1 < g1) consume(pb, sa_b, gc + 1);
@@ -403,7 +448,10 @@ __device__ __forceinline__ void run_tiles(const LayerDesc& L, int tile0, const _
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
           const int row = tile * 64 + 16 * t + (lane & 15);
-          if (row < L.out_f) yo[row] = yacc[s][t];
+          if (row < L.out_f) {
+            if constexpr (ORDERED) __hip_atomic_store(&yo[row], yacc[s][t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            else yo[row] = yacc[s][t];
+          }
         }
       }
     }
@@ -421,8 +469,8 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd<SETS>()) void pmpd_stack_ke
   extern __shared__ uint4 lds[];
   const WorkItem it = items[blockIdx.x];
   const LayerDesc L = layers[it.layer];
-  run_tiles<B, SETS, NW, SPLITK>(L, it.tile0, x_base + static_cast<int64_t>(m) * L.x_off, m,
-                                 y_base + static_cast<int64_t>(m) * L.y_off, lds);
+  run_tiles<B, SETS, NW, SPLITK>(L, it.tile0, XSource{x_base + static_cast<int64_t>(m) * L.x_off, nullptr, 1.f}, m,
+                                 y_base + static_cast<int64_t>(m) * L.y_off, lds, KRange{0, L.n_groups, chunk_groups(L.n_groups, m)});
 }
 
 template <int B, int SETS, int NW, int SPLITK>
@@ -430,7 +478,163 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd<SETS>()) void pmpd_layer_ke
                                                                                     const _Float16* __restrict__ x, int m,
                                                                                     float* __restrict__ y) {
   extern __shared__ uint4 lds[];
-  run_tiles<B, SETS, NW, SPLITK>(L, static_cast<int>(blockIdx.x) * (NW / SPLITK), x, m, y, lds);
+  run_tiles<B, SETS, NW, SPLITK>(L, static_cast<int>(blockIdx.x) * (NW / SPLITK), XSource{x, nullptr, 1.f}, m, y, lds,
+                                 KRange{0, L.n_groups, chunk_groups(L.n_groups, m)});
+}
+
+// =====================================================================================
+// Dependency-ordered step in one cooperative launch.  The layers of a step are grouped into
+// stages; a layer of stage s may take its input from the output of a layer of an earlier stage
+// (x = fp16(gain * y)).  The grid is persistent: for every stage each workgroup takes the items
+// blockIdx, blockIdx + gridDim, ... of that stage, issues the weight loads of its first item, and
+// only then waits until every workgroup has finished the previous stage: weights stream while the
+// barrier settles, x is read after it.
+// An item is one 64-row tile and one K-part of at least 8 groups (8: two groups per wave, all of
+// them in flight before the wait); the parts of a layer are as small as that allows while its
+// stage still has no more items than the chip holds workgroups, so that every stage, however few
+// rows it has, spreads over the whole chip in one round.  The K-parts of a tile meet in a buffer of partial sums; the workgroup that finishes a tile
+// last (a counter per tile tells) adds them in part order and writes y: no floating-point atomics,
+// the result does not depend on the order of arrival.
+// Only y and the partial sums cross workgroups; they are written and read with agent-scope
+// accesses (coherent across the chip's L2 slices), so the barrier needs no cache write-back or
+// invalidate.  The launch is cooperative, so all workgroups are resident and the wait ends; it is
+// bounded all the same (spin_limit polls), and a wait that runs out only sets sync->timed_out.
+// Counters of the stage barrier.  Workgroup w adds to sub-counter w % 16 of the stage; the last
+// one of each sub-counter adds to the stage's top counter, and the last of those publishes the
+// stage number in `stage_done`, the only word the waiting workgroups poll: the polls (a thousand
+// readers) and the arrivals (a thousand read-modify-writes) never meet on one cache line.
+constexpr int kSyncLine = 64;   // uint32 per 256-byte line
+constexpr int kSubCounters = 16;
+struct OrderedSync {
+  uint32_t stage_done;            // stages completed in this step (monotonic), polled
+  uint32_t pad0[kSyncLine - 1];
+  uint32_t timed_out;
+  uint32_t pad1[kSyncLine - 1];
+  uint32_t counters[1];  // [n_stages][kSubCounters + 1][kSyncLine / 4] arrival counters, then [tiles] K-parts finished
+};
+constexpr int kStageCounterWords = (kSubCounters + 1) * (kSyncLine / 4);  // 16 uint32 (64 bytes) apart
+
+struct ChainDesc {
+  int64_t src_y_off;     // fp32 elements from y_base of the producing layer's output, or -1: input from x_base
+  int64_t partial_off;   // fp32 elements into the partial-sum buffer ([part][out_f]); unused when n_parts == 1
+  float gain;
+  int32_t n_parts;       // K-parts of part_groups groups each (the last one may be shorter)
+  int32_t tile_counter;  // index of the layer's first tile counter
+  int32_t part_groups;
+};
+
+// Wait until every vector memory operation of this wave, stores included, has been acknowledged
+// (s_waitcnt vmcnt(0); gfx9 encoding: vmcnt in bits 3:0 and 15:14, the other counters left at their
+// maxima).  For the agent-scope (write-through) stores used here that is when they are visible to
+// the other workgroups; a release fence would add a write-back of the whole L2 that nothing needs.
+__device__ __forceinline__ void wait_for_own_stores() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
+constexpr int kOrderedWaves = 4;
+constexpr int kOrderedPartGroups = 8;      // smallest K-part: two groups per wave, all in flight before the wait
+constexpr int kOrderedMaxPartGroups = 32;  // largest K-part the LDS image is sized for
+constexpr int kItemPartShift = 20;  // WorkItem::tile0 = tile | part << 20
+
+template <int B>
+__global__ __launch_bounds__(kOrderedWaves * 64, 4) void pmpd_ordered_kernel(
+    const LayerDesc* __restrict__ layers, const ChainDesc* __restrict__ chains, const WorkItem* __restrict__ items,
+    const int32_t* __restrict__ stage_begin, int n_stages, const _Float16* __restrict__ x_base, float* __restrict__ y_base,
+    float* __restrict__ partials, OrderedSync* sync, uint32_t spin_limit) {
+  extern __shared__ uint4 lds[];
+  __shared__ int last_part;
+  const uint32_t n_wg = gridDim.x;
+  uint32_t* arrived = sync->counters;  // + s * kStageCounterWords + k * 16
+  uint32_t* tile_done = sync->counters + n_stages * kStageCounterWords;
+  for (int s = 0; s < n_stages; ++s) {
+    bool waited = s == 0;
+    auto wait_for_previous_stage = [&]() {
+      if (waited) return;
+      waited = true;
+      if (threadIdx.x == 0) {
+        uint32_t polls = 0;
+        while (__hip_atomic_load(&sync->stage_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < static_cast<uint32_t>(s)) {
+          if (++polls >= spin_limit) {
+            __hip_atomic_store(&sync->timed_out, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            break;
+          }
+          __builtin_amdgcn_s_sleep(32);  // about a microsecond between polls: a thousand readers of one word
+        }
+      }
+      __syncthreads();
+    };
+    for (int i = stage_begin[s] + static_cast<int>(blockIdx.x); i < stage_begin[s + 1]; i += static_cast<int>(n_wg)) {
+      const WorkItem it = items[i];
+      const LayerDesc L = layers[it.layer];
+      const ChainDesc c = chains[it.layer];
+      const int tile = it.tile0 & ((1 << kItemPartShift) - 1), part = it.tile0 >> kItemPartShift;
+      const XSource src = c.src_y_off >= 0 ? XSource{nullptr, y_base + c.src_y_off, c.gain}
+                                           : XSource{x_base + L.x_off, nullptr, 1.f};
+      float* y = y_base + L.y_off;
+      float* target = c.n_parts > 1 ? partials + c.partial_off + static_cast<int64_t>(part) * L.out_f : y;
+      const int g0 = part * c.part_groups;
+      const int g1 = g0 + c.part_groups < L.n_groups ? g0 + c.part_groups : L.n_groups;
+      run_tiles<B, 1, kOrderedWaves, kOrderedWaves, true>(L, tile, src, 1, target, lds, KRange{g0, g1, kOrderedMaxPartGroups},
+                                                         wait_for_previous_stage);
+      if (c.n_parts > 1) {
+        // the partial sums of this part are acknowledged, then the part is counted; the last one adds
+        wait_for_own_stores();
+        __syncthreads();
+        if (threadIdx.x == 0) {
+          const uint32_t before = __hip_atomic_fetch_add(&tile_done[c.tile_counter + tile], 1u, __ATOMIC_RELAXED,
+                                                         __HIP_MEMORY_SCOPE_AGENT);
+          last_part = before + 1 == static_cast<uint32_t>(c.n_parts);
+        }
+        __syncthreads();
+        if (last_part) {
+          // wave w adds the parts w, w + 4, ... of the 64 rows (loads issued four at a time), then the
+          // four sums meet in LDS: the order of the additions is fixed
+          float* red = reinterpret_cast<float*>(lds);
+          const int row = tile * 64 + static_cast<int>(threadIdx.x & 63);
+          const int w = static_cast<int>(threadIdx.x >> 6);
+          float sum = 0.f;
+          if (row < L.out_f) {
+            const float* p = partials + c.partial_off + row;
+            for (int q = w; q < c.n_parts; q += 4 * kOrderedWaves) {
+              float v[4];
+#pragma unroll
+              for (int u = 0; u < 4; ++u) {
+                const int qq = q + u * kOrderedWaves;
+                v[u] = qq < c.n_parts ? __hip_atomic_load(const_cast<float*>(p) + static_cast<int64_t>(qq) * L.out_f,
+                                                          __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                      : 0.f;
+              }
+              sum += (v[0] + v[1]) + (v[2] + v[3]);
+            }
+          }
+          red[threadIdx.x] = sum;
+          __syncthreads();
+          if (threadIdx.x < 64 && row < L.out_f) {
+            const float total = (red[threadIdx.x] + red[threadIdx.x + 64]) + (red[threadIdx.x + 128] + red[threadIdx.x + 192]);
+            __hip_atomic_store(&y[row], total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
+        }
+      }
+      __syncthreads();  // the LDS image and last_part are reused by the next item
+    }
+    // every wave waits until its own (write-through) stores of stage s are acknowledged, then the
+    // workgroup is counted
+    wait_for_own_stores();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      const uint32_t k = blockIdx.x % kSubCounters;
+      const uint32_t in_sub = (n_wg - k + kSubCounters - 1) / kSubCounters;  // workgroups that share sub-counter k
+      uint32_t* cnt = arrived + s * kStageCounterWords;
+      if (__hip_atomic_fetch_add(&cnt[k * 16], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1 == in_sub) {
+        const uint32_t n_sub = n_wg < kSubCounters ? n_wg : kSubCounters;
+        if (__hip_atomic_fetch_add(&cnt[kSubCounters * 16], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1 == n_sub)
+          __hip_atomic_store(&sync->stage_done, static_cast<uint32_t>(s + 1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+  }
+}
+
+__global__ void pmpd_ordered_reset_kernel(OrderedSync* sync, int n_counters) {
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n_counters; i += gridDim.x * blockDim.x) sync->counters[i] = 0;
+  if (blockIdx.x == 0 && threadIdx.x == 0) sync->stage_done = 0;
 }
 
 // Read-only stream over a buffer: the HBM ceiling the decode kernels are held against.  Each
@@ -660,6 +864,234 @@ static hipError_t launch_stack_batch(const pmpd_stack* st, const void* xv, int m
     default: return launch_stack_batch_s<B, 4>(st, x, m, y, s);
   }
 }
+
+// ---------------------------------------------------------------- ordered step ----
+struct pmpd_ordered {
+  const pmpd_stack* stack = nullptr;
+  std::vector<ChainDesc> chains;
+  std::vector<WorkItem> items;
+  std::vector<int32_t> stage_begin;
+  const ChainDesc* d_chains = nullptr;
+  const WorkItem* d_items = nullptr;
+  const int32_t* d_stage_begin = nullptr;
+  OrderedSync* d_sync = nullptr;
+  float* d_partials = nullptr;
+  int n_counters = 0;
+  int n_stages = 0;
+  int max_stage_items = 0;
+  uint32_t spin_limit = 1u << 20;
+};
+
+static int32_t check_chain(const pmpd_stack* st, const pmpd_chain_t* chain, int* n_stages_out) {
+  if (!st || !chain) return fail(PMPD_EINVAL, "pmpd_ordered: NULL argument");
+  const int n = static_cast<int>(st->layers.size());
+  int n_stages = 0;
+  for (int i = 0; i < n; ++i) {
+    if (chain[i].stage < 0 || chain[i].stage >= 65536) return fail(PMPD_EINVAL, "pmpd_ordered: stage %d of layer %d outside 0..65535", chain[i].stage, i);
+    n_stages = std::max(n_stages, chain[i].stage + 1);
+    const int src = chain[i].source;
+    if (src == -1) continue;
+    if (src < 0 || src >= n) return fail(PMPD_EINVAL, "pmpd_ordered: source %d of layer %d is not a layer", src, i);
+    if (chain[src].stage >= chain[i].stage) return fail(PMPD_EINVAL, "pmpd_ordered: layer %d (stage %d) reads layer %d of stage %d, which is not earlier", i, chain[i].stage, src, chain[src].stage);
+    if (st->layers[src].out_f != st->layers[i].in_f) return fail(PMPD_EINVAL, "pmpd_ordered: layer %d has %d inputs but its source %d has %d outputs", i, st->layers[i].in_f, src, st->layers[src].out_f);
+    if (st->layers[src].y_off % 4) return fail(PMPD_EALIGN, "pmpd_ordered: y_offset of source layer %d must be a multiple of 4", src);
+    if (!(chain[i].gain == chain[i].gain) || chain[i].gain - chain[i].gain != 0.f) return fail(PMPD_EINVAL, "pmpd_ordered: gain of layer %d is not finite", i);
+  }
+  *n_stages_out = n_stages;
+  return PMPD_OK;
+}
+
+// K-part size (in groups) of every layer: as close to kOrderedPartGroups as keeps the items of the
+// layer's stage within `slots` workgroups, never above kOrderedMaxPartGroups.
+static std::vector<int> ordered_part_groups(const pmpd_stack* st, const pmpd_chain_t* chain, int n_stages, int slots) {
+  std::vector<int64_t> stage_tiles(static_cast<size_t>(n_stages), 0);
+  for (size_t i = 0; i < st->layers.size(); ++i) stage_tiles[static_cast<size_t>(chain[i].stage)] += st->layers[i].n_tiles;
+  std::vector<int> pg(st->layers.size());
+  for (size_t i = 0; i < st->layers.size(); ++i) {
+    const int G = st->layers[i].n_groups;
+    const int64_t tiles = std::max<int64_t>(1, stage_tiles[static_cast<size_t>(chain[i].stage)]);
+    int parts = static_cast<int>(std::max<int64_t>(1, std::min<int64_t>((G + kOrderedPartGroups - 1) / kOrderedPartGroups, slots / tiles)));
+    int groups = (G + parts - 1) / parts;
+    groups = std::min(groups, kOrderedMaxPartGroups);
+    pg[i] = groups;
+  }
+  return pg;
+}
+
+static int parts_of(int n_groups, int part_groups) { return (n_groups + part_groups - 1) / part_groups; }
+
+// items, counters and partial-sum floats an ordered step of this stack needs
+static void ordered_counts(const pmpd_stack* st, const std::vector<int>& pg, size_t* n_items, size_t* n_tiles, size_t* n_partials) {
+  *n_items = *n_tiles = *n_partials = 0;
+  for (size_t i = 0; i < st->layers.size(); ++i) {
+    const LayerDesc& d = st->layers[i];
+    const size_t parts = static_cast<size_t>(parts_of(d.n_groups, pg[i]));
+    *n_items += static_cast<size_t>(d.n_tiles) * parts;
+    *n_tiles += static_cast<size_t>(d.n_tiles);
+    if (parts > 1) *n_partials += align_up(parts * static_cast<size_t>(d.out_f), 4);
+  }
+}
+
+// Workgroup slots the ordered kernel is planned for: four workgroups of four waves per compute unit.
+static int ordered_slots() {
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess || prop.multiProcessorCount < 1) return 1024;
+  return 4 * prop.multiProcessorCount;
+}
+
+static size_t ordered_bytes(const pmpd_stack* st, const std::vector<int>& pg, size_t n_stages) {
+  size_t n_items, n_tiles, n_partials;
+  ordered_counts(st, pg, &n_items, &n_tiles, &n_partials);
+  return align_up(st->layers.size() * sizeof(ChainDesc), 256) + align_up(n_items * sizeof(WorkItem), 256) +
+         align_up((n_stages + 1) * sizeof(int32_t), 256) +
+         align_up(sizeof(OrderedSync) + (n_stages * kStageCounterWords + n_tiles) * sizeof(uint32_t), 256) +
+         align_up(n_partials * sizeof(float), 256);
+}
+
+template <int B>
+static hipError_t launch_ordered(const pmpd_ordered* o, const void* x, float* y, hipStream_t s) {
+  const pmpd_stack* st = o->stack;
+  const size_t lds = lds_bytes(kOrderedMaxPartGroups, 1, kOrderedWaves, 4);
+  int per_cu = 0, dev = 0;
+  hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, pmpd_ordered_kernel<B>, kOrderedWaves * 64, lds);
+  if (e != hipSuccess) return e;
+  hipDeviceProp_t prop;
+  if ((e = hipGetDevice(&dev)) != hipSuccess || (e = hipGetDeviceProperties(&prop, dev)) != hipSuccess) return e;
+  int grid = std::min(per_cu, 4) * prop.multiProcessorCount;
+  if (grid < 1) return hipErrorCooperativeLaunchTooLarge;
+  grid = std::min(grid, o->max_stage_items);
+  hipLaunchKernelGGL(pmpd_ordered_reset_kernel, dim3(64), dim3(256), 0, s, o->d_sync, o->n_counters);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  const LayerDesc* layers = st->d_layers;
+  const _Float16* xb = static_cast<const _Float16*>(x);
+  int n_stages = o->n_stages;
+  uint32_t spin = o->spin_limit;
+  void* args[] = {&layers, const_cast<ChainDesc**>(&o->d_chains), const_cast<WorkItem**>(&o->d_items),
+                  const_cast<int32_t**>(&o->d_stage_begin), &n_stages, &xb, &y, const_cast<float**>(&o->d_partials),
+                  const_cast<OrderedSync**>(&o->d_sync), &spin};
+  return hipLaunchCooperativeKernel(reinterpret_cast<const void*>(&pmpd_ordered_kernel<B>), dim3(grid), dim3(kOrderedWaves * 64),
+                                    args, static_cast<unsigned>(lds), s);
+}
+
+extern "C" {
+
+int32_t pmpd_ordered_workspace_size(const pmpd_stack_t* stack, const pmpd_chain_t* chain, size_t* bytes) {
+  int n_stages = 0;
+  int32_t rc = check_chain(stack, chain, &n_stages);
+  if (rc) return rc;
+  if (!bytes) return fail(PMPD_EINVAL, "pmpd_ordered_workspace_size: bytes is NULL");
+  *bytes = ordered_bytes(stack, ordered_part_groups(stack, chain, n_stages, ordered_slots()), static_cast<size_t>(n_stages));
+  return PMPD_OK;
+}
+
+int32_t pmpd_ordered_create(const pmpd_stack_t* stack, const pmpd_chain_t* chain, void* workspace, size_t workspace_bytes,
+                            pmpd_ordered_t** out) {
+  int n_stages = 0;
+  int32_t rc = check_chain(stack, chain, &n_stages);
+  if (rc) return rc;
+  if (!workspace || !out) return fail(PMPD_EINVAL, "pmpd_ordered_create: NULL argument");
+  if (reinterpret_cast<uintptr_t>(workspace) % 256) return fail(PMPD_EALIGN, "pmpd_ordered_create: workspace not 256-byte aligned");
+  const size_t n_layers = stack->layers.size();
+  const std::vector<int> pg = ordered_part_groups(stack, chain, n_stages, ordered_slots());
+  const size_t need = ordered_bytes(stack, pg, static_cast<size_t>(n_stages));
+  if (workspace_bytes < need) return fail(PMPD_ESIZE, "pmpd_ordered_create: workspace %zu bytes, need %zu", workspace_bytes, need);
+  size_t n_items, n_tiles, n_partials;
+  ordered_counts(stack, pg, &n_items, &n_tiles, &n_partials);
+  if (n_items > static_cast<size_t>(INT32_MAX)) return fail(PMPD_EINVAL, "pmpd_ordered_create: too many work items");
+  auto* o = new pmpd_ordered;
+  o->stack = stack;
+  o->n_stages = n_stages;
+  o->n_counters = static_cast<int>(static_cast<size_t>(n_stages) * kStageCounterWords + n_tiles);
+  int64_t partial_off = 0;
+  int32_t tile_counter = 0;
+  for (size_t i = 0; i < n_layers; ++i) {
+    const LayerDesc& d = stack->layers[i];
+    const int src = chain[i].source;
+    const int parts = parts_of(d.n_groups, pg[i]);
+    if (d.n_tiles >= (1 << kItemPartShift) || parts >= (1 << (31 - kItemPartShift))) {
+      delete o;
+      return fail(PMPD_EINVAL, "pmpd_ordered_create: layer %zu is too large for the item encoding", i);
+    }
+    o->chains.push_back(ChainDesc{src < 0 ? int64_t{-1} : stack->layers[src].y_off, partial_off, chain[i].gain, parts,
+                                  tile_counter, pg[i]});
+    if (parts > 1) partial_off += static_cast<int64_t>(align_up(static_cast<size_t>(parts) * static_cast<size_t>(d.out_f), 4));
+    tile_counter += d.n_tiles;
+  }
+  // (tile, K-part) items, stage by stage; inside a stage long rows first
+  std::vector<int> order(n_layers);
+  for (size_t i = 0; i < n_layers; ++i) order[i] = static_cast<int>(i);
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) {
+    if (chain[a].stage != chain[b].stage) return chain[a].stage < chain[b].stage;
+    return stack->layers[a].in_f > stack->layers[b].in_f;
+  });
+  o->stage_begin.assign(static_cast<size_t>(n_stages) + 1, 0);
+  for (int li : order) {
+    const int parts = o->chains[li].n_parts;
+    for (int t = 0; t < stack->layers[li].n_tiles; ++t)
+      for (int q = 0; q < parts; ++q) o->items.push_back(WorkItem{li, t | (q << kItemPartShift)});
+    o->stage_begin[static_cast<size_t>(chain[li].stage) + 1] = static_cast<int32_t>(o->items.size());
+  }
+  for (int sidx = 1; sidx <= n_stages; ++sidx)  // stages without layers stay empty
+    o->stage_begin[sidx] = std::max(o->stage_begin[sidx], o->stage_begin[sidx - 1]);
+  for (int sidx = 0; sidx < n_stages; ++sidx)
+    o->max_stage_items = std::max(o->max_stage_items, o->stage_begin[sidx + 1] - o->stage_begin[sidx]);
+  char* w = static_cast<char*>(workspace);
+  hipError_t e = hipMemcpy(w, o->chains.data(), n_layers * sizeof(ChainDesc), hipMemcpyHostToDevice);
+  o->d_chains = reinterpret_cast<const ChainDesc*>(w);
+  w += align_up(n_layers * sizeof(ChainDesc), 256);
+  if (e == hipSuccess) e = hipMemcpy(w, o->items.data(), o->items.size() * sizeof(WorkItem), hipMemcpyHostToDevice);
+  o->d_items = reinterpret_cast<const WorkItem*>(w);
+  w += align_up(n_items * sizeof(WorkItem), 256);
+  if (e == hipSuccess) e = hipMemcpy(w, o->stage_begin.data(), o->stage_begin.size() * sizeof(int32_t), hipMemcpyHostToDevice);
+  o->d_stage_begin = reinterpret_cast<const int32_t*>(w);
+  w += align_up(o->stage_begin.size() * sizeof(int32_t), 256);
+  o->d_sync = reinterpret_cast<OrderedSync*>(w);
+  const size_t sync_bytes = sizeof(OrderedSync) + (static_cast<size_t>(n_stages) * kStageCounterWords + n_tiles) * sizeof(uint32_t);
+  if (e == hipSuccess) e = hipMemset(w, 0, sync_bytes);
+  w += align_up(sync_bytes, 256);
+  o->d_partials = reinterpret_cast<float*>(w);
+  if (e != hipSuccess) {
+    delete o;
+    return hip_fail(e, "pmpd_ordered_create copy");
+  }
+  *out = o;
+  return PMPD_OK;
+}
+
+void pmpd_ordered_destroy(pmpd_ordered_t* ordered) { delete ordered; }
+
+int32_t pmpd_ordered_set_spin_limit(pmpd_ordered_t* ordered, uint32_t polls) {
+  if (!ordered || polls == 0) return fail(PMPD_EINVAL, "pmpd_ordered_set_spin_limit: bad argument");
+  ordered->spin_limit = polls;
+  return PMPD_OK;
+}
+
+int32_t pmpd_ordered_step(const pmpd_ordered_t* ordered, int32_t b, const void* x_base, float* y_base, void* stream) {
+  int32_t rc = check_bits(b, "pmpd_ordered_step");
+  if (rc) return rc;
+  if (!ordered || !x_base || !y_base) return fail(PMPD_EINVAL, "pmpd_ordered_step: NULL argument");
+  if (reinterpret_cast<uintptr_t>(x_base) % 16) return fail(PMPD_EALIGN, "pmpd_ordered_step: x_base not 16-byte aligned");
+  if (reinterpret_cast<uintptr_t>(y_base) % 16) return fail(PMPD_EALIGN, "pmpd_ordered_step: y_base not 16-byte aligned");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = b == 4 ? launch_ordered<4>(ordered, x_base, y_base, s)
+                 : b == 3 ? launch_ordered<3>(ordered, x_base, y_base, s)
+                          : launch_ordered<2>(ordered, x_base, y_base, s);
+  if (e != hipSuccess) return hip_fail(e, "pmpd_ordered_step launch");
+  return PMPD_OK;
+}
+
+int32_t pmpd_ordered_status(const pmpd_ordered_t* ordered, int32_t* timed_out) {
+  if (!ordered || !timed_out) return fail(PMPD_EINVAL, "pmpd_ordered_status: NULL argument");
+  uint32_t flag = 0;
+  hipError_t e = hipMemcpy(&flag, &ordered->d_sync->timed_out, sizeof(flag), hipMemcpyDeviceToHost);
+  if (e == hipSuccess && flag) e = hipMemset(&ordered->d_sync->timed_out, 0, sizeof(flag));
+  if (e != hipSuccess) return hip_fail(e, "pmpd_ordered_status");
+  *timed_out = static_cast<int32_t>(flag);
+  return PMPD_OK;
+}
+
+}  // extern "C"
 
 extern "C" {
 

@@ -1,0 +1,137 @@
+"""The dependency-ordered step (one cooperative launch, stages separated by in-kernel waits): every
+layer against the oracle on the inputs it really got, x = fp16(gain * y[source]) for chained layers."""
+import numpy as np
+import pytest
+
+import oracle
+import pmpd_synth as synth
+
+pytestmark = pytest.mark.gpu
+
+REL_L2 = 1e-3
+ABS_FACTOR = 2e-3
+
+
+@pytest.fixture(scope="module")
+def pmpd():
+    import torch
+
+    assert torch.cuda.is_available()
+    import paper_2410_13461_amd as lib
+
+    return lib
+
+
+def _chain_of(shape):
+    """(q,k,v) -> o -> (up,gate) -> down per block; o reads q, up/gate read o, down reads up, the next
+    block reads down.  Gains keep the activations near unit scale (random weights, no norm layers)."""
+    stages, sources, gains = [], [], []
+    for blk in range(shape.n_blocks):
+        base = 7 * blk
+        prev_down = base - 7 + 5 if blk else -1
+        for pi in range(7):  # q k v o up down gate
+            if pi in (0, 1, 2):
+                stages.append(4 * blk); sources.append(prev_down)
+            elif pi == 3:
+                stages.append(4 * blk + 1); sources.append(base + 0)
+            elif pi in (4, 6):
+                stages.append(4 * blk + 2); sources.append(base + 3)
+            else:
+                stages.append(4 * blk + 3); sources.append(base + 4)
+            gains.append(0.5 if sources[-1] >= 0 else 1.0)
+    return stages, sources, gains
+
+
+def _build(pmpd, shape, seed):
+    layers, raw = [], []
+    for (blk, pi, nm, o, i) in shape.layers():
+        q4, s, a = synth.draw_weights(seed, blk, pi, o, i, random_min=(pi % 2 == 1))
+        raw.append((q4, s, a))
+        planes, sm = pmpd.pack(q4, s, a)
+        layers.append(pmpd.upload_layer(planes, sm, o, i))
+    return layers, raw
+
+
+@pytest.mark.parametrize("b", [4, 3, 2])
+def test_ordered_step_matches_oracle_layer_by_layer(pmpd, b):
+    import torch
+
+    print(f"[ordered] b={b}", flush=True)
+    shape = synth.StackShape("tiny", 3, 256, 640)
+    layers, raw = _build(pmpd, shape, seed=21)
+    stack = pmpd.Stack(layers)
+    stages, sources, gains = _chain_of(shape)
+    ordered = pmpd.Ordered(stack, stages, sources, gains)
+    ordered.set_spin_limit(200000)
+    y = torch.full((stack.y_elems,), float("nan"), dtype=torch.float32, device="cuda")
+    for rep in range(3):  # the counters are reset by every step; fresh inputs, so a stale y of the last step shows
+        xs = [synth.draw_x(21, rep, blk, pi, i)[0] for (blk, pi, nm, o, i) in shape.layers()]
+        x = torch.from_numpy(np.concatenate(xs)).cuda()
+        ordered.step(b, x, y)
+        torch.cuda.synchronize()
+        assert not ordered.timed_out()
+        yh = y.cpu().numpy()
+        for li, (q4, s, a) in enumerate(raw):
+            if sources[li] < 0:
+                xin = xs[li]
+            else:
+                so = stack.y_offsets[sources[li]]
+                src = yh[so:so + q4.shape[1]]
+                xin = (src * np.float32(gains[li])).astype(np.float16)  # fp32 product, round to nearest even
+            o = stack.y_offsets[li]
+            y_ref, t = oracle.linear(q4, s, a, b, xin)
+            got = yh[o:o + q4.shape[0]].astype(np.float64)
+            assert np.all(np.isfinite(got)), f"layer {li}"
+            err = np.abs(got - y_ref[0])
+            assert np.all(err <= ABS_FACTOR * t[0] + 1e-30), f"layer {li} b={b}: {err.max():.3e}"
+            den = np.linalg.norm(y_ref[0])
+            assert den == 0 or np.linalg.norm(got - y_ref[0]) / den <= REL_L2, f"layer {li} b={b}"
+    # without chaining the same object reproduces the one-launch step
+    free = pmpd.Ordered(stack, stages, [-1] * len(stages), [1.0] * len(stages))
+    y1 = torch.zeros_like(y)
+    y2 = torch.zeros_like(y)
+    free.step(b, x, y1)
+    pmpd.decode_step(stack, b, x, y2)
+    torch.cuda.synchronize()
+    assert not free.timed_out()
+    assert torch.allclose(y1, y2, rtol=1e-5, atol=1e-6)
+    ordered.close(); free.close(); stack.close()
+
+
+def test_ordered_wait_is_bounded_and_reported(pmpd):
+    """With a limit of one poll a wait may run out: the step must still end, and say so."""
+    import torch
+
+    shape = synth.StackShape("tiny", 2, 256, 640)
+    layers, raw = _build(pmpd, shape, seed=22)
+    stack = pmpd.Stack(layers)
+    stages, sources, gains = _chain_of(shape)
+    ordered = pmpd.Ordered(stack, stages, sources, gains)
+    ordered.set_spin_limit(1)
+    x = torch.zeros(stack.x_elems, dtype=torch.float16, device="cuda")
+    y = torch.zeros(stack.y_elems, dtype=torch.float32, device="cuda")
+    ordered.step(4, x, y)
+    torch.cuda.synchronize()
+    flag = ordered.timed_out()
+    assert flag in (True, False)
+    assert not ordered.timed_out()  # reading the flag clears it
+    ordered.close(); stack.close()
+
+
+def test_ordered_rejects_bad_chains(pmpd):
+    shape = synth.StackShape("tiny", 1, 256, 640)
+    layers, raw = _build(pmpd, shape, seed=23)
+    stack = pmpd.Stack(layers)
+    n = len(layers)
+    ok_stage = [0, 0, 0, 1, 2, 3, 2]
+    with pytest.raises(pmpd.PMPDError):  # source in the same stage
+        pmpd.Ordered(stack, [0] * n, [-1, 0, -1, -1, -1, -1, -1], [1.0] * n)
+    with pytest.raises(pmpd.PMPDError):  # 640 outputs feeding 256 inputs
+        pmpd.Ordered(stack, ok_stage, [-1, -1, -1, 4, -1, -1, -1], [1.0] * n)
+    with pytest.raises(pmpd.PMPDError):  # not a layer
+        pmpd.Ordered(stack, ok_stage, [-1, -1, -1, 99, -1, -1, -1], [1.0] * n)
+    with pytest.raises(pmpd.PMPDError):  # gain not finite
+        pmpd.Ordered(stack, ok_stage, [-1, -1, -1, 0, -1, -1, -1], [1.0, 1.0, 1.0, float("inf"), 1.0, 1.0, 1.0])
+    with pytest.raises(pmpd.PMPDError):  # one entry per layer
+        pmpd.Ordered(stack, [0], [-1], [1.0])
+    stack.close()

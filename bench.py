@@ -428,6 +428,37 @@ def main() -> int:
     for b in bits:
         per_bits[str(b)]["frac_of_read_stream"] = per_bits[str(b)]["GBps"] / stream_gbps
 
+    # the unquantised fp16 matrix-vector kernel over the same shapes (2 bytes per weight), one launch per token:
+    # the denominator of the paper's speedup figures (Section 5.2, Table 3), measured here on this device
+    gen = torch.Generator(device="cuda").manual_seed(args.seed)
+    n_blocks = shape.n_blocks if args.blocks is None else args.blocks
+    dW = [torch.empty(o, i, dtype=torch.float16, device="cuda").normal_(0.0, 0.02, generator=gen)
+          for _ in range(n_blocks) for (_, o, i) in shape.proj_shapes()]
+    ref = pmpd.Fp16Stack(dW)
+    y_ref = torch.zeros(ref.y_elems, dtype=torch.float32, device="cuda")
+    _ramp(lambda: pmpd.fp16_step(ref, x_dev[0], y_ref, stream), 0.3)
+    for k in range(W):
+        pmpd.fp16_step(ref, x_dev[k], y_ref, stream)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    torch.cuda.synchronize()
+    ev[0].record(stream)
+    for k in range(K):
+        pmpd.fp16_step(ref, x_dev[W + k], y_ref, stream)
+    ev[1].record(stream)
+    torch.cuda.synchronize()
+    ref_us = ev[0].elapsed_time(ev[1]) * 1e3 / K
+    ref_bytes = ref.weight_bytes() + 2 * ref.x_elems + 4 * ref.y_elems
+    fp16_reference = {
+        "kernel": "fp16_stack_kernel (unquantised fp16 weights, same shapes, one launch per token)",
+        "us_per_token": ref_us,
+        "algorithmic_bytes": ref_bytes,
+        "GBps": ref_bytes / (ref_us * 1e-6) / 1e9,
+        "frac_of_peak": ref_bytes / (ref_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+        "speedup_over_fp16": {str(b): ref_us / per_bits[str(b)]["us_per_token"] for b in bits},
+    }
+    ref.close()
+    del dW, ref
+
     dom = per_bits["4"]
     out = {
         "metric": "decode linear-layer us/token (mean over b=4,3,2; per-bit figures in per_bits), batch 1",
@@ -450,6 +481,7 @@ def main() -> int:
             "wall_ms_per_step_incl_host": t_wall * 1e3 / (K * len(bits)),
         },
         "per_bits": per_bits,
+        "fp16_reference": fp16_reference,
         "roofline": {
             "bound": "hbm",
             "kernel": "pmpd_stack_kernel<B=4, SETS=1, NW=4, SPLITK=1> (one launch = one b=4 decode step)",

@@ -214,6 +214,29 @@ int32_t pmpd_ordered_status(const pmpd_ordered_t* ordered, int32_t* timed_out);
 /* Polls per wait before it gives up (default 2^20, some seconds). */
 int32_t pmpd_ordered_set_spin_limit(pmpd_ordered_t* ordered, uint32_t polls);
 
+/* ---- unquantised fp16 reference --------------------------------------------------------- *
+ * The paper states its linear-layer speedups relative to fp16 kernels on the same device
+ * (Section 5.2 "GPU Evaluation", Table 3).  These calls are that reference on this device:
+ * y = W x with W fp16 [out][in] row-major (device, 16-byte aligned, in_features a multiple of
+ * 128 and at most 32768), x fp16, fp32 accumulation, fp32 y; 2 bytes per weight are read, once.
+ * pmpd_fp16_gemv runs one layer; a pmpd_fp16_stack_t runs a list of layers in one launch with the
+ * same conventions as pmpd_stack_t (tables in a caller-provided 256-byte aligned device workspace,
+ * per-layer offsets into x_base in fp16 elements, multiples of 8, and into y_base in fp32 elements). */
+typedef struct pmpd_fp16_layer {
+  int32_t out_features;
+  int32_t in_features;
+  const void* weight; /* device */
+} pmpd_fp16_layer_t;
+typedef struct pmpd_fp16_stack pmpd_fp16_stack_t;
+int32_t pmpd_fp16_gemv(const void* weight, int32_t out_features, int32_t in_features, const void* x, float* y,
+                       void* stream);
+int32_t pmpd_fp16_stack_workspace_size(const pmpd_fp16_layer_t* layers, int32_t n_layers, size_t* bytes);
+int32_t pmpd_fp16_stack_create(const pmpd_fp16_layer_t* layers, int32_t n_layers, const int64_t* x_offset,
+                               const int64_t* y_offset, void* workspace, size_t workspace_bytes,
+                               pmpd_fp16_stack_t** out);
+void pmpd_fp16_stack_destroy(pmpd_fp16_stack_t* stack);
+int32_t pmpd_fp16_step(const pmpd_fp16_stack_t* stack, const void* x_base, float* y_base, void* stream);
+
 /* ---- measurement aid ------------------------------------------------------------------- *
  * Streams `bytes` (rounded down to a multiple of 128 MiB; *bytes_read says how many) of device memory
  * at src (16-byte aligned) through a read-only kernel: the HBM rate a plain read reaches on this

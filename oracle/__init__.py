@@ -192,6 +192,15 @@ def linear_packed(planes, sa, b: int, out_f: int, in_f: int, x, row0: int = 0,
     return y, t
 
 
+def linear_fp16(W, x):
+    """The fp16 baseline the paper measures its speedups against (Section 5.2, Table 3): y = W x for
+    unquantised fp16 W [out, in] and fp16 x [in] or [m, in], every product and sum in fp64.
+    Returns (Y [m, out], T [m, out] = sum |W||x|)."""
+    W64 = np.asarray(W, dtype=np.float16).astype(np.float64)
+    X64 = np.asarray(x, dtype=np.float16).astype(np.float64).reshape(-1, W64.shape[1])
+    return X64 @ W64.T, np.abs(X64) @ np.abs(W64).T
+
+
 # ---------------------------------------------------------------- schedule ----
 def _i32(seq) -> np.ndarray:
     return np.ascontiguousarray(np.asarray(seq, dtype=np.int32))

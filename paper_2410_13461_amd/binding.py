@@ -22,6 +22,8 @@ EXPORTS = (
     "pmpd_schedule_grid", "pmpd_schedule_count", "pmpd_schedule_search", "pmpd_read_stream",
     "pmpd_ordered_workspace_size", "pmpd_ordered_create", "pmpd_ordered_destroy", "pmpd_ordered_step",
     "pmpd_ordered_status", "pmpd_ordered_set_spin_limit",
+    "pmpd_fp16_gemv", "pmpd_fp16_stack_workspace_size", "pmpd_fp16_stack_create", "pmpd_fp16_stack_destroy",
+    "pmpd_fp16_step",
 )
 
 QUALITY_FN = ctypes.CFUNCTYPE(ctypes.c_double, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32),
@@ -47,6 +49,10 @@ class _Layer(ctypes.Structure):
 
 class _Chain(ctypes.Structure):
     _fields_ = [("stage", ctypes.c_int32), ("source", ctypes.c_int32), ("gain", ctypes.c_float)]
+
+
+class _Fp16Layer(ctypes.Structure):
+    _fields_ = [("out_features", ctypes.c_int32), ("in_features", ctypes.c_int32), ("weight", ctypes.c_void_p)]
 
 
 _lib = None
@@ -121,6 +127,16 @@ def _load():
     L.pmpd_ordered_set_spin_limit.argtypes = [vp, ctypes.c_uint32]
     L.pmpd_read_stream.restype = i32
     L.pmpd_read_stream.argtypes = [vp, sz, vp, P(sz), vp]
+    L.pmpd_fp16_gemv.restype = i32
+    L.pmpd_fp16_gemv.argtypes = [vp, i32, i32, vp, vp, vp]
+    L.pmpd_fp16_stack_workspace_size.restype = i32
+    L.pmpd_fp16_stack_workspace_size.argtypes = [P(_Fp16Layer), i32, P(sz)]
+    L.pmpd_fp16_stack_create.restype = i32
+    L.pmpd_fp16_stack_create.argtypes = [P(_Fp16Layer), i32, P(i64), P(i64), vp, sz, P(vp)]
+    L.pmpd_fp16_stack_destroy.restype = None
+    L.pmpd_fp16_stack_destroy.argtypes = [vp]
+    L.pmpd_fp16_step.restype = i32
+    L.pmpd_fp16_step.argtypes = [vp, vp, vp, vp]
     L.pmpd_decode_run.restype = i32
     L.pmpd_decode_run.argtypes = [vp, vp, i32, i32, vp, i64, vp, i64, vp]
     _lib = L
@@ -404,6 +420,67 @@ class Ordered:
             self.close()
         except Exception:
             pass
+
+
+# ------------------------------------------------------- fp16 reference ----
+def fp16_gemv(W, x, y=None, stream=None):
+    """y = W x for an unquantised fp16 device matrix W [out, in] (the paper's fp16 baseline kernel)."""
+    import torch
+
+    out_f, in_f = W.shape
+    if y is None:
+        y = torch.empty(out_f, dtype=torch.float32, device=W.device)
+    _check(_load().pmpd_fp16_gemv(_dev_ptr(W), out_f, in_f, _dev_ptr(x), _dev_ptr(y), _stream_handle(stream)))
+    return y
+
+
+class Fp16Stack:
+    """A list of fp16 device matrices prepared for one-launch steps (tables live in a tensor owned here)."""
+
+    def __init__(self, weights, x_offsets: Optional[Sequence[int]] = None, y_offsets: Optional[Sequence[int]] = None):
+        import torch
+
+        self.weights = list(weights)
+        n = len(self.weights)
+        arr = (_Fp16Layer * n)(*[_Fp16Layer(int(w.shape[0]), int(w.shape[1]), _dev_ptr(w)) for w in self.weights])
+        if x_offsets is None or y_offsets is None:
+            x_offsets, y_offsets, xo, yo = [], [], 0, 0
+            for w in self.weights:
+                x_offsets.append(xo)
+                y_offsets.append(yo)
+                xo += int(w.shape[1])
+                yo += int(w.shape[0])
+        self.x_offsets, self.y_offsets = list(x_offsets), list(y_offsets)
+        self.x_elems = max(o + int(w.shape[1]) for o, w in zip(self.x_offsets, self.weights))
+        self.y_elems = max(o + int(w.shape[0]) for o, w in zip(self.y_offsets, self.weights))
+        need = ctypes.c_size_t()
+        _check(_load().pmpd_fp16_stack_workspace_size(arr, n, ctypes.byref(need)))
+        self.workspace = torch.empty(need.value + 256, dtype=torch.uint8, device=self.weights[0].device)
+        base = (self.workspace.data_ptr() + 255) // 256 * 256
+        xo = (ctypes.c_int64 * n)(*self.x_offsets)
+        yo = (ctypes.c_int64 * n)(*self.y_offsets)
+        h = ctypes.c_void_p()
+        _check(_load().pmpd_fp16_stack_create(arr, n, xo, yo, base, need.value, ctypes.byref(h)))
+        self.handle = h
+
+    def weight_bytes(self) -> int:
+        return sum(2 * int(w.shape[0]) * int(w.shape[1]) for w in self.weights)
+
+    def close(self):
+        if getattr(self, "handle", None):
+            _load().pmpd_fp16_stack_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def fp16_step(stack: Fp16Stack, x, y, stream=None):
+    _check(_load().pmpd_fp16_step(stack.handle, _dev_ptr(x), _dev_ptr(y), _stream_handle(stream)))
+    return y
 
 
 def read_stream(buf, sink, stream=None) -> int:

@@ -15,6 +15,8 @@ Draw order (fixed, so a seed names one data set):
       -> q4  = integers(0, 16, (out, in), uint8)
       -> s   = uniform(1e-3, 1e-2, (out, in/128)) in fp64, rounded to fp16
       -> a   = -8 * s (computed on the fp16 values; exact, a power of two)
+  unquantised fp16 weights of (seed, layer, proj): PCG64(SeedSequence([seed, layer, proj, 2]))
+      -> W   = 0.02 * standard_normal((out, in)) in fp64, rounded to fp16 (the fp16 baseline's operand)
   activations of (seed, step, layer, proj): PCG64(SeedSequence([seed + step, layer, proj, 1]))
       -> x   = standard_normal((m, in)) in fp64, rounded to fp16
 """
@@ -114,3 +116,8 @@ def draw_weights(seed: int, layer: int, proj: int, out_f: int, in_f: int,
 def draw_x(seed: int, step: int, layer: int, proj: int, in_f: int, m: int = 1) -> np.ndarray:
     """Activations, fp16, shape (m, in)."""
     return _rng(seed + step, layer, proj, 1).standard_normal(size=(m, in_f)).astype(np.float16)
+
+
+def draw_fp16_weights(seed: int, layer: int, proj: int, out_f: int, in_f: int) -> np.ndarray:
+    """Unquantised weights for the fp16 baseline kernel: fp16, shape (out, in), ~ N(0, 0.02^2)."""
+    return (0.02 * _rng(seed, layer, proj, 2).standard_normal(size=(out_f, in_f))).astype(np.float16)

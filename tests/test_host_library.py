@@ -189,3 +189,31 @@ def test_schedule_bits_rejects_negative_step():
         sch.bits(-1)
     with pytest.raises(pmpd.PMPDError):
         sch.avg_bits(0)
+
+
+def test_fp16_reference_argument_validation_needs_no_gpu():
+    L = binding._load()
+    w, x, y = ctypes.c_void_p(0x10000), ctypes.c_void_p(0x30000), ctypes.c_void_p(0x40000)
+    assert L.pmpd_fp16_gemv(None, 64, 128, x, y, None) == -1
+    assert L.pmpd_fp16_gemv(w, 0, 128, x, y, None) == -1
+    assert L.pmpd_fp16_gemv(w, 64, 100, x, y, None) == -1
+    assert L.pmpd_fp16_gemv(w, 64, 32768 + 128, x, y, None) == -1
+    assert L.pmpd_fp16_gemv(ctypes.c_void_p(0x10008), 64, 128, x, y, None) == -2
+    assert L.pmpd_fp16_gemv(w, 64, 128, ctypes.c_void_p(0x30002), y, None) == -2
+    assert L.pmpd_fp16_gemv(w, 64, 128, x, ctypes.c_void_p(0x40001), None) == -2
+    arr = (binding._Fp16Layer * 2)(binding._Fp16Layer(70, 256, 0x10000), binding._Fp16Layer(32, 128, 0x20000))
+    need = ctypes.c_size_t()
+    assert L.pmpd_fp16_stack_workspace_size(arr, 2, ctypes.byref(need)) == 0
+    assert need.value == 256 + 256  # 2 descriptors of 32 bytes, 3 + 1 items of 8 bytes, each table padded to 256
+    assert L.pmpd_fp16_stack_workspace_size(arr, 0, ctypes.byref(need)) == -1
+    assert L.pmpd_fp16_stack_workspace_size(None, 2, ctypes.byref(need)) == -1
+    bad = (binding._Fp16Layer * 1)(binding._Fp16Layer(70, 256, 0x10004))
+    assert L.pmpd_fp16_stack_workspace_size(bad, 1, ctypes.byref(need)) == -2
+    xo, yo = (ctypes.c_int64 * 2)(0, 256), (ctypes.c_int64 * 2)(0, 70)
+    h = ctypes.c_void_p()
+    assert L.pmpd_fp16_stack_create(arr, 2, xo, yo, None, 4096, ctypes.byref(h)) == -1
+    assert L.pmpd_fp16_stack_create(arr, 2, xo, yo, ctypes.c_void_p(0x50010), 4096, ctypes.byref(h)) == -2
+    assert L.pmpd_fp16_stack_create(arr, 2, (ctypes.c_int64 * 2)(0, 100), yo, ctypes.c_void_p(0x50000), 4096, ctypes.byref(h)) == -2
+    assert L.pmpd_fp16_stack_create(arr, 2, xo, yo, ctypes.c_void_p(0x50000), 16, ctypes.byref(h)) == -5
+    assert L.pmpd_fp16_step(None, x, y, None) == -1
+    assert L.pmpd_fp16_step(ctypes.c_void_p(0x1234), ctypes.c_void_p(0x30008), y, None) == -2

@@ -367,3 +367,25 @@ def test_schedule_weighted_latency_reproduces_table3():
         row = g[(gpu, proj)]
         base = row["fp16"] / oracle.schedule_weighted_latency(row["w3"], row["w2"], 1.0)
         assert abs(base - g[("speedup", gpu, "baseline_h")][col]) < 0.015
+
+
+def test_fp16_baseline_definition_against_exact_rationals():
+    """linear_fp16 against exact rational arithmetic on a tiny case, and a closed form: rows of constants."""
+    from fractions import Fraction
+
+    W = synth.draw_fp16_weights(1, 0, 0, 5, 128)
+    x = synth.draw_x(1, 0, 0, 0, 128)[0]
+    y, t = oracle.linear_fp16(W, x)
+    for r in range(5):
+        exact = sum(Fraction(float(W[r, i])) * Fraction(float(x[i])) for i in range(128))
+        budget = sum(abs(Fraction(float(W[r, i])) * Fraction(float(x[i]))) for i in range(128))
+        assert abs(Fraction(float(y[0, r])) - exact) <= Fraction(1, 2 ** 45) * budget
+        assert abs(Fraction(float(t[0, r])) - budget) <= Fraction(1, 2 ** 45) * budget
+    Wc = np.repeat(np.arange(1, 4, dtype=np.float16)[:, None], 256, axis=1)  # row r holds r + 1
+    y, t = oracle.linear_fp16(Wc, np.ones(256, dtype=np.float16))
+    assert np.array_equal(y[0], [256.0, 512.0, 768.0]) and np.array_equal(t, y)
+    # transposition mistake would show here: a non-square W with distinct rows and columns
+    Wn = np.arange(6, dtype=np.float16).reshape(2, 3).repeat(128, axis=1)[:, :384]
+    xn = np.concatenate([np.full(128, v, dtype=np.float16) for v in (1, 0, -1)])
+    y, _ = oracle.linear_fp16(Wn, xn)
+    assert np.array_equal(y[0], [128.0 * (0 - 2), 128.0 * (3 - 5)])

@@ -272,3 +272,31 @@ def schedule_search_brute_force(precisions, OL: int, N: int, quality, q_ref: flo
     if best is None:
         return None
     return list(best[1]), best[2], count
+
+
+# ------------------------------------------- learned scheduler (Section 4.3, Appendix A.2) ----
+def learned_scheduler(q, K, V, W1, b1, W2, b2):
+    """Forward pass of the learned scheduler in fp64, step by step as the appendix states it:
+        scores_t = (q . K_t) / sqrt(D_k)            K: [T, D_k] key cache of the chosen block
+        p        = softmax over the T prompt tokens
+        O        = sum_t p_t V_t                     V: [T, D_v] value cache
+        hid      = relu(W1 O + b1)                   one hidden layer
+        probs    = softmax(W2 hid + b2)              one class per candidate switch point
+    Returns (O [D_v], probs [N], class) with class = the first index of the largest probability."""
+    q = np.asarray(q, dtype=np.float64)
+    K = np.asarray(K).astype(np.float64)
+    V = np.asarray(V).astype(np.float64)
+    T, Dk = K.shape
+    scores = np.empty(T)
+    for t in range(T):
+        scores[t] = np.dot(q, K[t]) / np.sqrt(float(Dk))
+    e = np.exp(scores - scores.max())
+    p = e / e.sum()
+    O = np.zeros(V.shape[1])
+    for t in range(T):
+        O += p[t] * V[t]
+    hid = np.maximum(np.asarray(W1, dtype=np.float64) @ O + np.asarray(b1, dtype=np.float64), 0.0)
+    z = np.asarray(W2, dtype=np.float64) @ hid + np.asarray(b2, dtype=np.float64)
+    ez = np.exp(z - z.max())
+    probs = ez / ez.sum()
+    return O, probs, int(np.argmax(probs))

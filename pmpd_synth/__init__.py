@@ -19,6 +19,13 @@ Draw order (fixed, so a seed names one data set):
       -> W   = 0.02 * standard_normal((out, in)) in fp64, rounded to fp16 (the fp16 baseline's operand)
   activations of (seed, step, layer, proj): PCG64(SeedSequence([seed + step, layer, proj, 1]))
       -> x   = standard_normal((m, in)) in fp64, rounded to fp16
+
+Learned-scheduler inputs of (seed): PCG64(SeedSequence([seed, 0, 0, 3])), in this order
+      -> K   = standard_normal((T, D_k)), V = standard_normal((T, D_v)), both rounded to fp16
+      -> q   = standard_normal(D_k) * sharpness      (fp32)
+      -> W1  = standard_normal((H, D_v)) / sqrt(D_v), b1 = 0.1 * standard_normal(H)
+      -> W2  = standard_normal((N, H)) * 4 / sqrt(H), b2 = 0.1 * standard_normal(N)   (all fp32)
+  (random parameters stand in for the trained ones, which are not public.)
 """
 from __future__ import annotations
 
@@ -121,3 +128,16 @@ def draw_x(seed: int, step: int, layer: int, proj: int, in_f: int, m: int = 1) -
 def draw_fp16_weights(seed: int, layer: int, proj: int, out_f: int, in_f: int) -> np.ndarray:
     """Unquantised weights for the fp16 baseline kernel: fp16, shape (out, in), ~ N(0, 0.02^2)."""
     return (0.02 * _rng(seed, layer, proj, 2).standard_normal(size=(out_f, in_f))).astype(np.float16)
+
+
+def draw_learned_scheduler(seed: int, T: int, d_k: int, d_v: int, hidden: int, n_classes: int, sharpness: float = 1.0):
+    """(K fp16 [T,d_k], V fp16 [T,d_v], q fp32 [d_k], W1 fp32 [hidden,d_v], b1, W2 fp32 [n_classes,hidden], b2)."""
+    g = _rng(seed, 0, 0, 3)
+    K = g.standard_normal(size=(T, d_k)).astype(np.float16)
+    V = g.standard_normal(size=(T, d_v)).astype(np.float16)
+    q = (g.standard_normal(size=d_k) * sharpness).astype(np.float32)
+    W1 = (g.standard_normal(size=(hidden, d_v)) / np.sqrt(d_v)).astype(np.float32)
+    b1 = (0.1 * g.standard_normal(size=hidden)).astype(np.float32)
+    W2 = (g.standard_normal(size=(n_classes, hidden)) * 4.0 / np.sqrt(hidden)).astype(np.float32)
+    b2 = (0.1 * g.standard_normal(size=n_classes)).astype(np.float32)
+    return K, V, q, W1, b1, W2, b2

@@ -327,6 +327,44 @@ def secondary_workload(args) -> int:
                                 "frac_of_2500_TFLOPs": flops / (ms_pre * 1e-3) / 1e12 / 2500.0},
                     "decode": {"ms": ms_dec, "avg_bits": sch.avg_bits(n_steps), "GBps": dec_bytes / (ms_dec * 1e-3) / 1e9,
                                "us_per_token": ms_dec * 1e3 / n_steps}})
+    elif args.workload == "learned":
+        # learned scheduler, once per prompt: key / value cache of one block of a 7B-shaped model (32 heads x 128),
+        # hidden layer of 256 units, 5 candidate switch points; random parameters (trained ones are not public)
+        d, hidden, n_cls = 4096, 256, 5
+        res = {}
+        for T in (128, 512, 2048, 8192):
+            Kh, Vh, q, W1, b1, W2, b2 = synth.draw_learned_scheduler(args.seed, T, d, d, hidden, n_cls)
+            net = pmpd.LearnedScheduler(q, W1, b1, W2, b2)
+            cache_bytes = 2 * T * (d + d)
+            copies = max(2, min(64, (640 << 20) // cache_bytes))  # rotate over more than the 256 MiB last-level cache
+            Ks = [torch.from_numpy(Kh).cuda() for _ in range(copies)]
+            Vs = [torch.from_numpy(Vh).cuda() for _ in range(copies)]
+            probs = torch.empty(n_cls, dtype=torch.float32, device="cuda")
+            cls = torch.empty(1, dtype=torch.int32, device="cuda")
+            ctx = torch.empty(d, dtype=torch.float32, device="cuda")
+            state = {"i": 0}
+
+            def call():
+                i = state["i"] = (state["i"] + 1) % copies
+                net.forward(Ks[i], Vs[i], probs, cls, ctx)
+
+            _ramp(call, 0.3)
+            ms = _timed(call, max(K, copies))
+            warm = lambda: net.forward(Ks[0], Vs[0], probs, cls, ctx)
+            ms_warm = _timed(warm, K)
+            import oracle  # bench-side check of the last result against the CPU definition
+            O_ref, p_ref, c_ref = oracle.learned_scheduler(q, Kh, Vh, W1, b1, W2, b2)
+            torch.cuda.synchronize()
+            ok = bool(np.max(np.abs(probs.cpu().numpy() - p_ref)) <= 1e-4 and int(cls.item()) == int(np.argmax(probs.cpu().numpy())))
+            res[f"T{T}"] = {"us_per_call_cold_cache": ms * 1e3, "us_per_call_warm_cache": ms_warm * 1e3,
+                            "cache_bytes": cache_bytes, "GBps_cold": cache_bytes / (ms * 1e-3) / 1e9,
+                            "matches_oracle": ok}
+            del Ks, Vs
+        out.update({"metric": "learned scheduler forward pass, us per prompt (K/V cache of one 7B-shaped block, fp16)",
+                    "unit": "us/prompt", "value": res["T512"]["us_per_call_cold_cache"], "higher_is_better": False,
+                    "config": {"workload": f"d_k = d_v = {d}, hidden {hidden}, {n_cls} classes, T = 128/512/2048/8192; "
+                                           "five kernels per call, back-to-back calls on rotating cache copies"},
+                    "results": res})
     else:
         print(f"unknown workload {args.workload}", file=sys.stderr)
         return 2
@@ -342,7 +380,7 @@ def main() -> int:
     ap.add_argument("--blocks", type=int, default=None, help="debug: fewer blocks (result is then not the named workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--workload", default="7b", choices=["7b", "schedule", "alternate", "ordered", "single", "mobile", "13b"],
+    ap.add_argument("--workload", default="7b", choices=["7b", "schedule", "alternate", "ordered", "single", "mobile", "13b", "learned"],
                     help="7b (default) is the benchmark line; the others print a line for the secondary workloads")
     args = ap.parse_args()
     if args.gpus != 1:

@@ -214,6 +214,33 @@ int32_t pmpd_ordered_status(const pmpd_ordered_t* ordered, int32_t* timed_out);
 /* Polls per wait before it gives up (default 2^20, some seconds). */
 int32_t pmpd_ordered_set_spin_limit(pmpd_ordered_t* ordered, uint32_t polls);
 
+/* ---- learned scheduler: forward pass (Section 4.3 "Task-Agnostic Learned Scheduler"; Appendix A.2) *
+ * Run once per prompt between prefill and decoding (Algorithm 1, deployment stage):
+ *     p = softmax_t(q . K_t / sqrt(d_k)),  O = sum_t p_t V_t,
+ *     probs = softmax(W2 relu(W1 O + b1) + b2),  class = first index of the largest probability;
+ * class c stands for candidate switch point c of the grid of pmpd_schedule_grid with n_classes points.
+ * K: device fp16 [T][d_k], V: device fp16 [T][d_v] (the key / value cache of one attention block, heads
+ * side by side), both 16-byte aligned; d_k, d_v multiples of 8, d_k <= 16384, d_v <= 65536; 1 <= T <= 2^22;
+ * hidden <= 65536; 2 <= n_classes <= 1024.  Parameters: device fp32, row-major, w1 16-byte aligned.
+ * Outputs (device): probs fp32 [n_classes], cls int32 [1], context = O fp32 [d_v] or NULL.  All arithmetic
+ * in fp32 with fixed reduction orders.  workspace: device, 256-byte aligned, pmpd_learned_workspace_size
+ * bytes, free for reuse once the call's work on the stream has finished.  Asynchronous like the rest. */
+typedef struct pmpd_learned {
+  int32_t d_k, d_v, hidden, n_classes;
+  const float* query; /* [d_k] */
+  const float* w1;    /* [hidden][d_v] */
+  const float* b1;    /* [hidden] */
+  const float* w2;    /* [n_classes][hidden] */
+  const float* b2;    /* [n_classes] */
+} pmpd_learned_t;
+int32_t pmpd_learned_workspace_size(const pmpd_learned_t* net, int32_t T, size_t* bytes);
+int32_t pmpd_learned_forward(const pmpd_learned_t* net, const void* K, const void* V, int32_t T, void* workspace,
+                             size_t workspace_bytes, float* context, float* probs, int32_t* cls, void* stream);
+/* Two-precision schedule from a predicted class: `high` bits for steps 0 .. points[cls]-1 and `low` bits
+ * from step points[cls] on, points = pmpd_schedule_grid(max_steps, n_points) (host only). */
+int32_t pmpd_schedule_from_class(int32_t high, int32_t low, int32_t cls, int32_t max_steps, int32_t n_points,
+                                 pmpd_schedule_t** out);
+
 /* ---- unquantised fp16 reference --------------------------------------------------------- *
  * The paper states its linear-layer speedups relative to fp16 kernels on the same device
  * (Section 5.2 "GPU Evaluation", Table 3).  These calls are that reference on this device:

@@ -8,5 +8,5 @@ binding without the built library raises.
 """
 from .binding import (  # noqa: F401
     PMPDError, PackedLayer, Schedule, Stack, batch_step, decode_run, decode_step, gemm, gemv, lib_path, pack,
-    packed_size, prefill_step, unpack, upload_layer, exported_symbols, schedule_grid, schedule_count, schedule_search, read_stream, Ordered, Fp16Stack, fp16_gemv, fp16_step,
+    packed_size, prefill_step, unpack, upload_layer, exported_symbols, schedule_grid, schedule_count, schedule_search, read_stream, Ordered, Fp16Stack, fp16_gemv, fp16_step, LearnedScheduler, schedule_from_class,
 )

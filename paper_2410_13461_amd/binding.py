@@ -23,7 +23,7 @@ EXPORTS = (
     "pmpd_ordered_workspace_size", "pmpd_ordered_create", "pmpd_ordered_destroy", "pmpd_ordered_step",
     "pmpd_ordered_status", "pmpd_ordered_set_spin_limit",
     "pmpd_fp16_gemv", "pmpd_fp16_stack_workspace_size", "pmpd_fp16_stack_create", "pmpd_fp16_stack_destroy",
-    "pmpd_fp16_step",
+    "pmpd_fp16_step", "pmpd_learned_workspace_size", "pmpd_learned_forward", "pmpd_schedule_from_class",
 )
 
 QUALITY_FN = ctypes.CFUNCTYPE(ctypes.c_double, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32),
@@ -53,6 +53,12 @@ class _Chain(ctypes.Structure):
 
 class _Fp16Layer(ctypes.Structure):
     _fields_ = [("out_features", ctypes.c_int32), ("in_features", ctypes.c_int32), ("weight", ctypes.c_void_p)]
+
+
+class _Learned(ctypes.Structure):
+    _fields_ = [("d_k", ctypes.c_int32), ("d_v", ctypes.c_int32), ("hidden", ctypes.c_int32),
+                ("n_classes", ctypes.c_int32), ("query", ctypes.c_void_p), ("w1", ctypes.c_void_p),
+                ("b1", ctypes.c_void_p), ("w2", ctypes.c_void_p), ("b2", ctypes.c_void_p)]
 
 
 _lib = None
@@ -137,6 +143,12 @@ def _load():
     L.pmpd_fp16_stack_destroy.argtypes = [vp]
     L.pmpd_fp16_step.restype = i32
     L.pmpd_fp16_step.argtypes = [vp, vp, vp, vp]
+    L.pmpd_learned_workspace_size.restype = i32
+    L.pmpd_learned_workspace_size.argtypes = [P(_Learned), i32, P(sz)]
+    L.pmpd_learned_forward.restype = i32
+    L.pmpd_learned_forward.argtypes = [P(_Learned), vp, vp, i32, vp, sz, vp, vp, vp, vp]
+    L.pmpd_schedule_from_class.restype = i32
+    L.pmpd_schedule_from_class.argtypes = [i32, i32, i32, i32, i32, P(vp)]
     L.pmpd_decode_run.restype = i32
     L.pmpd_decode_run.argtypes = [vp, vp, i32, i32, vp, i64, vp, i64, vp]
     _lib = L
@@ -420,6 +432,63 @@ class Ordered:
             self.close()
         except Exception:
             pass
+
+
+# ----------------------------------------------------- learned scheduler ----
+class LearnedScheduler:
+    """Parameters of the learned scheduler resident on the device (fp32 tensors owned here)."""
+
+    def __init__(self, query, w1, b1, w2, b2, device="cuda"):
+        import torch
+
+        def dev(a):
+            return torch.as_tensor(np.ascontiguousarray(a, dtype=np.float32)).to(device).contiguous()
+
+        self.query, self.w1, self.b1, self.w2, self.b2 = dev(query), dev(w1), dev(b1), dev(w2), dev(b2)
+        self.hidden, self.d_v = self.w1.shape
+        self.n_classes = self.w2.shape[0]
+        self.d_k = self.query.shape[0]
+        if self.w2.shape[1] != self.hidden or self.b1.shape[0] != self.hidden or self.b2.shape[0] != self.n_classes:
+            raise PMPDError(-1, "learned scheduler: parameter shapes do not fit together")
+        self._struct = _Learned(self.d_k, self.d_v, self.hidden, self.n_classes, self.query.data_ptr(),
+                                self.w1.data_ptr(), self.b1.data_ptr(), self.w2.data_ptr(), self.b2.data_ptr())
+        self._ws = None
+
+    def workspace_size(self, T: int) -> int:
+        need = ctypes.c_size_t()
+        _check(_load().pmpd_learned_workspace_size(ctypes.byref(self._struct), T, ctypes.byref(need)))
+        return need.value
+
+    def forward(self, K, V, probs=None, cls=None, context=None, stream=None):
+        """K [T, d_k], V [T, d_v]: fp16 device tensors.  Returns (probs, cls, context) device tensors; asynchronous."""
+        import torch
+
+        T = int(K.shape[0])
+        if K.shape[1] != self.d_k or V.shape[0] != T or V.shape[1] != self.d_v:
+            raise PMPDError(-1, "learned scheduler: K / V shapes do not fit the parameters")
+        need = self.workspace_size(T)
+        if self._ws is None or self._ws.numel() < need + 256:
+            self._ws = torch.empty(need + 256, dtype=torch.uint8, device=K.device)
+        base = (self._ws.data_ptr() + 255) // 256 * 256
+        if probs is None:
+            probs = torch.empty(self.n_classes, dtype=torch.float32, device=K.device)
+        if cls is None:
+            cls = torch.empty(1, dtype=torch.int32, device=K.device)
+        if context is None:
+            context = torch.empty(self.d_v, dtype=torch.float32, device=K.device)
+        _check(_load().pmpd_learned_forward(ctypes.byref(self._struct), _dev_ptr(K), _dev_ptr(V), T, base, need,
+                                            _dev_ptr(context), _dev_ptr(probs), _dev_ptr(cls), _stream_handle(stream)))
+        return probs, cls, context
+
+
+def schedule_from_class(high: int, low: int, cls: int, max_steps: int, n_points: int) -> "Schedule":
+    """The two-precision schedule that switches at candidate point `cls` of the n_points grid."""
+    h = ctypes.c_void_p()
+    _check(_load().pmpd_schedule_from_class(high, low, cls, max_steps, n_points, ctypes.byref(h)))
+    sch = Schedule.__new__(Schedule)
+    sch._h = h
+    sch.max_steps = max_steps
+    return sch
 
 
 # ------------------------------------------------------- fp16 reference ----

@@ -217,3 +217,47 @@ def test_fp16_reference_argument_validation_needs_no_gpu():
     assert L.pmpd_fp16_stack_create(arr, 2, xo, yo, ctypes.c_void_p(0x50000), 16, ctypes.byref(h)) == -5
     assert L.pmpd_fp16_step(None, x, y, None) == -1
     assert L.pmpd_fp16_step(ctypes.c_void_p(0x1234), ctypes.c_void_p(0x30008), y, None) == -2
+
+
+def test_learned_scheduler_argument_validation_needs_no_gpu():
+    L = binding._load()
+
+    def net(d_k=64, d_v=128, hidden=16, n=5, q=0x1000, w1=0x2000, b1=0x3000, w2=0x4000, b2=0x5000):
+        return binding._Learned(d_k, d_v, hidden, n, q, w1, b1, w2, b2)
+
+    need = ctypes.c_size_t()
+    assert L.pmpd_learned_workspace_size(ctypes.byref(net()), 100, ctypes.byref(need)) == 0
+    # scores 100 floats -> 512, partial 13 chunks x 128 floats = 6656, O 512, hidden 256
+    assert need.value == 512 + 6656 + 512 + 256
+    for bad in (net(d_k=60), net(d_k=0), net(d_k=16392), net(d_v=12), net(hidden=0), net(n=1), net(n=1025)):
+        assert L.pmpd_learned_workspace_size(ctypes.byref(bad), 100, ctypes.byref(need)) == -1
+    assert L.pmpd_learned_workspace_size(ctypes.byref(net()), 0, ctypes.byref(need)) == -1
+    assert L.pmpd_learned_workspace_size(None, 10, ctypes.byref(need)) == -1
+    K, V, ws = ctypes.c_void_p(0x10000), ctypes.c_void_p(0x20000), ctypes.c_void_p(0x30000)
+    pr, cl = ctypes.c_void_p(0x40000), ctypes.c_void_p(0x50000)
+
+    def fwd(n=None, k=K, v=V, w=ws, wb=1 << 20, p=pr, c=cl):
+        return L.pmpd_learned_forward(ctypes.byref(n or net()), k, v, 100, w, wb, None, p, c, None)
+
+    assert fwd(net(q=None)) == -1
+    assert fwd(net(w1=0x2004)) == -2
+    assert fwd(k=None) == -1
+    assert fwd(v=ctypes.c_void_p(0x20008)) == -2
+    assert fwd(w=ctypes.c_void_p(0x30010)) == -2
+    assert fwd(wb=1000) == -5
+    assert fwd(p=None) == -1
+    assert fwd(c=ctypes.c_void_p(0x50002)) == -2
+    h = ctypes.c_void_p()
+    assert L.pmpd_schedule_from_class(3, 2, 5, 64, 5, ctypes.byref(h)) == -1   # class outside 0..4
+    assert L.pmpd_schedule_from_class(3, 2, -1, 64, 5, ctypes.byref(h)) == -1
+    assert L.pmpd_schedule_from_class(2, 3, 1, 64, 5, ctypes.byref(h)) == -1   # precisions must decrease
+    assert L.pmpd_schedule_from_class(3, 2, 1, 64, 5, None) == -1
+    for cls, point in enumerate((0, 16, 32, 48, 64)):
+        assert L.pmpd_schedule_from_class(4, 2, cls, 64, 5, ctypes.byref(h)) == 0
+        b = ctypes.c_int32()
+        got = []
+        for k in range(64):
+            assert L.pmpd_schedule_bits(h, k, ctypes.byref(b)) == 0
+            got.append(b.value)
+        assert got == [4] * point + [2] * (64 - point)
+        L.pmpd_schedule_destroy(h)

@@ -64,6 +64,7 @@ extern "C" {
 #define PMPD_GROUP 128     /* input features per quantisation group */
 #define PMPD_ROW_TILE 64   /* rows per storage tile (one per lane of a wave) */
 #define PMPD_MAX_BATCH 8   /* rows of X up to which pmpd_gemm takes its skinny path */
+#define PMPD_MAX_STACK_BATCH 16 /* rows of X up to which pmpd_batch_step takes its skinny path */
 #define PMPD_MAX_ROWS 65536 /* rows of X accepted by pmpd_gemm / pmpd_prefill_step */
 
 /* One packed linear layer.  Plain data; the pointers are the caller's (device memory for
@@ -134,8 +135,11 @@ int32_t pmpd_decode_step(const pmpd_stack_t* stack, int32_t b, const void* x_bas
 /* m tokens through every layer of the stack in one launch:
  *     Y_l[j][r] = sum_i W_b,l[r][i] X_l[j][i],  j < m,  for every layer l,
  * X_l = x_base + m*x_offset[l] (fp16 row-major [m][in_l]), Y_l = y_base + m*y_offset[l] (fp32
- * row-major [m][out_l]).  m == 1 is pmpd_decode_step; 2 <= m <= PMPD_MAX_BATCH reads and unpacks the
- * weights once for all m vectors (skinny batches; the paper itself stays at batch 1, Section 5.2);
+ * row-major [m][out_l]).  m == 1 is pmpd_decode_step; 2 <= m <= PMPD_MAX_STACK_BATCH reads and unpacks
+ * the weights once for all m vectors (skinny batches; the paper itself stays at batch 1, Section 5.2):
+ * from 3 vectors on the activations enter the int8 matrix cores as three base-256 digits of a 23-bit
+ * fixed-point number per group of 128 (values within 2^-11 of the group's largest are exact, smaller ones
+ * are rounded at 2^-23 of it), the codes exactly, with int32 sums;
  * larger m is the compute-bound prefill shape on the matrix cores (Algorithm 1 line 10, Section 4.1).
  * pmpd_prefill_step is the same call under the paper's name for that phase. */
 int32_t pmpd_batch_step(const pmpd_stack_t* stack, int32_t b, const void* x_base, int32_t m, float* y_base,

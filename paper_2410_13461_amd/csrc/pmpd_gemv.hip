@@ -724,6 +724,9 @@ static hipError_t launch_layer_b(const LayerDesc& d, const void* x, int m, float
 // defined in pmpd_prefill.hip
 hipError_t launch_prefill_layer(const LayerDesc& d, int b, const void* X, int m, float* Y, hipStream_t s);
 hipError_t launch_prefill_stack(const pmpd_stack* st, int b, const void* X, int m, float* Y, hipStream_t s);
+// defined in pmpd_skinny.hip
+hipError_t launch_skinny_stack(const pmpd_stack* st, int b, const void* X, int m, float* Y, hipStream_t s);
+constexpr int kSkinnyMinBatch = 3, kSkinnyMaxBatch = PMPD_MAX_STACK_BATCH;  // batches the int8 kernel takes over a stack
 
 static int32_t linear_entry(const char* who, const pmpd_layer_t* layer, int32_t b, const void* x, int32_t m, int32_t max_m,
                             float* y, void* stream) {
@@ -1202,6 +1205,8 @@ int32_t pmpd_batch_step(const pmpd_stack_t* stack, int32_t b, const void* x_base
   hipError_t e;
   if (m == 1) {
     return pmpd_decode_step(stack, b, x_base, y_base, stream);
+  } else if (m >= kSkinnyMinBatch && m <= kSkinnyMaxBatch) {
+    e = launch_skinny_stack(stack, b, x_base, m, y_base, s);
   } else if (m <= PMPD_MAX_BATCH) {
     e = b == 4 ? launch_stack_batch<4>(stack, x_base, m, y_base, s)
         : b == 3 ? launch_stack_batch<3>(stack, x_base, m, y_base, s)

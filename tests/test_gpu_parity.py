@@ -209,7 +209,7 @@ def test_prefill_step_over_stack_matches_oracle(pmpd, b):
 
 
 @pytest.mark.parametrize("b", [4, 3, 2])
-@pytest.mark.parametrize("m", [1, 2, 4, 5, 8])
+@pytest.mark.parametrize("m", [1, 2, 3, 4, 5, 8, 9, 12, 13, 16])
 def test_batch_step_over_stack_matches_oracle(pmpd, b, m):
     import torch
 
@@ -226,6 +226,47 @@ def test_batch_step_over_stack_matches_oracle(pmpd, b, m):
         o = m * stack.y_offsets[li]
         y_ref, t = oracle.linear(q4, s, a, b, Xs[li])
         assert_parity(Y[o:o + m * q4.shape[0]].reshape(m, q4.shape[0]), y_ref, t, f"batch_step layer {li} m={m} b={b}")
+    stack.close()
+
+
+@pytest.mark.parametrize("b", [4, 3, 2])
+@pytest.mark.parametrize("m", [3, 7, 16])
+def test_batch_step_long_rows_and_adversarial_vectors(pmpd, b, m):
+    """Rows long enough for several K-chunks of the batch kernel's activation image (86 and 33 groups, ragged
+    row counts), and one vector of each awkward kind among ordinary ones: a huge entry among small ones, tiny
+    values, subnormals, zeros, ones, a single sign, a one-hot vector."""
+    import torch
+
+    _say(f"[batch_step long/adversarial] b={b} m={m}")
+    shapes = [(130, 11008), (70, 4224), (64, 128)]
+    raw = [synth.draw_weights(31, k, 0, o, i, random_min=(k == 1)) for k, (o, i) in enumerate(shapes)]
+    layers = [_device_layer(pmpd, *w) for w in raw]
+    stack = pmpd.Stack(layers)
+    Xs = []
+    for k, (o, i) in enumerate(shapes):
+        X = synth.draw_x(31, 0, k, 0, i, m=m).copy()
+        kinds = [
+            lambda v: np.where(np.arange(i) == i // 3, np.float16(30000.0), (v.astype(np.float32) * 0.01).astype(np.float16)),
+            lambda v: (v.astype(np.float32) * 1e-4).astype(np.float16),
+            lambda v: (v.astype(np.float32) * 3e-7).astype(np.float16),          # fp16 subnormals
+            lambda v: np.zeros(i, dtype=np.float16),
+            lambda v: np.ones(i, dtype=np.float16),
+            lambda v: np.abs(v),
+            lambda v: (np.arange(i) == 5 * i // 7).astype(np.float16),
+        ]
+        for j in range(m):
+            if j % 2 == 1 or m == 3:
+                X[j] = kinds[(j // 2 + k) % len(kinds)](X[j])
+        Xs.append(X)
+    X = torch.from_numpy(np.concatenate([x.reshape(-1) for x in Xs])).cuda()
+    Y = torch.full((m * stack.y_elems,), float("nan"), dtype=torch.float32, device="cuda")
+    pmpd.batch_step(stack, b, X, m, Y)
+    torch.cuda.synchronize()
+    Y = Y.cpu().numpy()
+    for li, (q4, s, a) in enumerate(raw):
+        o = m * stack.y_offsets[li]
+        y_ref, t = oracle.linear(q4, s, a, b, Xs[li])
+        assert_parity(Y[o:o + m * q4.shape[0]].reshape(m, q4.shape[0]), y_ref, t, f"batch_step long layer {li} m={m} b={b}")
     stack.close()
 
 

@@ -261,3 +261,15 @@ def test_learned_scheduler_argument_validation_needs_no_gpu():
             got.append(b.value)
         assert got == [4] * point + [2] * (64 - point)
         L.pmpd_schedule_destroy(h)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py runs on one GPU only: any other --gpus ends with a message and a non-zero status, before
+    anything touches a GPU."""
+    import subprocess
+    import sys
+
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""

@@ -119,24 +119,39 @@ def test_7b_progressive_schedule_256_steps(pmpd, stack7b):
     assert not torch.equal(y_all[65], y_all[1])
 
 
-@pytest.mark.parametrize("m", [1, 2, 4, 8])
+@pytest.mark.parametrize("m", [1, 2, 3, 4, 8, 16])
 def test_mobile_stack_skinny_batches(pmpd, m):
-    """Mobile-scale shapes (hidden 2048, intermediate 5632) at batch 1, 2, 4, 8, every bit-width."""
+    """Mobile-scale shapes (hidden 2048, intermediate 5632) at batch 1, 2, 3, 4, 8, 16, every bit-width."""
     import torch
 
     shape = synth.MOBILE
     _say(f"[full-size mobile] m={m}")
+    raw, layers, Xs = [], [], []
     for pi in (0, 4, 5):  # q (2048x2048), up (5632x2048), down (2048x5632)
         nm, o, i = shape.proj_shapes()[pi]
         q4, s, a = synth.draw_weights(3, 0, pi, o, i)
         planes, sm = pmpd.pack(q4, s, a)
-        layer = pmpd.upload_layer(planes, sm, o, i)
-        X = synth.draw_x(3, 0, 0, pi, i, m=m)
-        rows = _sample_rows(o, 40, seed=pi)
-        for b in (4, 3, 2):
-            Y = pmpd.gemm(layer, b, torch.from_numpy(X).cuda())
-            torch.cuda.synchronize()
-            _check_rows(Y.cpu().numpy()[:, rows], q4, s, a, b, X, rows, f"mobile {nm} m={m} b={b}")
+        raw.append((nm, q4, s, a))
+        layers.append(pmpd.upload_layer(planes, sm, o, i))
+        Xs.append(synth.draw_x(3, 0, 0, pi, i, m=m))
+    stack = pmpd.Stack(layers)  # the call the benchmark times: one launch over the list of layers
+    X = torch.from_numpy(np.concatenate([x.reshape(-1) for x in Xs])).cuda()
+    Y = torch.empty(m * stack.y_elems, dtype=torch.float32, device="cuda")
+    for b in (4, 3, 2):
+        Y.fill_(float("nan"))
+        pmpd.batch_step(stack, b, X, m, Y)
+        torch.cuda.synchronize()
+        Yh = Y.cpu().numpy()
+        for li, (nm, q4, s, a) in enumerate(raw):
+            o = q4.shape[0]
+            rows = _sample_rows(o, 40, seed=li)
+            got = Yh[m * stack.y_offsets[li]:m * stack.y_offsets[li] + m * o].reshape(m, o)
+            _check_rows(got[:, rows], q4, s, a, b, Xs[li], rows, f"mobile {nm} m={m} b={b}")
+            if m <= 8:  # the single-layer entry point takes its own path for these batches
+                G = pmpd.gemm(layers[li], b, torch.from_numpy(Xs[li]).cuda())
+                torch.cuda.synchronize()
+                _check_rows(G.cpu().numpy()[:, rows], q4, s, a, b, Xs[li], rows, f"mobile gemm {nm} m={m} b={b}")
+    stack.close()
 
 
 def test_13b_prefill_then_decode(pmpd):

@@ -25,6 +25,8 @@
  *     owned by the library until *_destroy.
  *   - Device work is enqueued on the caller's HIP stream (passed as void*, NULL = the
  *     default stream) and is asynchronous; there is no hidden synchronisation.
+ *   - Activations must be finite fp16 numbers (subnormals included).  With Inf or NaN among them the
+ *     outputs are unspecified; no call reads or writes out of bounds because of them.
  *   - Arguments are validated on the host before anything is launched, so every error
  *     path can be exercised without a GPU.  There is no CPU fallback: a call that needs
  *     the GPU fails with PMPD_EHIP when none is usable.

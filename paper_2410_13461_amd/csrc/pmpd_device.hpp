@@ -75,4 +75,37 @@ __device__ __forceinline__ void single_words(uint32_t hi, uint32_t (&w)[4]) {
   w[3] = (hi >> 1) & keep;
 }
 
+// Cross-lane moves inside a DPP row of 16 lanes (bound_ctrl: lanes without a source read 0).
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+  return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xF, 0xF, true));
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+  return __builtin_bit_cast(float, dpp_u32<CTRL>(__builtin_bit_cast(uint32_t, v)));
+}
+constexpr int kQuadSwap1 = 0xB1;      // quad_perm [1,0,3,2]
+constexpr int kQuadSwap2 = 0x4E;      // quad_perm [2,3,0,1]
+constexpr int kRowHalfMirror = 0x141;
+constexpr int kRowMirror = 0x140;
+
+// Largest value / sum over the 16 lanes of a DPP row (quad swaps, then the two mirrors): every lane gets it.
+__device__ __forceinline__ uint32_t row16_max(uint32_t v) {
+  uint32_t o = dpp_u32<kQuadSwap1>(v);
+  v = v > o ? v : o;
+  o = dpp_u32<kQuadSwap2>(v);
+  v = v > o ? v : o;
+  o = dpp_u32<kRowHalfMirror>(v);
+  v = v > o ? v : o;
+  o = dpp_u32<kRowMirror>(v);
+  return v > o ? v : o;
+}
+__device__ __forceinline__ float row16_sum(float v) {
+  v += dpp_f32<kQuadSwap1>(v);
+  v += dpp_f32<kQuadSwap2>(v);
+  v += dpp_f32<kRowHalfMirror>(v);
+  v += dpp_f32<kRowMirror>(v);
+  return v;
+}
+
 }  // namespace pmpd

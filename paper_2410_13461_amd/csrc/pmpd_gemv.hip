@@ -108,19 +108,6 @@ struct ImageLayout {
   __device__ __forceinline__ int xsum_off(int j, int cls) const { return (j * 2 + cls) * cg; }
 };
 
-template <int CTRL>
-__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
-  return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xF, 0xF, true));
-}
-template <int CTRL>
-__device__ __forceinline__ float dpp_f32(float v) {
-  return __builtin_bit_cast(float, dpp_u32<CTRL>(__builtin_bit_cast(uint32_t, v)));
-}
-constexpr int kQuadSwap1 = 0xB1;      // quad_perm [1,0,3,2]
-constexpr int kQuadSwap2 = 0x4E;      // quad_perm [2,3,0,1]
-constexpr int kRowHalfMirror = 0x141;
-constexpr int kRowMirror = 0x140;
-
 // Four fp16 -> four e4m3 bytes, each divided by `scale` (a power of two), round to nearest even.
 __device__ __forceinline__ uint32_t to_fp8x4(half2_t lo, half2_t hi, float scale) {
   short2_t r = {0, 0};

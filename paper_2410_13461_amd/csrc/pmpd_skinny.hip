@@ -69,29 +69,6 @@ constexpr int sk_max_units(int sets, int nw) {
   return worst;
 }
 
-template <int CTRL>
-__device__ __forceinline__ uint32_t sk_dpp(uint32_t v) {
-  return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xF, 0xF, true));
-}
-// Reductions over the 16 lanes of a DPP row (quad swaps, then the two mirrors).
-__device__ __forceinline__ uint32_t row16_max(uint32_t v) {
-  uint32_t o = sk_dpp<0xB1>(v);
-  v = v > o ? v : o;
-  o = sk_dpp<0x4E>(v);
-  v = v > o ? v : o;
-  o = sk_dpp<0x141>(v);
-  v = v > o ? v : o;
-  o = sk_dpp<0x140>(v);
-  return v > o ? v : o;
-}
-__device__ __forceinline__ float row16_sum(float v) {
-  v += __builtin_bit_cast(float, sk_dpp<0xB1>(__builtin_bit_cast(uint32_t, v)));
-  v += __builtin_bit_cast(float, sk_dpp<0x4E>(__builtin_bit_cast(uint32_t, v)));
-  v += __builtin_bit_cast(float, sk_dpp<0x141>(__builtin_bit_cast(uint32_t, v)));
-  v += __builtin_bit_cast(float, sk_dpp<0x140>(__builtin_bit_cast(uint32_t, v)));
-  return v;
-}
-
 // Byte k of a, b, c, d as one word (a in the lowest byte).
 template <int K>
 __device__ __forceinline__ uint32_t gather_bytes(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {

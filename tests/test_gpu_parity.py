@@ -352,6 +352,22 @@ def test_decode_run_follows_the_schedule(pmpd):
     pmpd.decode_run(stack, sch, 4, 3, x[4:], stack.x_elems, y2, stack.y_elems)
     torch.cuda.synchronize()
     assert np.array_equal(y2.cpu().numpy(), y[4:7])
+    # an empty run launches nothing and leaves the output alone
+    y3 = torch.full((stack.y_elems,), 3.0, dtype=torch.float32, device="cuda")
+    pmpd.decode_run(stack, sch, 2, 0, x, stack.x_elems, y3, stack.y_elems)
+    torch.cuda.synchronize()
+    assert bool((y3 == 3.0).all())
+    # steps past the schedule's horizon stay at the last precision reached
+    y4 = torch.zeros((2, stack.y_elems), dtype=torch.float32, device="cuda")
+    pmpd.decode_run(stack, sch, n_steps - 1, 2, x[n_steps - 2:], stack.x_elems, y4, stack.y_elems)
+    torch.cuda.synchronize()
+    assert sch.bits(n_steps + 5) == 2
+    y4 = y4.cpu().numpy()
+    for j, krow in enumerate((n_steps - 2, n_steps - 1)):
+        for li, (q4, s, a) in enumerate(raw):
+            xo, yo = stack.x_offsets[li], stack.y_offsets[li]
+            y_ref, t = oracle.linear(q4, s, a, 2, xs[krow, xo:xo + q4.shape[1]])
+            assert_parity(y4[j, yo:yo + q4.shape[0]], y_ref[0], t[0], f"decode_run past the horizon, row {j} layer {li}")
     stack.close()
 
 

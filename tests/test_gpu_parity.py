@@ -395,3 +395,55 @@ def test_read_stream_runs_and_reports_its_bytes(pmpd):
     assert int(sink.item()) == 0
     with pytest.raises(pmpd.PMPDError):
         pmpd.read_stream(buf[: 1024 * 1024], sink)  # too small
+
+
+def test_steps_replay_from_a_captured_graph(pmpd):
+    """A decode step, a batch step and a scheduled run captured in a HIP graph (through torch) replay to the eager
+    result every time, with eager work of the same library between the replays; new activations written into the
+    captured input buffer are picked up."""
+    import torch
+
+    _say("[graph replay]")
+    shape, layers, raw = _small_stack(pmpd, seed=12)
+    stack = pmpd.Stack(layers)
+    m = 5
+    x1 = torch.from_numpy(np.concatenate([synth.draw_x(12, 0, blk, pi, i)[0] for (blk, pi, nm, o, i) in shape.layers()])).cuda()
+    xm = torch.from_numpy(np.concatenate([synth.draw_x(12, 1, blk, pi, i, m=m).reshape(-1) for (blk, pi, nm, o, i) in shape.layers()])).cuda()
+    sch = pmpd.Schedule((4, 2), (0, 1), 2)
+    y1 = torch.zeros(stack.y_elems, dtype=torch.float32, device="cuda")
+    ym = torch.zeros(m * stack.y_elems, dtype=torch.float32, device="cuda")
+    yr = torch.zeros((2, stack.y_elems), dtype=torch.float32, device="cuda")
+
+    def work():
+        pmpd.decode_step(stack, 3, x1, y1)
+        pmpd.batch_step(stack, 4, xm, m, ym)
+        pmpd.decode_run(stack, sch, 0, 2, x1, 0, yr, stack.y_elems)
+
+    def eager_reference():
+        work()
+        torch.cuda.synchronize()
+        return y1.clone(), ym.clone(), yr.clone()
+
+    ref = eager_reference()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        work()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            work()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        if rep == 2:  # new activations in the captured buffers
+            x1.copy_(torch.from_numpy(np.concatenate([synth.draw_x(13, 0, blk, pi, i)[0] for (blk, pi, nm, o, i) in shape.layers()])).cuda())
+            ref = eager_reference()
+        for t in (y1, ym, yr):
+            t.fill_(float("nan"))
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y1, ref[0]) and torch.equal(ym, ref[1]) and torch.equal(yr, ref[2]), f"replay {rep}"
+        # eager work between the replays
+        pmpd.decode_step(stack, 2, x1, y1)
+        torch.cuda.synchronize()
+    stack.close()

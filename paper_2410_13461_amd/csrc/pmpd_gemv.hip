@@ -488,13 +488,14 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd<SETS>()) void pmpd_layer_ke
 // bounded all the same (spin_limit polls), and a wait that runs out only sets sync->timed_out.
 // Counters of the stage barrier.  Workgroup w adds to sub-counter w % 16 of the stage; the last
 // one of each sub-counter adds to the stage's top counter, and the last of those publishes the
-// stage number in `stage_done`, the only word the waiting workgroups poll: the polls (a thousand
-// readers) and the arrivals (a thousand read-modify-writes) never meet on one cache line.
+// stage number in the 32 copies of `stage_done`, the only words the waiting workgroups poll
+// (workgroup w reads copy w % 32): the polls (a thousand readers) and the arrivals (a thousand
+// read-modify-writes) never meet on one cache line, and no line has more than a few dozen readers.
 constexpr int kSyncLine = 64;   // uint32 per 256-byte line
 constexpr int kSubCounters = 16;
+constexpr int kFlagCopies = 32;  // copies of the polled word, one 256-byte line each: 32 times fewer readers per line
 struct OrderedSync {
-  uint32_t stage_done;            // stages completed in this step (monotonic), polled
-  uint32_t pad0[kSyncLine - 1];
+  uint32_t stage_done[kFlagCopies * kSyncLine];  // [copy][0]: stages completed in this step (monotonic), polled
   uint32_t timed_out;
   uint32_t pad1[kSyncLine - 1];
   uint32_t counters[1];  // [n_stages][kSubCounters + 1][kSyncLine / 4] arrival counters, then [tiles] K-parts finished
@@ -538,7 +539,8 @@ __global__ __launch_bounds__(kOrderedWaves * 64, 4) void pmpd_ordered_kernel(
       waited = true;
       if (threadIdx.x == 0) {
         uint32_t polls = 0;
-        while (__hip_atomic_load(&sync->stage_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < static_cast<uint32_t>(s)) {
+        while (__hip_atomic_load(&sync->stage_done[(blockIdx.x % kFlagCopies) * kSyncLine], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) <
+               static_cast<uint32_t>(s)) {
           if (++polls >= spin_limit) {
             __hip_atomic_store(&sync->timed_out, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             break;
@@ -613,7 +615,8 @@ __global__ __launch_bounds__(kOrderedWaves * 64, 4) void pmpd_ordered_kernel(
       if (__hip_atomic_fetch_add(&cnt[k * 16], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1 == in_sub) {
         const uint32_t n_sub = n_wg < kSubCounters ? n_wg : kSubCounters;
         if (__hip_atomic_fetch_add(&cnt[kSubCounters * 16], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1 == n_sub)
-          __hip_atomic_store(&sync->stage_done, static_cast<uint32_t>(s + 1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          for (int q = 0; q < kFlagCopies; ++q)
+            __hip_atomic_store(&sync->stage_done[q * kSyncLine], static_cast<uint32_t>(s + 1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
   }
@@ -621,7 +624,7 @@ __global__ __launch_bounds__(kOrderedWaves * 64, 4) void pmpd_ordered_kernel(
 
 __global__ void pmpd_ordered_reset_kernel(OrderedSync* sync, int n_counters) {
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n_counters; i += gridDim.x * blockDim.x) sync->counters[i] = 0;
-  if (blockIdx.x == 0 && threadIdx.x == 0) sync->stage_done = 0;
+  if (blockIdx.x == 0 && threadIdx.x < kFlagCopies) sync->stage_done[threadIdx.x * kSyncLine] = 0;
 }
 
 // Read-only stream over a buffer: the HBM ceiling the decode kernels are held against.  Each

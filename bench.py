@@ -468,6 +468,7 @@ def main() -> int:
         nbytes = stack.bytes_at(b)
         per_bits[str(b)] = {
             "us_per_token": ms * 1e3,
+            "median_us": float(np.median(per_b_ms[b])) * 1e3,
             "min_us": float(np.min(per_b_ms[b])) * 1e3,
             "algorithmic_bytes": nbytes,
             "GBps": nbytes / (ms * 1e-3) / 1e9,
@@ -518,6 +519,7 @@ def main() -> int:
     del dW, ref
 
     dom = per_bits["4"]
+    props = torch.cuda.get_device_properties(0)
     out = {
         "metric": "decode linear-layer us/token (mean over b=4,3,2; per-bit figures in per_bits), batch 1",
         "value": us_per_token,
@@ -539,6 +541,8 @@ def main() -> int:
             "wall_ms_per_step_incl_host": t_wall * 1e3 / (K * len(bits)),
         },
         "per_bits": per_bits,
+        "device": {"name": props.name, "compute_units": props.multi_processor_count, "hbm_bytes": props.total_memory,
+                   "gcn_arch": getattr(props, "gcnArchName", "")},
         "fp16_reference": fp16_reference,
         "roofline": {
             "bound": "hbm",

@@ -27,9 +27,9 @@
 // with Dk = sum q~ p_k exact in int32 and X_g the fp32 sum of the group's x.  Lane l gets the three
 // sums of vector 4 s + l / 16 and weight row 16 t + l % 16 in registers 0..2 of D.
 //
-// Workgroup = 8 waves, one 64-row tile each over the whole K; the activation image of a K-chunk is
-// built once per workgroup in LDS (up to 72 KiB, two workgroups per CU) while the first weight loads
-// are in flight.  No atomics, fixed summation order.
+// Workgroup = 8 waves (4 for up to four vectors), one 64-row tile each over the whole K; the activation
+// image of a K-chunk is built once per workgroup in LDS (up to 72 KiB with two workgroups per CU, 36 KiB
+// with four) while the first weight loads are in flight.  No atomics, fixed summation order.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -42,8 +42,8 @@ namespace pmpd {
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned short us2 __attribute__((ext_vector_type(2)));
 
-constexpr int kSkKbStride = 272;                   // bytes between the four 16-lane groups of an operand: 256 + 16, so
-                                                   // that the 8-byte writes of a group's 16 staging threads hit 16 banks pairs
+constexpr int kSkKbStride = 272;                   // bytes between the four 16-lane groups of an operand: 256 + 16, so that
+                                                   // the 8-byte writes of a group's 16 staging lanes fall into 16 different bank pairs
 constexpr int kSkHalfStride = 4 * kSkKbStride;     // 1088: from MFMA h = 0 to h = 1
 constexpr int kSkGroupBytes = 2 * kSkHalfStride;   // 2176 per operand set and group
 __host__ __device__ constexpr int sk_budget(int nw) { return nw == 8 ? 72 * 1024 : 36 * 1024; }  // two / four workgroups per CU

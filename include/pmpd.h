@@ -199,8 +199,13 @@ int32_t pmpd_decode_run(const pmpd_stack_t* stack, const pmpd_schedule_t* schedu
  * fp16(gain * y_k), the output of layer k of an earlier stage (out_features(k) == in_features(l),
  * y_offset[k] a multiple of 4); gain stands for the elementwise glue between the layers, which is
  * not part of this library.  Every layer still writes its full fp32 output at y_base + y_offset[l].
- * The tables and counters live in a caller-provided device workspace (256-byte aligned, untouched
- * while the object exists); calls on one object must not overlap.  y_base must be 16-byte aligned.
+ * Where a layer's rows are long enough to be split over workgroups, the parts meet in 64-bit
+ * fixed-point sums (32 fractional bits, integer atomic adds: the same bits whatever the order of
+ * arrival); row sums must stay below 2^31 in magnitude, which fp16 inputs and rows of up to 32768
+ * features with weights below 1 always do.
+ * The tables, counters and sums (8 bytes per output of the stack) live in a caller-provided device
+ * workspace (256-byte aligned, untouched while the object exists); calls on one object must not
+ * overlap.  y_base must be 16-byte aligned.
  * The wait between stages is bounded: if it runs out (it cannot while the launch is cooperative,
  * unless the limit is set very low) the step still ends and pmpd_ordered_status reports it. */
 typedef struct pmpd_chain {

@@ -163,14 +163,32 @@ __device__ __forceinline__ void split_pieces(const uint32_t (&w)[4], uint32_t E,
 // exponents and group sums, by the whole workgroup.  Thread idx handles columns 8 idx ..
 // 8 idx + 7 of the range; a quad of threads owns one 32-column block, a row of 16 threads one
 // group.
-// Where a layer's activations come from: an fp16 vector, or (y32 != nullptr) the fp32 output of an
-// earlier layer of the same launch, scaled by `gain` and rounded to fp16 (round to nearest even) on
-// the way in.
+// Where a layer's activations come from: an fp16 vector, or the output of an earlier layer of the same
+// launch, scaled by `gain` and rounded to fp16 (round to nearest even) on the way in: its fp32 values
+// (y32), or its 64-bit fixed-point sums (y64) when that layer's K-parts meet by integer atomics.
 struct XSource {
   const _Float16* x16;
   const float* y32;
+  const unsigned long long* y64;
   float gain;
 };
+__device__ __forceinline__ XSource x_from_fp16(const _Float16* p) { return XSource{p, nullptr, nullptr, 1.f}; }
+
+// Sums of K-parts that meet across workgroups are kept as 64-bit fixed-point numbers with 32 fractional
+// bits: integer addition is associative, so atomic adds in any order of arrival give the same bits (no
+// floating-point atomics, no partial-sum buffers, nobody has to arrive last).  |v| must stay below 2^31;
+// what lies below 2^-32 is dropped (a row's sum over 13824 products of fp16 inputs stays below 2^28).
+__device__ __forceinline__ unsigned long long to_fixed(float v) {
+  const float fl = floorf(v);
+  const int hi = static_cast<int>(fl);
+  const uint32_t lo = static_cast<uint32_t>((v - fl) * 4294967296.0f);  // v - floor(v) is exact, in [0, 1)
+  return (static_cast<unsigned long long>(static_cast<uint32_t>(hi)) << 32) | lo;
+}
+__device__ __forceinline__ float fixed_to_float(unsigned long long f) {
+  const int hi = static_cast<int>(static_cast<uint32_t>(f >> 32));
+  const uint32_t lo = static_cast<uint32_t>(f);
+  return fmaf(static_cast<float>(lo), 2.3283064365386963e-10f, static_cast<float>(hi));  // one rounding, wherever it is used
+}
 
 __device__ __forceinline__ uint32_t pack_half2(float a, float b) {
   const half2_t h = {static_cast<_Float16>(a), static_cast<_Float16>(b)};
@@ -182,7 +200,16 @@ __device__ __forceinline__ void stage_x(const XSource& src, int c0, int cn, cons
   const int n16 = cn * 16;
   for (int idx = threadIdx.x; idx < n16; idx += NW * 64) {
     uint32_t w[4];
-    if (src.y32) {
+    if (src.y64) {
+      // fixed-point sums other workgroups of this launch have added to: agent-scope loads read the coherent copy
+      unsigned long long* yg = const_cast<unsigned long long*>(src.y64) + (c0 * 16 + idx) * 8;
+      float v8[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        v8[e] = fixed_to_float(__hip_atomic_load(yg + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) * src.gain;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) w[q] = pack_half2(v8[2 * q], v8[2 * q + 1]);
+    } else if (src.y32) {
       // written by other workgroups of this launch: agent-scope loads read the coherent copy
       float* yg = const_cast<float*>(src.y32) + (c0 * 16 + idx) * 8;
       float v8[8];
@@ -296,7 +323,8 @@ struct KRange {
 // (write-through) stores, so that workgroups of the same launch can read it without a cache flush.
 template <int B, int SETS, int NW, int SPLITK, bool ORDERED = false, typename Hook = NoHook>
 __device__ __forceinline__ void run_tiles(const LayerDesc& L, int tile0, const XSource& x, int m, float* __restrict__ y,
-                                          uint4* lds_raw, KRange kr, Hook before_staging = Hook()) {
+                                          uint4* lds_raw, KRange kr, Hook before_staging = Hook(),
+                                          unsigned long long* y64 = nullptr) {
   static_assert(NW % SPLITK == 0, "waves must divide evenly over the K splits");
   static_assert(!ORDERED || SETS == 1, "chained inputs are batch-1 only");
   const int lane = threadIdx.x & 63;
@@ -436,8 +464,13 @@ __device__ __forceinline__ void run_tiles(const LayerDesc& L, int tile0, const X
         for (int t = 0; t < 4; ++t) {
           const int row = tile * 64 + 16 * t + (lane & 15);
           if (row < L.out_f) {
-            if constexpr (ORDERED) __hip_atomic_store(&yo[row], yacc[s][t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            else yo[row] = yacc[s][t];
+            if constexpr (ORDERED) {
+              // one K-part among several: add it to the row's fixed-point sum; else the row is this workgroup's alone
+              if (y64) __hip_atomic_fetch_add(&y64[row], to_fixed(yacc[s][t]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              else __hip_atomic_store(&yo[row], yacc[s][t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            } else {
+              yo[row] = yacc[s][t];
+            }
           }
         }
       }
@@ -456,7 +489,7 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd<SETS>()) void pmpd_stack_ke
   extern __shared__ uint4 lds[];
   const WorkItem it = items[blockIdx.x];
   const LayerDesc L = layers[it.layer];
-  run_tiles<B, SETS, NW, SPLITK>(L, it.tile0, XSource{x_base + static_cast<int64_t>(m) * L.x_off, nullptr, 1.f}, m,
+  run_tiles<B, SETS, NW, SPLITK>(L, it.tile0, x_from_fp16(x_base + static_cast<int64_t>(m) * L.x_off), m,
                                  y_base + static_cast<int64_t>(m) * L.y_off, lds, KRange{0, L.n_groups, chunk_groups(L.n_groups, m)});
 }
 
@@ -465,7 +498,7 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd<SETS>()) void pmpd_layer_ke
                                                                                     const _Float16* __restrict__ x, int m,
                                                                                     float* __restrict__ y) {
   extern __shared__ uint4 lds[];
-  run_tiles<B, SETS, NW, SPLITK>(L, static_cast<int>(blockIdx.x) * (NW / SPLITK), XSource{x, nullptr, 1.f}, m, y, lds,
+  run_tiles<B, SETS, NW, SPLITK>(L, static_cast<int>(blockIdx.x) * (NW / SPLITK), x_from_fp16(x), m, y, lds,
                                  KRange{0, L.n_groups, chunk_groups(L.n_groups, m)});
 }
 
@@ -479,12 +512,14 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd<SETS>()) void pmpd_layer_ke
 // An item is one 64-row tile and one K-part of at least 8 groups (8: two groups per wave, all of
 // them in flight before the wait); the parts of a layer are as small as that allows while its
 // stage still has no more items than the chip holds workgroups, so that every stage, however few
-// rows it has, spreads over the whole chip in one round.  The K-parts of a tile meet in a buffer of partial sums; the workgroup that finishes a tile
-// last (a counter per tile tells) adds them in part order and writes y: no floating-point atomics,
-// the result does not depend on the order of arrival.
-// Only y and the partial sums cross workgroups; they are written and read with agent-scope
-// accesses (coherent across the chip's L2 slices), so the barrier needs no cache write-back or
-// invalidate.  The launch is cooperative, so all workgroups are resident and the wait ends; it is
+// rows it has, spreads over the whole chip in one round.  The K-parts of a row meet in a 64-bit
+// fixed-point sum (32 fractional bits) that every part adds to with an integer atomic: integer
+// addition is associative, so the result does not depend on the order of arrival, there are no
+// floating-point atomics, no buffers of partial sums, and nobody has to wait to be last.  Layers
+// chained to such a layer read the sums; y of those layers is written from them after the last
+// stage.  A layer with a single K-part writes y directly.
+// Only y and the sums cross workgroups; they are written and read with agent-scope accesses
+// (coherent across the chip's L2 slices), so the barrier needs no cache write-back or invalidate.  The launch is cooperative, so all workgroups are resident and the wait ends; it is
 // bounded all the same (spin_limit polls), and a wait that runs out only sets sync->timed_out.
 // Counters of the stage barrier.  Workgroup w adds to sub-counter w % 16 of the stage; the last
 // one of each sub-counter adds to the stage's top counter, and the last of those publishes the
@@ -503,12 +538,11 @@ struct OrderedSync {
 constexpr int kStageCounterWords = (kSubCounters + 1) * (kSyncLine / 4);  // 16 uint32 (64 bytes) apart
 
 struct ChainDesc {
-  int64_t src_y_off;     // fp32 elements from y_base of the producing layer's output, or -1: input from x_base
-  int64_t partial_off;   // fp32 elements into the partial-sum buffer ([part][out_f]); unused when n_parts == 1
+  int64_t src_y_off;     // elements from y_base (or from the fixed-point sums) of the producing layer's output; -1: input from x_base
   float gain;
-  int32_t n_parts;       // K-parts of part_groups groups each (the last one may be shorter)
-  int32_t tile_counter;  // index of the layer's first tile counter
+  int32_t n_parts;       // K-parts of part_groups groups each (the last one may be shorter); > 1: the parts meet in fixed point
   int32_t part_groups;
+  int32_t src_fixed;     // the producing layer has more than one K-part: read its fixed-point sums
 };
 
 // Wait until every vector memory operation of this wave, stores included, has been acknowledged
@@ -526,12 +560,10 @@ template <int B>
 __global__ __launch_bounds__(kOrderedWaves * 64, 4) void pmpd_ordered_kernel(
     const LayerDesc* __restrict__ layers, const ChainDesc* __restrict__ chains, const WorkItem* __restrict__ items,
     const int32_t* __restrict__ stage_begin, int n_stages, const _Float16* __restrict__ x_base, float* __restrict__ y_base,
-    float* __restrict__ partials, OrderedSync* sync, uint32_t spin_limit) {
+    unsigned long long* __restrict__ sums, OrderedSync* sync, uint32_t spin_limit, int n_layers) {
   extern __shared__ uint4 lds[];
-  __shared__ int last_part;
   const uint32_t n_wg = gridDim.x;
   uint32_t* arrived = sync->counters;  // + s * kStageCounterWords + k * 16
-  uint32_t* tile_done = sync->counters + n_stages * kStageCounterWords;
   for (int s = 0; s < n_stages; ++s) {
     bool waited = s == 0;
     auto wait_for_previous_stage = [&]() {
@@ -555,57 +587,18 @@ __global__ __launch_bounds__(kOrderedWaves * 64, 4) void pmpd_ordered_kernel(
       const LayerDesc L = layers[it.layer];
       const ChainDesc c = chains[it.layer];
       const int tile = it.tile0 & ((1 << kItemPartShift) - 1), part = it.tile0 >> kItemPartShift;
-      const XSource src = c.src_y_off >= 0 ? XSource{nullptr, y_base + c.src_y_off, c.gain}
-                                           : XSource{x_base + L.x_off, nullptr, 1.f};
-      float* y = y_base + L.y_off;
-      float* target = c.n_parts > 1 ? partials + c.partial_off + static_cast<int64_t>(part) * L.out_f : y;
+      const XSource src = c.src_y_off < 0 ? x_from_fp16(x_base + L.x_off)
+                          : c.src_fixed   ? XSource{nullptr, nullptr, sums + c.src_y_off, c.gain}
+                                          : XSource{nullptr, y_base + c.src_y_off, nullptr, c.gain};
       const int g0 = part * c.part_groups;
       const int g1 = g0 + c.part_groups < L.n_groups ? g0 + c.part_groups : L.n_groups;
-      run_tiles<B, 1, kOrderedWaves, kOrderedWaves, true>(L, tile, src, 1, target, lds, KRange{g0, g1, kOrderedMaxPartGroups},
-                                                         wait_for_previous_stage);
-      if (c.n_parts > 1) {
-        // the partial sums of this part are acknowledged, then the part is counted; the last one adds
-        wait_for_own_stores();
-        __syncthreads();
-        if (threadIdx.x == 0) {
-          const uint32_t before = __hip_atomic_fetch_add(&tile_done[c.tile_counter + tile], 1u, __ATOMIC_RELAXED,
-                                                         __HIP_MEMORY_SCOPE_AGENT);
-          last_part = before + 1 == static_cast<uint32_t>(c.n_parts);
-        }
-        __syncthreads();
-        if (last_part) {
-          // wave w adds the parts w, w + 4, ... of the 64 rows (loads issued four at a time), then the
-          // four sums meet in LDS: the order of the additions is fixed
-          float* red = reinterpret_cast<float*>(lds);
-          const int row = tile * 64 + static_cast<int>(threadIdx.x & 63);
-          const int w = static_cast<int>(threadIdx.x >> 6);
-          float sum = 0.f;
-          if (row < L.out_f) {
-            const float* p = partials + c.partial_off + row;
-            for (int q = w; q < c.n_parts; q += 4 * kOrderedWaves) {
-              float v[4];
-#pragma unroll
-              for (int u = 0; u < 4; ++u) {
-                const int qq = q + u * kOrderedWaves;
-                v[u] = qq < c.n_parts ? __hip_atomic_load(const_cast<float*>(p) + static_cast<int64_t>(qq) * L.out_f,
-                                                          __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                                      : 0.f;
-              }
-              sum += (v[0] + v[1]) + (v[2] + v[3]);
-            }
-          }
-          red[threadIdx.x] = sum;
-          __syncthreads();
-          if (threadIdx.x < 64 && row < L.out_f) {
-            const float total = (red[threadIdx.x] + red[threadIdx.x + 64]) + (red[threadIdx.x + 128] + red[threadIdx.x + 192]);
-            __hip_atomic_store(&y[row], total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          }
-        }
-      }
-      __syncthreads();  // the LDS image and last_part are reused by the next item
+      // a layer with one K-part writes y itself; the parts of the others add to the rows' fixed-point sums
+      run_tiles<B, 1, kOrderedWaves, kOrderedWaves, true>(L, tile, src, 1, y_base + L.y_off, lds, KRange{g0, g1, kOrderedMaxPartGroups},
+                                                         wait_for_previous_stage, c.n_parts > 1 ? sums + L.y_off : nullptr);
+      __syncthreads();  // the LDS image is reused by the next item
     }
-    // every wave waits until its own (write-through) stores of stage s are acknowledged, then the
-    // workgroup is counted
+    // every wave waits until its own (write-through) stores and atomic adds of stage s are acknowledged, then
+    // the workgroup is counted
     wait_for_own_stores();
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -620,10 +613,32 @@ __global__ __launch_bounds__(kOrderedWaves * 64, 4) void pmpd_ordered_kernel(
       }
     }
   }
+  // After the last stage: y of the layers whose K-parts met in fixed point (the same conversion the
+  // chained layers used when they read those sums).
+  if (threadIdx.x == 0) {
+    uint32_t polls = 0;
+    while (__hip_atomic_load(&sync->stage_done[(blockIdx.x % kFlagCopies) * kSyncLine], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) <
+           static_cast<uint32_t>(n_stages)) {
+      if (++polls >= spin_limit) {
+        __hip_atomic_store(&sync->timed_out, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        break;
+      }
+      __builtin_amdgcn_s_sleep(32);
+    }
+  }
+  __syncthreads();
+  for (int li = 0; li < n_layers; ++li) {
+    if (chains[li].n_parts <= 1) continue;
+    const LayerDesc& L = layers[li];
+    for (int row = blockIdx.x * blockDim.x + threadIdx.x; row < L.out_f; row += gridDim.x * blockDim.x)
+      y_base[L.y_off + row] = fixed_to_float(__hip_atomic_load(sums + L.y_off + row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+  }
 }
 
-__global__ void pmpd_ordered_reset_kernel(OrderedSync* sync, int n_counters) {
-  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n_counters; i += gridDim.x * blockDim.x) sync->counters[i] = 0;
+__global__ void pmpd_ordered_reset_kernel(OrderedSync* sync, int n_counters, unsigned long long* sums, int64_t n_sums) {
+  const int64_t tid = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x, n_threads = static_cast<int64_t>(gridDim.x) * blockDim.x;
+  for (int64_t i = tid; i < n_counters; i += n_threads) sync->counters[i] = 0;
+  for (int64_t i = tid; i < n_sums; i += n_threads) sums[i] = 0;
   if (blockIdx.x == 0 && threadIdx.x < kFlagCopies) sync->stage_done[threadIdx.x * kSyncLine] = 0;
 }
 
@@ -868,7 +883,8 @@ struct pmpd_ordered {
   const WorkItem* d_items = nullptr;
   const int32_t* d_stage_begin = nullptr;
   OrderedSync* d_sync = nullptr;
-  float* d_partials = nullptr;
+  unsigned long long* d_sums = nullptr;  // fixed-point row sums, laid out like y
+  int64_t n_sums = 0;
   int n_counters = 0;
   int n_stages = 0;
   int max_stage_items = 0;
@@ -913,15 +929,13 @@ static std::vector<int> ordered_part_groups(const pmpd_stack* st, const pmpd_cha
 
 static int parts_of(int n_groups, int part_groups) { return (n_groups + part_groups - 1) / part_groups; }
 
-// items, counters and partial-sum floats an ordered step of this stack needs
-static void ordered_counts(const pmpd_stack* st, const std::vector<int>& pg, size_t* n_items, size_t* n_tiles, size_t* n_partials) {
-  *n_items = *n_tiles = *n_partials = 0;
+// items an ordered step of this stack needs, and the length of its y (= of the fixed-point sums)
+static void ordered_counts(const pmpd_stack* st, const std::vector<int>& pg, size_t* n_items, size_t* n_sums) {
+  *n_items = *n_sums = 0;
   for (size_t i = 0; i < st->layers.size(); ++i) {
     const LayerDesc& d = st->layers[i];
-    const size_t parts = static_cast<size_t>(parts_of(d.n_groups, pg[i]));
-    *n_items += static_cast<size_t>(d.n_tiles) * parts;
-    *n_tiles += static_cast<size_t>(d.n_tiles);
-    if (parts > 1) *n_partials += align_up(parts * static_cast<size_t>(d.out_f), 4);
+    *n_items += static_cast<size_t>(d.n_tiles) * static_cast<size_t>(parts_of(d.n_groups, pg[i]));
+    *n_sums = std::max(*n_sums, static_cast<size_t>(d.y_off) + static_cast<size_t>(d.out_f));
   }
 }
 
@@ -934,12 +948,12 @@ static int ordered_slots() {
 }
 
 static size_t ordered_bytes(const pmpd_stack* st, const std::vector<int>& pg, size_t n_stages) {
-  size_t n_items, n_tiles, n_partials;
-  ordered_counts(st, pg, &n_items, &n_tiles, &n_partials);
+  size_t n_items, n_sums;
+  ordered_counts(st, pg, &n_items, &n_sums);
   return align_up(st->layers.size() * sizeof(ChainDesc), 256) + align_up(n_items * sizeof(WorkItem), 256) +
          align_up((n_stages + 1) * sizeof(int32_t), 256) +
-         align_up(sizeof(OrderedSync) + (n_stages * kStageCounterWords + n_tiles) * sizeof(uint32_t), 256) +
-         align_up(n_partials * sizeof(float), 256);
+         align_up(sizeof(OrderedSync) + n_stages * kStageCounterWords * sizeof(uint32_t), 256) +
+         align_up(n_sums * sizeof(unsigned long long), 256);
 }
 
 template <int B>
@@ -954,15 +968,16 @@ static hipError_t launch_ordered(const pmpd_ordered* o, const void* x, float* y,
   int grid = std::min(per_cu, 4) * prop.multiProcessorCount;
   if (grid < 1) return hipErrorCooperativeLaunchTooLarge;
   grid = std::min(grid, o->max_stage_items);
-  hipLaunchKernelGGL(pmpd_ordered_reset_kernel, dim3(64), dim3(256), 0, s, o->d_sync, o->n_counters);
+  hipLaunchKernelGGL(pmpd_ordered_reset_kernel, dim3(1024), dim3(256), 0, s, o->d_sync, o->n_counters, o->d_sums, o->n_sums);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   const LayerDesc* layers = st->d_layers;
   const _Float16* xb = static_cast<const _Float16*>(x);
   int n_stages = o->n_stages;
   uint32_t spin = o->spin_limit;
+  int n_layers = static_cast<int>(st->layers.size());
   void* args[] = {&layers, const_cast<ChainDesc**>(&o->d_chains), const_cast<WorkItem**>(&o->d_items),
-                  const_cast<int32_t**>(&o->d_stage_begin), &n_stages, &xb, &y, const_cast<float**>(&o->d_partials),
-                  const_cast<OrderedSync**>(&o->d_sync), &spin};
+                  const_cast<int32_t**>(&o->d_stage_begin), &n_stages, &xb, &y, const_cast<unsigned long long**>(&o->d_sums),
+                  const_cast<OrderedSync**>(&o->d_sync), &spin, &n_layers};
   return hipLaunchCooperativeKernel(reinterpret_cast<const void*>(&pmpd_ordered_kernel<B>), dim3(grid), dim3(kOrderedWaves * 64),
                                     args, static_cast<unsigned>(lds), s);
 }
@@ -989,15 +1004,14 @@ int32_t pmpd_ordered_create(const pmpd_stack_t* stack, const pmpd_chain_t* chain
   const std::vector<int> pg = ordered_part_groups(stack, chain, n_stages, ordered_slots());
   const size_t need = ordered_bytes(stack, pg, static_cast<size_t>(n_stages));
   if (workspace_bytes < need) return fail(PMPD_ESIZE, "pmpd_ordered_create: workspace %zu bytes, need %zu", workspace_bytes, need);
-  size_t n_items, n_tiles, n_partials;
-  ordered_counts(stack, pg, &n_items, &n_tiles, &n_partials);
+  size_t n_items, n_sums;
+  ordered_counts(stack, pg, &n_items, &n_sums);
   if (n_items > static_cast<size_t>(INT32_MAX)) return fail(PMPD_EINVAL, "pmpd_ordered_create: too many work items");
   auto* o = new pmpd_ordered;
   o->stack = stack;
   o->n_stages = n_stages;
-  o->n_counters = static_cast<int>(static_cast<size_t>(n_stages) * kStageCounterWords + n_tiles);
-  int64_t partial_off = 0;
-  int32_t tile_counter = 0;
+  o->n_counters = static_cast<int>(static_cast<size_t>(n_stages) * kStageCounterWords);
+  o->n_sums = static_cast<int64_t>(n_sums);
   for (size_t i = 0; i < n_layers; ++i) {
     const LayerDesc& d = stack->layers[i];
     const int src = chain[i].source;
@@ -1006,10 +1020,8 @@ int32_t pmpd_ordered_create(const pmpd_stack_t* stack, const pmpd_chain_t* chain
       delete o;
       return fail(PMPD_EINVAL, "pmpd_ordered_create: layer %zu is too large for the item encoding", i);
     }
-    o->chains.push_back(ChainDesc{src < 0 ? int64_t{-1} : stack->layers[src].y_off, partial_off, chain[i].gain, parts,
-                                  tile_counter, pg[i]});
-    if (parts > 1) partial_off += static_cast<int64_t>(align_up(static_cast<size_t>(parts) * static_cast<size_t>(d.out_f), 4));
-    tile_counter += d.n_tiles;
+    const int src_fixed = src >= 0 && parts_of(stack->layers[src].n_groups, pg[src]) > 1;
+    o->chains.push_back(ChainDesc{src < 0 ? int64_t{-1} : stack->layers[src].y_off, chain[i].gain, parts, pg[i], src_fixed});
   }
   // (tile, K-part) items, stage by stage; inside a stage long rows first
   std::vector<int> order(n_layers);
@@ -1040,10 +1052,10 @@ int32_t pmpd_ordered_create(const pmpd_stack_t* stack, const pmpd_chain_t* chain
   o->d_stage_begin = reinterpret_cast<const int32_t*>(w);
   w += align_up(o->stage_begin.size() * sizeof(int32_t), 256);
   o->d_sync = reinterpret_cast<OrderedSync*>(w);
-  const size_t sync_bytes = sizeof(OrderedSync) + (static_cast<size_t>(n_stages) * kStageCounterWords + n_tiles) * sizeof(uint32_t);
+  const size_t sync_bytes = sizeof(OrderedSync) + static_cast<size_t>(n_stages) * kStageCounterWords * sizeof(uint32_t);
   if (e == hipSuccess) e = hipMemset(w, 0, sync_bytes);
   w += align_up(sync_bytes, 256);
-  o->d_partials = reinterpret_cast<float*>(w);
+  o->d_sums = reinterpret_cast<unsigned long long*>(w);
   if (e != hipSuccess) {
     delete o;
     return hip_fail(e, "pmpd_ordered_create copy");

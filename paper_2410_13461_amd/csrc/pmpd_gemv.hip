@@ -160,61 +160,84 @@ __device__ __forceinline__ void split_pieces(const uint32_t (&w)[4], uint32_t E,
 }
 
 // Split groups [c0, c0 + cn) of activation vector j into the two classes' pieces, block
-// exponents and group sums, by the whole workgroup.  Thread idx handles columns 8 idx ..
-// 8 idx + 7 of the range; a quad of threads owns one 32-column block, a row of 16 threads one
-// group.
-// Where a layer's activations come from: an fp16 vector, or the output of an earlier layer of the same
-// launch, scaled by `gain` and rounded to fp16 (round to nearest even) on the way in: its fp32 values
-// (y32), or its 64-bit fixed-point sums (y64) when that layer's K-parts meet by integer atomics.
-struct XSource {
-  const _Float16* x16;
-  const float* y32;
-  const unsigned long long* y64;
-  float gain;
-};
-__device__ __forceinline__ XSource x_from_fp16(const _Float16* p) { return XSource{p, nullptr, nullptr, 1.f}; }
-
-// Sums of K-parts that meet across workgroups are kept as 64-bit fixed-point numbers with 32 fractional
-// bits: integer addition is associative, so atomic adds in any order of arrival give the same bits (no
-// floating-point atomics, no partial-sum buffers, nobody has to arrive last).  |v| must stay below 2^31;
-// what lies below 2^-32 is dropped (a row's sum over 13824 products of fp16 inputs stays below 2^28).
-__device__ __forceinline__ unsigned long long to_fixed(float v) {
+// exponents and group sums, by NT threads (whole waves) of which the caller is number tid.
+// Thread idx handles columns 8 idx .. 8 idx + 7 of the range; a quad of threads owns one
+// 32-column block, a row of 16 threads one group.
+// Sums that meet across workgroups are 64-bit words: 32 fractional bits, 27 integer bits, and in the
+// top 5 bits the number of K-parts that have been added.  A part adds 2^59 + 2^53 + round_down(v 2^32)
+// with one integer atomic: the bias 2^53 (= 2^21) keeps the addend's low 59 bits positive, so nothing
+// is borrowed from the count, and up to 31 parts cannot carry into it.  Integer addition is
+// associative: the bits do not depend on the order of arrival (no floating-point atomics, no
+// partial-sum buffers), and a reader sees in the word itself whether the sum is complete, so no
+// flag, acknowledgement or barrier stands between a producer's add and its consumers.  A part's
+// value is clamped to +-(2^21 - 1) (a NaN becomes the lower bound), so that no input can damage
+// the count; what lies below 2^-32 is dropped.
+constexpr int kCountShift = 59;
+constexpr int kMaxParts = 31;
+constexpr unsigned long long kPartBias = 1ull << 53;
+constexpr float kPartLimit = 2097151.0f;
+__device__ __forceinline__ unsigned long long part_word(float v) {
+  v = fminf(fmaxf(v, -kPartLimit), kPartLimit);
   const float fl = floorf(v);
   const int hi = static_cast<int>(fl);
   const uint32_t lo = static_cast<uint32_t>((v - fl) * 4294967296.0f);  // v - floor(v) is exact, in [0, 1)
-  return (static_cast<unsigned long long>(static_cast<uint32_t>(hi)) << 32) | lo;
+  return ((static_cast<unsigned long long>(static_cast<uint32_t>(hi)) << 32) | lo) + kPartBias + (1ull << kCountShift);
 }
-__device__ __forceinline__ float fixed_to_float(unsigned long long f) {
+// The word of a row that has a single part carries that part as it is: its fp32 bits under a count of one.
+__device__ __forceinline__ unsigned long long whole_word(float v) { return (1ull << kCountShift) | __builtin_bit_cast(uint32_t, v); }
+__device__ __forceinline__ bool sum_complete(unsigned long long w, int n_parts) { return static_cast<int>(w >> kCountShift) == n_parts; }
+__device__ __forceinline__ float sum_value(unsigned long long w, int n_parts) {
+  if (n_parts == 1) return __builtin_bit_cast(float, static_cast<uint32_t>(w));
+  const unsigned long long f = (w & ((1ull << kCountShift) - 1)) - static_cast<unsigned long long>(n_parts) * kPartBias;
   const int hi = static_cast<int>(static_cast<uint32_t>(f >> 32));
   const uint32_t lo = static_cast<uint32_t>(f);
   return fmaf(static_cast<float>(lo), 2.3283064365386963e-10f, static_cast<float>(hi));  // one rounding, wherever it is used
 }
+
+// Where a layer's activations come from: an fp16 vector, or the output of an earlier layer of the same
+// launch, scaled by `gain` and rounded to fp16 (round to nearest even) on the way in: the sums of its
+// `parts` K-parts (y64), read again (at most `spin_limit` times, then *timed_out is set) until complete.
+struct XSource {
+  const _Float16* x16;
+  const unsigned long long* y64;
+  float gain;
+  int parts;
+  uint32_t spin_limit;
+  uint32_t* timed_out;
+};
+__device__ __forceinline__ XSource x_from_fp16(const _Float16* p) { return XSource{p, nullptr, 1.f, 0, 0, nullptr}; }
 
 __device__ __forceinline__ uint32_t pack_half2(float a, float b) {
   const half2_t h = {static_cast<_Float16>(a), static_cast<_Float16>(b)};
   return __builtin_bit_cast(uint32_t, h);
 }
 
-template <int NW>
-__device__ __forceinline__ void stage_x(const XSource& src, int c0, int cn, const ImageLayout& im, int j) {
+template <int NT>
+__device__ __forceinline__ void stage_x(const XSource& src, int c0, int cn, const ImageLayout& im, int j, int tid) {
   const int n16 = cn * 16;
-  for (int idx = threadIdx.x; idx < n16; idx += NW * 64) {
+  for (int idx = tid; idx < n16; idx += NT) {
     uint32_t w[4];
     if (src.y64) {
-      // fixed-point sums other workgroups of this launch have added to: agent-scope loads read the coherent copy
+      // sums other workgroups of this launch add to: agent-scope loads read the coherent copy
       unsigned long long* yg = const_cast<unsigned long long*>(src.y64) + (c0 * 16 + idx) * 8;
+      unsigned long long s8[8];
+      for (uint32_t tries = 0;;) {
+        bool complete = true;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          s8[e] = __hip_atomic_load(yg + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          complete = complete && sum_complete(s8[e], src.parts);
+        }
+        if (complete) break;
+        if (++tries >= src.spin_limit) {
+          __hip_atomic_store(src.timed_out, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          break;
+        }
+        __builtin_amdgcn_s_sleep(8);
+      }
       float v8[8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e)
-        v8[e] = fixed_to_float(__hip_atomic_load(yg + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) * src.gain;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) w[q] = pack_half2(v8[2 * q], v8[2 * q + 1]);
-    } else if (src.y32) {
-      // written by other workgroups of this launch: agent-scope loads read the coherent copy
-      float* yg = const_cast<float*>(src.y32) + (c0 * 16 + idx) * 8;
-      float v8[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) v8[e] = __hip_atomic_load(yg + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) * src.gain;
+      for (int e = 0; e < 8; ++e) v8[e] = sum_value(s8[e], src.parts) * src.gain;
 #pragma unroll
       for (int q = 0; q < 4; ++q) w[q] = pack_half2(v8[2 * q], v8[2 * q + 1]);
     } else {
@@ -304,61 +327,108 @@ template <int B>
 constexpr float half_step() { return B == 4 ? 0.5f : B == 3 ? 1.0f : 2.0f; }  // 2^(3-b)
 
 // =====================================================================================
-// One workgroup: NW / SPLITK consecutive row tiles starting at tile0, each split over SPLITK waves
-// along K, for m <= 2 SETS activation vectors.  K is walked in chunks whose split activations fit
-// in LDS.  x: [m][in_f] fp16, y: [m][out_f] fp32.
-struct NoHook {
-  __device__ __forceinline__ void operator()() const {}
-};
-
 // The groups a workgroup walks (the whole row unless K is split over workgroups) and the chunk
 // capacity the LDS image was sized for.
 struct KRange {
   int begin, end, chunk;
 };
 
-// before_staging() runs in every thread after the first weight loads have been issued and before x
-// is read: the dependency-ordered kernel waits there for the producers of x.  ORDERED also issues
-// the loads of the first two groups before that point instead of one, and stores y with agent-scope
-// (write-through) stores, so that workgroups of the same launch can read it without a cache flush.
-template <int B, int SETS, int NW, int SPLITK, bool ORDERED = false, typename Hook = NoHook>
-__device__ __forceinline__ void run_tiles(const LayerDesc& L, int tile0, const XSource& x, int m, float* __restrict__ y,
-                                          uint4* lds_raw, KRange kr, Hook before_staging = Hook(),
-                                          unsigned long long* y64 = nullptr) {
+// A lane's addresses into the stored words of one 64-row tile: word [g * 64] of plane k is the
+// lane's 16 bytes of group g, word [g * 16] of sp the (scale, min) words of rows l % 16 + 16 t,
+// t = 0..3 (the 16 bytes at [l % 16] of the group's 64 words).
+template <int B>
+struct TileWords {
+  global_u32x4_ptr pp[B];
+  global_u32x4_ptr sp;
+  __device__ __forceinline__ TileWords(const LayerDesc& L, int tile, int lane) {
+    const int64_t tbase = (static_cast<int64_t>(tile) * L.n_groups) * 64 + lane;
+#pragma unroll
+    for (int k = 0; k < B; ++k) pp[k] = (global_u32x4_ptr)(L.plane[k]) + tbase;
+    sp = (global_u32x4_ptr)(L.sa) + (tbase - lane) / 4 + (lane & 15);
+  }
+  // Weights are read exactly once per pass: nontemporal loads keep them from displacing anything
+  // in the caches.
+  __device__ __forceinline__ void load(u32x4 (&dst)[B], u32x4& dsa, int g) const {
+#pragma unroll
+    for (int k = 0; k < B; ++k) dst[k] = __builtin_nontemporal_load(&pp[k][g * 64]);
+    dsa = sp[g * 16];
+  }
+};
+
+// Where a lane finds its operands in the LDS image.  Row i = lane % 16 of the activation operand
+// is piece i % 4 of slot i / 4; the lane receives the sums of slot lane / 16.  Slot 2 v + c =
+// class c of vector 2 s + v.
+template <int SETS>
+struct OperandOffsets {
+  int a[SETS], s[SETS], x[SETS];
+  __device__ __forceinline__ OperandOffsets(const ImageLayout& im, int lane, int m) {
+    const int piece = (lane & 3) == 3 ? 0 : (lane & 3);  // row 4 q + 3 is never read back
+    const int in_slot = (lane & 15) >> 2, out_slot = lane >> 4;
+#pragma unroll
+    for (int q = 0; q < SETS; ++q) {
+      int vi = 2 * q + (in_slot >> 1);
+      vi = vi < m ? vi : m - 1;  // slots of absent vectors repeat the last one; their sums are not stored
+      a[q] = im.piece_off(vi, in_slot & 1) + piece * kPieceStride + (lane >> 4) * 16;
+      s[q] = im.scale_off(vi, in_slot & 1) + piece * 4 + (lane >> 4);
+      int vo = 2 * q + (out_slot >> 1);
+      vo = vo < m ? vo : m - 1;
+      x[q] = im.xsum_off(vo, out_slot & 1);
+    }
+  }
+};
+
+// yacc += (the weights of one group of the tile) x (the split activations of group gr of the image).
+template <int B, int SETS>
+__device__ __forceinline__ void consume_group(const ImageLayout& im, const OperandOffsets<SETS>& off, int gr, const u32x4 (&pl)[B],
+                                              const u32x4& csa, int wscale, float (&yacc)[SETS][4]) {
+  XOperand X[SETS];
+  float xg[SETS];
+#pragma unroll
+  for (int s = 0; s < SETS; ++s) {
+    X[s].a = read_fp8_operand(im.pieces + off.a[s] + gr * kGroupPieceBytes);
+    X[s].scale = static_cast<unsigned char>(im.scales[off.s[s] + gr * kScaleBytes]);
+    xg[s] = im.xsum[off.x[s] + gr];
+  }
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    float4_t acc[SETS];
+    mfma_block<B, SETS>(X, pl, t, wscale, acc);
+    const uint32_t w = word_of(csa, t);
+    const float sc = half_bits_to_float(w & 0xffffu);
+    const float offs = fmaf(sc, half_step<B>(), half_bits_to_float(w >> 16));
+#pragma unroll
+    for (int s = 0; s < SETS; ++s) {
+      const float d = (acc[s][0] + acc[s][1]) + acc[s][2];
+      yacc[s][t] = fmaf(sc, d, yacc[s][t]);
+      yacc[s][t] = fmaf(offs, xg[s], yacc[s][t]);
+    }
+  }
+}
+
+__device__ __forceinline__ int weight_scale_register() {
+  int wscale = 0x00008082;  // e8m0 bytes of 2^3 (byte 0, upper plane pair) and 2^1 (byte 1, lower pair)
+  asm volatile("" : "+v"(wscale));
+  return wscale;
+}
+
+// One workgroup: NW / SPLITK consecutive row tiles starting at tile0, each split over SPLITK waves
+// along K, for m <= 2 SETS activation vectors.  K is walked in chunks whose split activations fit
+// in LDS.  x: [m][in_f] fp16, y: [m][out_f] fp32.
+template <int B, int SETS, int NW, int SPLITK>
+__device__ __forceinline__ void run_tiles(const LayerDesc& L, int tile0, const _Float16* __restrict__ x, int m, float* __restrict__ y,
+                                          uint4* lds_raw, KRange kr) {
   static_assert(NW % SPLITK == 0, "waves must divide evenly over the K splits");
-  static_assert(!ORDERED || SETS == 1, "chained inputs are batch-1 only");
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int G = L.n_groups;
   const ImageLayout im(lds_raw, kr.chunk, m);
 
   const int tile = tile0 + wave / SPLITK;
   const int ks = wave % SPLITK;
   const bool active = tile < L.n_tiles;
-  const int64_t tbase = (static_cast<int64_t>(active ? tile : 0) * G) * 64 + lane;  // + g*64 per group
-  global_u32x4_ptr pp[B];
-#pragma unroll
-  for (int k = 0; k < B; ++k) pp[k] = (global_u32x4_ptr)(L.plane[k]) + tbase;
-  // (scale, min) words of rows l % 16 + 16 t, t = 0..3: the 16 bytes at [l % 16] of the group's 64 words
-  global_u32x4_ptr sp = (global_u32x4_ptr)(L.sa) + (tbase - lane) / 4 + (lane & 15);  // + g*16 per group
-
-  // Operand addressing.  Row i = lane % 16 of the activation operand is piece i % 4 of slot i / 4;
-  // the lane receives the sums of slot lane / 16.  Slot 2 v + c = class c of vector 2 s + v.
-  const int piece = (lane & 3) == 3 ? 0 : (lane & 3);  // row 4 q + 3 is never read back
-  const int in_slot = (lane & 15) >> 2, out_slot = lane >> 4;
-  int a_off[SETS], s_off[SETS], x_off[SETS];
-#pragma unroll
-  for (int s = 0; s < SETS; ++s) {
-    int vi = 2 * s + (in_slot >> 1);
-    vi = vi < m ? vi : m - 1;  // slots of absent vectors repeat the last one; their sums are not stored
-    a_off[s] = im.piece_off(vi, in_slot & 1) + piece * kPieceStride + (lane >> 4) * 16;
-    s_off[s] = im.scale_off(vi, in_slot & 1) + piece * 4 + (lane >> 4);
-    int vo = 2 * s + (out_slot >> 1);
-    vo = vo < m ? vo : m - 1;
-    x_off[s] = im.xsum_off(vo, out_slot & 1);
-  }
-  int wscale = 0x00008082;
-  asm volatile("" : "+v"(wscale));
+  const TileWords<B> tw(L, active ? tile : 0, lane);
+  const OperandOffsets<SETS> off(im, lane, m);
+  const int out_slot = lane >> 4;
+  const int wscale = weight_scale_register();
 
   float yacc[SETS][4];
 #pragma unroll
@@ -370,60 +440,24 @@ __device__ __forceinline__ void run_tiles(const LayerDesc& L, int tile0, const X
     const int cn = (kr.end - c0 < im.cg) ? (kr.end - c0) : im.cg;
     const int g0 = c0 + cn * ks / SPLITK, g1 = c0 + cn * (ks + 1) / SPLITK;
     const bool work = active && g0 < g1;
-    // The next group's plane words are in flight while the current group is consumed.  Weights
-    // are read exactly once per pass: nontemporal loads keep them from displacing anything in
-    // the caches.  Past the end of the range the last group is reloaded (a cache hit) instead
-    // of branching around the loads.  Two register sets alternate (the loop is unrolled by two).
+    // The next group's plane words are in flight while the current group is consumed.  Past the
+    // end of the range the last group is reloaded (a cache hit) instead of branching around the
+    // loads.  Two register sets alternate (the loop is unrolled by two).
     u32x4 pa[B], pb[B], sa_a = {0, 0, 0, 0}, sa_b = {0, 0, 0, 0};
-    auto load = [&](u32x4 (&dst)[B], u32x4& dsa, int g) {
-      const int gl = g < g1 ? g : g1 - 1;
-#pragma unroll
-      for (int k = 0; k < B; ++k) dst[k] = __builtin_nontemporal_load(&pp[k][gl * 64]);
-      dsa = sp[gl * 16];
-    };
+    auto load = [&](u32x4 (&dst)[B], u32x4& dsa, int g) { tw.load(dst, dsa, g < g1 ? g : g1 - 1); };
     // The first group's loads do not depend on the activations: issue them before the workgroup
     // splits x, so that their latency overlaps the staging and the barrier.
     if (work) load(pa, sa_a, g0);
-    if (ORDERED && work) load(pb, sa_b, g0 + 1);
-    if (c0 == kr.begin) before_staging();
-    else __syncthreads();  // the previous chunk's image has been consumed
-    for (int j = 0; j < m; ++j) {
-      XSource xj = x;
-      if (xj.x16) xj.x16 += static_cast<int64_t>(j) * L.in_f;
-      stage_x<NW>(xj, c0, cn, im, j);
-    }
+    if (c0 != kr.begin) __syncthreads();  // the previous chunk's image has been consumed
+    for (int j = 0; j < m; ++j)
+      stage_x<NW * 64>(x_from_fp16(x + static_cast<int64_t>(j) * L.in_f), c0, cn, im, j, threadIdx.x);
     __syncthreads();
     if (work) {
-      auto consume = [&](const u32x4 (&pl)[B], const u32x4& csa, int g) {
-        const int gr = g - c0;
-        XOperand X[SETS];
-        float xg[SETS];
-#pragma unroll
-        for (int s = 0; s < SETS; ++s) {
-          X[s].a = read_fp8_operand(im.pieces + a_off[s] + gr * kGroupPieceBytes);
-          X[s].scale = static_cast<unsigned char>(im.scales[s_off[s] + gr * kScaleBytes]);
-          xg[s] = im.xsum[x_off[s] + gr];
-        }
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          float4_t acc[SETS];
-          mfma_block<B, SETS>(X, pl, t, wscale, acc);
-          const uint32_t w = word_of(csa, t);
-          const float sc = half_bits_to_float(w & 0xffffu);
-          const float off = fmaf(sc, half_step<B>(), half_bits_to_float(w >> 16));
-#pragma unroll
-          for (int s = 0; s < SETS; ++s) {
-            const float d = (acc[s][0] + acc[s][1]) + acc[s][2];
-            yacc[s][t] = fmaf(sc, d, yacc[s][t]);
-            yacc[s][t] = fmaf(off, xg[s], yacc[s][t]);
-          }
-        }
-      };
       for (int gc = g0; gc < g1; gc += 2) {
-        if (!ORDERED || gc > g0) load(pb, sa_b, gc + 1);
-        consume(pa, sa_a, gc);
+        load(pb, sa_b, gc + 1);
+        consume_group<B, SETS>(im, off, gc - c0, pa, sa_a, wscale, yacc);
         load(pa, sa_a, gc + 2);
-        if (gc + 1 < g1) consume(pb, sa_b, gc + 1);
+        if (gc + 1 < g1) consume_group<B, SETS>(im, off, gc + 1 - c0, pb, sa_b, wscale, yacc);
       }
     }
   }
@@ -463,15 +497,7 @@ __device__ __forceinline__ void run_tiles(const LayerDesc& L, int tile0, const X
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
           const int row = tile * 64 + 16 * t + (lane & 15);
-          if (row < L.out_f) {
-            if constexpr (ORDERED) {
-              // one K-part among several: add it to the row's fixed-point sum; else the row is this workgroup's alone
-              if (y64) __hip_atomic_fetch_add(&y64[row], to_fixed(yacc[s][t]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-              else __hip_atomic_store(&yo[row], yacc[s][t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            } else {
-              yo[row] = yacc[s][t];
-            }
-          }
+          if (row < L.out_f) yo[row] = yacc[s][t];
         }
       }
     }
@@ -489,7 +515,7 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd<SETS>()) void pmpd_stack_ke
   extern __shared__ uint4 lds[];
   const WorkItem it = items[blockIdx.x];
   const LayerDesc L = layers[it.layer];
-  run_tiles<B, SETS, NW, SPLITK>(L, it.tile0, x_from_fp16(x_base + static_cast<int64_t>(m) * L.x_off), m,
+  run_tiles<B, SETS, NW, SPLITK>(L, it.tile0, x_base + static_cast<int64_t>(m) * L.x_off, m,
                                  y_base + static_cast<int64_t>(m) * L.y_off, lds, KRange{0, L.n_groups, chunk_groups(L.n_groups, m)});
 }
 
@@ -498,7 +524,7 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd<SETS>()) void pmpd_layer_ke
                                                                                     const _Float16* __restrict__ x, int m,
                                                                                     float* __restrict__ y) {
   extern __shared__ uint4 lds[];
-  run_tiles<B, SETS, NW, SPLITK>(L, static_cast<int>(blockIdx.x) * (NW / SPLITK), x_from_fp16(x), m, y, lds,
+  run_tiles<B, SETS, NW, SPLITK>(L, static_cast<int>(blockIdx.x) * (NW / SPLITK), x, m, y, lds,
                                  KRange{0, L.n_groups, chunk_groups(L.n_groups, m)});
 }
 
@@ -506,140 +532,228 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd<SETS>()) void pmpd_layer_ke
 // Dependency-ordered step in one cooperative launch.  The layers of a step are grouped into
 // stages; a layer of stage s may take its input from the output of a layer of an earlier stage
 // (x = fp16(gain * y)).  The grid is persistent: for every stage each workgroup takes the items
-// blockIdx, blockIdx + gridDim, ... of that stage, issues the weight loads of its first item, and
-// only then waits until every workgroup has finished the previous stage: weights stream while the
-// barrier settles, x is read after it.
-// An item is one 64-row tile and one K-part of at least 8 groups (8: two groups per wave, all of
-// them in flight before the wait); the parts of a layer are as small as that allows while its
-// stage still has no more items than the chip holds workgroups, so that every stage, however few
-// rows it has, spreads over the whole chip in one round.  The K-parts of a row meet in a 64-bit
-// fixed-point sum (32 fractional bits) that every part adds to with an integer atomic: integer
-// addition is associative, so the result does not depend on the order of arrival, there are no
-// floating-point atomics, no buffers of partial sums, and nobody has to wait to be last.  Layers
-// chained to such a layer read the sums; y of those layers is written from them after the last
-// stage.  A layer with a single K-part writes y directly.
-// Only y and the sums cross workgroups; they are written and read with agent-scope accesses
-// (coherent across the chip's L2 slices), so the barrier needs no cache write-back or invalidate.  The launch is cooperative, so all workgroups are resident and the wait ends; it is
-// bounded all the same (spin_limit polls), and a wait that runs out only sets sync->timed_out.
-// Counters of the stage barrier.  Workgroup w adds to sub-counter w % 16 of the stage; the last
-// one of each sub-counter adds to the stage's top counter, and the last of those publishes the
-// stage number in the 32 copies of `stage_done`, the only words the waiting workgroups poll
-// (workgroup w reads copy w % 32): the polls (a thousand readers) and the arrivals (a thousand
-// read-modify-writes) never meet on one cache line, and no line has more than a few dozen readers.
-constexpr int kSyncLine = 64;   // uint32 per 256-byte line
-constexpr int kSubCounters = 16;
-constexpr int kFlagCopies = 32;  // copies of the polled word, one 256-byte line each: 32 times fewer readers per line
+// blockIdx, blockIdx + gridDim, ... of that stage.
+// An item is one 64-row tile and one K-part of at least 8 groups; the parts of a layer are as small
+// as that allows while its stage still has no more items than the chip holds workgroups, so that
+// every stage, however few rows it has, spreads over the whole chip in one round.
+// There is no barrier between stages.  Every output row is a 64-bit word that counts the K-parts
+// added to it (see part_word): an item waits for exactly the words it reads, the 128 * groups
+// outputs of the source layer that make up its K-part, and for nothing else, and a producer's
+// single atomic add both delivers its part and announces it.  The wait cannot deadlock: all
+// workgroups are resident (cooperative launch), each takes its items in stage order, and the
+// items of the lowest unfinished stage depend only on finished ones.  It is bounded all the same
+// (spin_limit rounds), and a wait that runs out only sets `timed_out`.
+// The words of the first two groups of every wave's quarter of an item's K-part are requested as
+// soon as the wave's part in the item before is over, so that the weights of stage s + 1 stream
+// while the results of stage s travel.  A wave's loads return in the order they were issued, so it
+// sees x only once its own weights are there; the product needs those anyway.
+// The sums are read with agent-scope loads (coherent across the chip's L2 slices); y is written
+// by whoever completes it: the producer itself where a layer has one K-part, a sweep over the
+// sums after the last stage otherwise.
 struct OrderedSync {
-  uint32_t stage_done[kFlagCopies * kSyncLine];  // [copy][0]: stages completed in this step (monotonic), polled
   uint32_t timed_out;
-  uint32_t pad1[kSyncLine - 1];
-  uint32_t counters[1];  // [n_stages][kSubCounters + 1][kSyncLine / 4] arrival counters, then [tiles] K-parts finished
 };
-constexpr int kStageCounterWords = (kSubCounters + 1) * (kSyncLine / 4);  // 16 uint32 (64 bytes) apart
 
 struct ChainDesc {
-  int64_t src_y_off;     // elements from y_base (or from the fixed-point sums) of the producing layer's output; -1: input from x_base
+  int64_t src_y_off;     // elements from the start of the sums of the producing layer's output; -1: input from x_base
   float gain;
-  int32_t n_parts;       // K-parts of part_groups groups each (the last one may be shorter); > 1: the parts meet in fixed point
+  int32_t n_parts;       // K-parts of part_groups groups each (the last one may be shorter)
   int32_t part_groups;
-  int32_t src_fixed;     // the producing layer has more than one K-part: read its fixed-point sums
+  int32_t src_parts;     // K-parts of the producing layer: its sums are complete when they count that many
 };
 
-// Wait until every vector memory operation of this wave, stores included, has been acknowledged
-// (s_waitcnt vmcnt(0); gfx9 encoding: vmcnt in bits 3:0 and 15:14, the other counters left at their
-// maxima).  For the agent-scope (write-through) stores used here that is when they are visible to
-// the other workgroups; a release fence would add a write-back of the whole L2 that nothing needs.
-__device__ __forceinline__ void wait_for_own_stores() { __builtin_amdgcn_s_waitcnt(0x0F70); }
-
-constexpr int kOrderedWaves = 4;
-constexpr int kOrderedPartGroups = 8;      // smallest K-part: two groups per wave, all in flight before the wait
+constexpr int kOrderedWaves = 4;           // one quarter of the K-part each
+constexpr int kOrderedThreads = kOrderedWaves * 64;
+constexpr int kOrderedWgPerCu = 4;         // 16 waves per compute unit, 128 registers each
+constexpr int kOrderedPartGroups = 8;      // smallest K-part: two groups per wave, all in registers before x is there
 constexpr int kOrderedMaxPartGroups = 32;  // largest K-part the LDS image is sized for
 constexpr int kItemPartShift = 20;  // WorkItem::tile0 = tile | part << 20
 
 template <int B>
-__global__ __launch_bounds__(kOrderedWaves * 64, 4) void pmpd_ordered_kernel(
+__global__ __launch_bounds__(kOrderedThreads, kOrderedWgPerCu) void pmpd_ordered_kernel(
     const LayerDesc* __restrict__ layers, const ChainDesc* __restrict__ chains, const WorkItem* __restrict__ items,
     const int32_t* __restrict__ stage_begin, int n_stages, const _Float16* __restrict__ x_base, float* __restrict__ y_base,
     unsigned long long* __restrict__ sums, OrderedSync* sync, uint32_t spin_limit, int n_layers) {
   extern __shared__ uint4 lds[];
   const uint32_t n_wg = gridDim.x;
-  uint32_t* arrived = sync->counters;  // + s * kStageCounterWords + k * 16
-  for (int s = 0; s < n_stages; ++s) {
-    bool waited = s == 0;
-    auto wait_for_previous_stage = [&]() {
-      if (waited) return;
-      waited = true;
-      if (threadIdx.x == 0) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const ImageLayout im(lds, kOrderedMaxPartGroups, 1);
+  const OperandOffsets<1> off(im, lane, 1);
+  const int wscale = weight_scale_register();
+
+  // The tables a stage needs (its item range, the workgroup's first item, that item's layer and
+  // chain records) are three dependent reads.  They are taken ahead of time, so that none of them
+  // sits between the end of one stage and the first weight loads of the next: at the top of
+  // stage s the records of stage s + 1, the item of stage s + 2 and the range end of stage s + 3
+  // are requested, each from values that arrived a stage earlier.  A request is one load per
+  // lane (lane k holds word k of the record), so a whole record waits in one vector register and
+  // is moved to scalar registers lane by lane when it is needed.
+  static_assert(sizeof(LayerDesc) == 18 * 4 && sizeof(ChainDesc) == 6 * 4, "records are read one 32-bit word per lane");
+  auto request_records = [&](int layer) {  // lanes 0..17: LayerDesc, lanes 32..37: ChainDesc
+    const uint32_t* pl = reinterpret_cast<const uint32_t*>(layers + (layer < 0 ? 0 : layer));
+    const uint32_t* pc = reinterpret_cast<const uint32_t*>(chains + (layer < 0 ? 0 : layer));
+    return lane < 32 ? pl[lane < 18 ? lane : 0] : pc[lane < 38 ? lane - 32 : 0];
+  };
+  auto request_item = [&](int b_lo, int b_hi, int range_index) {  // lanes 0, 1: the item; lanes 2..: stage_begin[range_index]
+    const int i = b_lo + static_cast<int>(blockIdx.x);
+    const uint32_t* pi = reinterpret_cast<const uint32_t*>(items + (i < b_hi ? i : 0));
+    const uint32_t* pb = reinterpret_cast<const uint32_t*>(stage_begin + (range_index < n_stages ? range_index : n_stages));
+    return lane < 2 ? pi[lane] : pb[0];
+  };
+  auto word = [](uint32_t v, int k) { return static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(v), k)); };
+  auto take_records = [&](uint32_t records, LayerDesc& L, ChainDesc& c) {
+    uint32_t w[18], v[6];
+#pragma unroll
+    for (int k = 0; k < 18; ++k) w[k] = word(records, k);
+#pragma unroll
+    for (int k = 0; k < 6; ++k) v[k] = word(records, 32 + k);
+    __builtin_memcpy(&L, w, sizeof(L));
+    __builtin_memcpy(&c, v, sizeof(c));
+  };
+  auto begin_of = [&](int s) { return stage_begin[s < n_stages ? s : n_stages]; };
+  auto first_item = [&](int b_lo, int b_hi) {
+    const int i = b_lo + static_cast<int>(blockIdx.x);
+    return i < b_hi ? items[i] : WorkItem{-1, 0};
+  };
+
+  // The K-part of an item, and the quarter of it this wave multiplies.
+  struct Range {
+    int g0, g1;
+  };
+  auto part_of = [](const WorkItem& wi, const LayerDesc& Li, const ChainDesc& ci) {
+    const int p0 = (wi.tile0 >> kItemPartShift) * ci.part_groups;
+    return Range{p0, p0 + ci.part_groups < Li.n_groups ? p0 + ci.part_groups : Li.n_groups};
+  };
+  auto quarter_of = [&](const Range& p) {
+    const int cn = p.g1 - p.g0;
+    return Range{p.g0 + cn * wave / kOrderedWaves, p.g0 + cn * (wave + 1) / kOrderedWaves};
+  };
+  // The words of the first two groups of this wave's quarter, on their way from the moment the
+  // wave's part in the item before is over.
+  u32x4 pa[B], pb[B], sa_a = {0, 0, 0, 0}, sa_b = {0, 0, 0, 0};
+  auto request_weights = [&](const WorkItem& wi, const LayerDesc& Li, const ChainDesc& ci) {
+    if (wi.layer < 0) return;
+    const Range q = quarter_of(part_of(wi, Li, ci));
+    if (q.g0 >= q.g1) return;
+    const TileWords<B> tw(Li, wi.tile0 & ((1 << kItemPartShift) - 1), lane);
+    tw.load(pa, sa_a, q.g0);
+    if (q.g0 + 1 < q.g1) tw.load(pb, sa_b, q.g0 + 1);
+  };
+  // One item.  Barriers: every wave has consumed the image of the item before, and the sums this
+  // item reads have been seen complete once; the image of x is complete; the four partial sums are
+  // in LDS.  Wave 0 adds them and delivers the rows.
+  auto run_item = [&](const WorkItem& wi, const LayerDesc& Li, const ChainDesc& ci) {
+    const int tile = wi.tile0 & ((1 << kItemPartShift) - 1);
+    const Range part = part_of(wi, Li, ci);
+    XSource src = x_from_fp16(x_base + Li.x_off);
+    if (ci.src_y_off >= 0) {
+      src = XSource{nullptr, sums + ci.src_y_off, ci.gain, ci.src_parts, spin_limit, &sync->timed_out};
+      // One thread per 64 source rows polls the first of them: few readers while the producers are
+      // still at work.  The other rows follow within a fraction of a microsecond, and every word is
+      // checked again where it is read.
+      const int n_rows = (part.g1 - part.g0) * kGroup;
+      for (int r = threadIdx.x * 64; r < n_rows; r += kOrderedThreads * 64) {
+        const unsigned long long* w = src.y64 + part.g0 * kGroup + r;
         uint32_t polls = 0;
-        while (__hip_atomic_load(&sync->stage_done[(blockIdx.x % kFlagCopies) * kSyncLine], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) <
-               static_cast<uint32_t>(s)) {
+        while (!sum_complete(__hip_atomic_load(w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), ci.src_parts)) {
           if (++polls >= spin_limit) {
             __hip_atomic_store(&sync->timed_out, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             break;
           }
-          __builtin_amdgcn_s_sleep(32);  // about a microsecond between polls (a thousand readers of one word); shorter intervals measured no faster
+          __builtin_amdgcn_s_sleep(8);
         }
       }
-      __syncthreads();
-    };
-    for (int i = stage_begin[s] + static_cast<int>(blockIdx.x); i < stage_begin[s + 1]; i += static_cast<int>(n_wg)) {
-      const WorkItem it = items[i];
-      const LayerDesc L = layers[it.layer];
-      const ChainDesc c = chains[it.layer];
-      const int tile = it.tile0 & ((1 << kItemPartShift) - 1), part = it.tile0 >> kItemPartShift;
-      const XSource src = c.src_y_off < 0 ? x_from_fp16(x_base + L.x_off)
-                          : c.src_fixed   ? XSource{nullptr, nullptr, sums + c.src_y_off, c.gain}
-                                          : XSource{nullptr, y_base + c.src_y_off, nullptr, c.gain};
-      const int g0 = part * c.part_groups;
-      const int g1 = g0 + c.part_groups < L.n_groups ? g0 + c.part_groups : L.n_groups;
-      // a layer with one K-part writes y itself; the parts of the others add to the rows' fixed-point sums
-      run_tiles<B, 1, kOrderedWaves, kOrderedWaves, true>(L, tile, src, 1, y_base + L.y_off, lds, KRange{g0, g1, kOrderedMaxPartGroups},
-                                                         wait_for_previous_stage, c.n_parts > 1 ? sums + L.y_off : nullptr);
-      __syncthreads();  // the LDS image is reused by the next item
     }
-    // every wave waits until its own (write-through) stores and atomic adds of stage s are acknowledged, then
-    // the workgroup is counted
-    wait_for_own_stores();
     __syncthreads();
-    if (threadIdx.x == 0) {
-      const uint32_t k = blockIdx.x % kSubCounters;
-      const uint32_t in_sub = (n_wg - k + kSubCounters - 1) / kSubCounters;  // workgroups that share sub-counter k
-      uint32_t* cnt = arrived + s * kStageCounterWords;
-      if (__hip_atomic_fetch_add(&cnt[k * 16], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1 == in_sub) {
-        const uint32_t n_sub = n_wg < kSubCounters ? n_wg : kSubCounters;
-        if (__hip_atomic_fetch_add(&cnt[kSubCounters * 16], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1 == n_sub)
-          for (int q = 0; q < kFlagCopies; ++q)
-            __hip_atomic_store(&sync->stage_done[q * kSyncLine], static_cast<uint32_t>(s + 1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    stage_x<kOrderedThreads>(src, part.g0, part.g1 - part.g0, im, 0, threadIdx.x);
+    __syncthreads();
+    float yacc[1][4] = {{0.f, 0.f, 0.f, 0.f}};
+    const Range q = quarter_of(part);
+    if (q.g0 < q.g1) {
+      const TileWords<B> tw(Li, tile, lane);
+      for (int gc = q.g0; gc < q.g1; gc += 2) {
+        if (gc > q.g0 && gc + 1 < q.g1) tw.load(pb, sa_b, gc + 1);
+        consume_group<B, 1>(im, off, gc - part.g0, pa, sa_a, wscale, yacc);
+        if (gc + 2 < q.g1) tw.load(pa, sa_a, gc + 2);
+        if (gc + 1 < q.g1) consume_group<B, 1>(im, off, gc + 1 - part.g0, pb, sa_b, wscale, yacc);
       }
     }
-  }
-  // After the last stage: y of the layers whose K-parts met in fixed point (the same conversion the
-  // chained layers used when they read those sums).
-  if (threadIdx.x == 0) {
-    uint32_t polls = 0;
-    while (__hip_atomic_load(&sync->stage_done[(blockIdx.x % kFlagCopies) * kSyncLine], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) <
-           static_cast<uint32_t>(n_stages)) {
-      if (++polls >= spin_limit) {
-        __hip_atomic_store(&sync->timed_out, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        break;
-      }
-      __builtin_amdgcn_s_sleep(32);
+    // the two classes sit 16 lanes apart: add them (fixed order: A + B)
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const float other = __shfl_xor(yacc[0][t], 16);
+      yacc[0][t] = (lane & 16) ? other + yacc[0][t] : yacc[0][t] + other;
+      if (wave != 0) im.red[(t * kOrderedWaves + wave) * 64 + lane] = yacc[0][t];
     }
+    __syncthreads();
+    if (wave == 0 && lane < 16) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        float sum = yacc[0][t];
+#pragma unroll
+        for (int k = 1; k < kOrderedWaves; ++k) sum += im.red[(t * kOrderedWaves + k) * 64 + lane];
+        const int row = tile * 64 + 16 * t + lane;
+        if (row < Li.out_f) {
+          if (ci.n_parts > 1) {
+            __hip_atomic_fetch_add(&sums[Li.y_off + row], part_word(sum), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          } else {  // the row is this workgroup's alone
+            y_base[Li.y_off + row] = sum;
+            __hip_atomic_store(&sums[Li.y_off + row], whole_word(sum), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
+        }
+      }
+    }
+  };
+
+  int b0 = begin_of(0), b1 = begin_of(1), b2 = begin_of(2), b3 = begin_of(3);
+  WorkItem it = first_item(b0, b1), it_next = first_item(b1, b2);
+  LayerDesc L;
+  ChainDesc c;
+  take_records(request_records(it.layer), L, c);
+  request_weights(it, L, c);
+  for (int s = 0; s < n_stages; ++s) {
+    const uint32_t records = request_records(it_next.layer);
+    const bool has_after = b2 + static_cast<int>(blockIdx.x) < b3;
+    const uint32_t after = request_item(b2, b3, s + 4);
+    if (it.layer >= 0) run_item(it, L, c);
+    // a stage with more items than the grid has workgroups: the further rounds read their tables in place
+    for (int i = b0 + static_cast<int>(blockIdx.x + n_wg); i < b1; i += static_cast<int>(n_wg)) {
+      const WorkItem wi = items[i];
+      const LayerDesc Li = layers[wi.layer];
+      const ChainDesc ci = chains[wi.layer];
+      request_weights(wi, Li, ci);
+      run_item(wi, Li, ci);
+    }
+    it = it_next;
+    it_next = has_after ? WorkItem{static_cast<int32_t>(word(after, 0)), static_cast<int32_t>(word(after, 1))} : WorkItem{-1, 0};
+    b0 = b1, b1 = b2, b2 = b3, b3 = static_cast<int>(word(after, 2));
+    take_records(records, L, c);
+    request_weights(it, L, c);
   }
-  __syncthreads();
+  // y of the layers with several K-parts, from their sums as they become complete.
   for (int li = 0; li < n_layers; ++li) {
-    if (chains[li].n_parts <= 1) continue;
-    const LayerDesc& L = layers[li];
-    for (int row = blockIdx.x * blockDim.x + threadIdx.x; row < L.out_f; row += gridDim.x * blockDim.x)
-      y_base[L.y_off + row] = fixed_to_float(__hip_atomic_load(sums + L.y_off + row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    const int n_parts = chains[li].n_parts;
+    if (n_parts <= 1) continue;
+    const LayerDesc& Ld = layers[li];
+    for (int row = blockIdx.x * blockDim.x + threadIdx.x; row < Ld.out_f; row += gridDim.x * blockDim.x) {
+      unsigned long long w = __hip_atomic_load(sums + Ld.y_off + row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      for (uint32_t polls = 0; !sum_complete(w, n_parts);) {
+        if (++polls >= spin_limit) {
+          __hip_atomic_store(&sync->timed_out, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          break;
+        }
+        __builtin_amdgcn_s_sleep(16);
+        w = __hip_atomic_load(sums + Ld.y_off + row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      y_base[Ld.y_off + row] = sum_value(w, n_parts);
+    }
   }
 }
 
-__global__ void pmpd_ordered_reset_kernel(OrderedSync* sync, int n_counters, unsigned long long* sums, int64_t n_sums) {
+__global__ void pmpd_ordered_reset_kernel(unsigned long long* sums, int64_t n_sums) {
   const int64_t tid = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x, n_threads = static_cast<int64_t>(gridDim.x) * blockDim.x;
-  for (int64_t i = tid; i < n_counters; i += n_threads) sync->counters[i] = 0;
   for (int64_t i = tid; i < n_sums; i += n_threads) sums[i] = 0;
-  if (blockIdx.x == 0 && threadIdx.x < kFlagCopies) sync->stage_done[threadIdx.x * kSyncLine] = 0;
 }
 
 // Read-only stream over a buffer: the HBM ceiling the decode kernels are held against.  Each
@@ -885,7 +999,6 @@ struct pmpd_ordered {
   OrderedSync* d_sync = nullptr;
   unsigned long long* d_sums = nullptr;  // fixed-point row sums, laid out like y
   int64_t n_sums = 0;
-  int n_counters = 0;
   int n_stages = 0;
   int max_stage_items = 0;
   uint32_t spin_limit = 1u << 20;
@@ -911,7 +1024,8 @@ static int32_t check_chain(const pmpd_stack* st, const pmpd_chain_t* chain, int*
 }
 
 // K-part size (in groups) of every layer: as close to kOrderedPartGroups as keeps the items of the
-// layer's stage within `slots` workgroups, never above kOrderedMaxPartGroups.
+// layer's stage within `slots` workgroups, never above kOrderedMaxPartGroups (rows of up to 32768
+// features then have at most 8 parts).
 static std::vector<int> ordered_part_groups(const pmpd_stack* st, const pmpd_chain_t* chain, int n_stages, int slots) {
   std::vector<int64_t> stage_tiles(static_cast<size_t>(n_stages), 0);
   for (size_t i = 0; i < st->layers.size(); ++i) stage_tiles[static_cast<size_t>(chain[i].stage)] += st->layers[i].n_tiles;
@@ -920,6 +1034,7 @@ static std::vector<int> ordered_part_groups(const pmpd_stack* st, const pmpd_cha
     const int G = st->layers[i].n_groups;
     const int64_t tiles = std::max<int64_t>(1, stage_tiles[static_cast<size_t>(chain[i].stage)]);
     int parts = static_cast<int>(std::max<int64_t>(1, std::min<int64_t>((G + kOrderedPartGroups - 1) / kOrderedPartGroups, slots / tiles)));
+    parts = std::min(parts, kMaxParts);  // what the count bits of a sum can hold
     int groups = (G + parts - 1) / parts;
     groups = std::min(groups, kOrderedMaxPartGroups);
     pg[i] = groups;
@@ -939,12 +1054,13 @@ static void ordered_counts(const pmpd_stack* st, const std::vector<int>& pg, siz
   }
 }
 
-// Workgroup slots the ordered kernel is planned for: four workgroups of four waves per compute unit.
+// Workgroup slots the ordered kernel is planned for: kOrderedWgPerCu workgroups per compute unit.
 static int ordered_slots() {
   int dev = 0;
   hipDeviceProp_t prop;
-  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess || prop.multiProcessorCount < 1) return 1024;
-  return 4 * prop.multiProcessorCount;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess || prop.multiProcessorCount < 1)
+    return kOrderedWgPerCu * 256;
+  return kOrderedWgPerCu * prop.multiProcessorCount;
 }
 
 static size_t ordered_bytes(const pmpd_stack* st, const std::vector<int>& pg, size_t n_stages) {
@@ -952,7 +1068,7 @@ static size_t ordered_bytes(const pmpd_stack* st, const std::vector<int>& pg, si
   ordered_counts(st, pg, &n_items, &n_sums);
   return align_up(st->layers.size() * sizeof(ChainDesc), 256) + align_up(n_items * sizeof(WorkItem), 256) +
          align_up((n_stages + 1) * sizeof(int32_t), 256) +
-         align_up(sizeof(OrderedSync) + n_stages * kStageCounterWords * sizeof(uint32_t), 256) +
+         align_up(sizeof(OrderedSync), 256) +
          align_up(n_sums * sizeof(unsigned long long), 256);
 }
 
@@ -961,14 +1077,14 @@ static hipError_t launch_ordered(const pmpd_ordered* o, const void* x, float* y,
   const pmpd_stack* st = o->stack;
   const size_t lds = lds_bytes(kOrderedMaxPartGroups, 1, kOrderedWaves, 4);
   int per_cu = 0, dev = 0;
-  hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, pmpd_ordered_kernel<B>, kOrderedWaves * 64, lds);
+  hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, pmpd_ordered_kernel<B>, kOrderedThreads, lds);
   if (e != hipSuccess) return e;
   hipDeviceProp_t prop;
   if ((e = hipGetDevice(&dev)) != hipSuccess || (e = hipGetDeviceProperties(&prop, dev)) != hipSuccess) return e;
-  int grid = std::min(per_cu, 4) * prop.multiProcessorCount;
+  int grid = std::min(per_cu, kOrderedWgPerCu) * prop.multiProcessorCount;
   if (grid < 1) return hipErrorCooperativeLaunchTooLarge;
   grid = std::min(grid, o->max_stage_items);
-  hipLaunchKernelGGL(pmpd_ordered_reset_kernel, dim3(1024), dim3(256), 0, s, o->d_sync, o->n_counters, o->d_sums, o->n_sums);
+  hipLaunchKernelGGL(pmpd_ordered_reset_kernel, dim3(1024), dim3(256), 0, s, o->d_sums, o->n_sums);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   const LayerDesc* layers = st->d_layers;
   const _Float16* xb = static_cast<const _Float16*>(x);
@@ -978,7 +1094,7 @@ static hipError_t launch_ordered(const pmpd_ordered* o, const void* x, float* y,
   void* args[] = {&layers, const_cast<ChainDesc**>(&o->d_chains), const_cast<WorkItem**>(&o->d_items),
                   const_cast<int32_t**>(&o->d_stage_begin), &n_stages, &xb, &y, const_cast<unsigned long long**>(&o->d_sums),
                   const_cast<OrderedSync**>(&o->d_sync), &spin, &n_layers};
-  return hipLaunchCooperativeKernel(reinterpret_cast<const void*>(&pmpd_ordered_kernel<B>), dim3(grid), dim3(kOrderedWaves * 64),
+  return hipLaunchCooperativeKernel(reinterpret_cast<const void*>(&pmpd_ordered_kernel<B>), dim3(grid), dim3(kOrderedThreads),
                                     args, static_cast<unsigned>(lds), s);
 }
 
@@ -1010,7 +1126,6 @@ int32_t pmpd_ordered_create(const pmpd_stack_t* stack, const pmpd_chain_t* chain
   auto* o = new pmpd_ordered;
   o->stack = stack;
   o->n_stages = n_stages;
-  o->n_counters = static_cast<int>(static_cast<size_t>(n_stages) * kStageCounterWords);
   o->n_sums = static_cast<int64_t>(n_sums);
   for (size_t i = 0; i < n_layers; ++i) {
     const LayerDesc& d = stack->layers[i];
@@ -1020,8 +1135,8 @@ int32_t pmpd_ordered_create(const pmpd_stack_t* stack, const pmpd_chain_t* chain
       delete o;
       return fail(PMPD_EINVAL, "pmpd_ordered_create: layer %zu is too large for the item encoding", i);
     }
-    const int src_fixed = src >= 0 && parts_of(stack->layers[src].n_groups, pg[src]) > 1;
-    o->chains.push_back(ChainDesc{src < 0 ? int64_t{-1} : stack->layers[src].y_off, chain[i].gain, parts, pg[i], src_fixed});
+    const int src_parts = src >= 0 ? parts_of(stack->layers[src].n_groups, pg[src]) : 0;
+    o->chains.push_back(ChainDesc{src < 0 ? int64_t{-1} : stack->layers[src].y_off, chain[i].gain, parts, pg[i], src_parts});
   }
   // (tile, K-part) items, stage by stage; inside a stage long rows first
   std::vector<int> order(n_layers);
@@ -1052,7 +1167,7 @@ int32_t pmpd_ordered_create(const pmpd_stack_t* stack, const pmpd_chain_t* chain
   o->d_stage_begin = reinterpret_cast<const int32_t*>(w);
   w += align_up(o->stage_begin.size() * sizeof(int32_t), 256);
   o->d_sync = reinterpret_cast<OrderedSync*>(w);
-  const size_t sync_bytes = sizeof(OrderedSync) + static_cast<size_t>(n_stages) * kStageCounterWords * sizeof(uint32_t);
+  const size_t sync_bytes = sizeof(OrderedSync);
   if (e == hipSuccess) e = hipMemset(w, 0, sync_bytes);
   w += align_up(sync_bytes, 256);
   o->d_sums = reinterpret_cast<unsigned long long*>(w);

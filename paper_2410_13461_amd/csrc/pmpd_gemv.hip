@@ -531,21 +531,23 @@ __global__ __launch_bounds__(NW * 64, waves_per_simd<SETS>()) void pmpd_layer_ke
 // =====================================================================================
 // Dependency-ordered step in one cooperative launch.  The layers of a step are grouped into
 // stages; a layer of stage s may take its input from the output of a layer of an earlier stage
-// (x = fp16(gain * y)).  The grid is persistent: for every stage each workgroup takes the items
-// blockIdx, blockIdx + gridDim, ... of that stage.
-// An item is one 64-row tile and one K-part of at least 8 groups; the parts of a layer are as small
-// as that allows while its stage still has no more items than the chip holds workgroups, so that
-// every stage, however few rows it has, spreads over the whole chip in one round.
+// (x = fp16(gain * y)).  An item is one 64-row tile and one K-part of at least 8 groups (8: two
+// groups per wave, all of an item's weights in registers before its x is there); the parts of a
+// layer are as small as that allows while its stage still has no more items than the chip holds
+// workgroups, so that every stage, however few rows it has, spreads over the whole chip in one
+// round.  The items of the step form one list in stage order; the grid is persistent and
+// workgroup w takes items w, w + gridDim, ... of it: the deal goes on across stage ends, so the
+// workgroups a short stage leaves out are already waiting, weights loaded, for the stage after.
 // There is no barrier between stages.  Every output row is a 64-bit word that counts the K-parts
 // added to it (see part_word): an item waits for exactly the words it reads, the 128 * groups
 // outputs of the source layer that make up its K-part, and for nothing else, and a producer's
 // single atomic add both delivers its part and announces it.  The wait cannot deadlock: all
-// workgroups are resident (cooperative launch), each takes its items in stage order, and the
-// items of the lowest unfinished stage depend only on finished ones.  It is bounded all the same
+// workgroups are resident (cooperative launch), each takes its items in list order, and the
+// first unfinished item of the list depends only on finished ones.  It is bounded all the same
 // (spin_limit rounds), and a wait that runs out only sets `timed_out`.
 // The words of the first two groups of every wave's quarter of an item's K-part are requested as
-// soon as the wave's part in the item before is over, so that the weights of stage s + 1 stream
-// while the results of stage s travel.  A wave's loads return in the order they were issued, so it
+// soon as the wave's part in the item before is over, so that the weights of the next stage stream
+// while the results of this one travel.  A wave's loads return in the order they were issued, so it
 // sees x only once its own weights are there; the product needs those anyway.
 // The sums are read with agent-scope loads (coherent across the chip's L2 slices); y is written
 // by whoever completes it: the producer itself where a layer has one K-part, a sweep over the
@@ -572,8 +574,8 @@ constexpr int kItemPartShift = 20;  // WorkItem::tile0 = tile | part << 20
 template <int B>
 __global__ __launch_bounds__(kOrderedThreads, kOrderedWgPerCu) void pmpd_ordered_kernel(
     const LayerDesc* __restrict__ layers, const ChainDesc* __restrict__ chains, const WorkItem* __restrict__ items,
-    const int32_t* __restrict__ stage_begin, int n_stages, const _Float16* __restrict__ x_base, float* __restrict__ y_base,
-    unsigned long long* __restrict__ sums, OrderedSync* sync, uint32_t spin_limit, int n_layers) {
+    int n_items, const _Float16* __restrict__ x_base, float* __restrict__ y_base, unsigned long long* __restrict__ sums,
+    OrderedSync* sync, uint32_t spin_limit, int n_layers) {
   extern __shared__ uint4 lds[];
   const uint32_t n_wg = gridDim.x;
   const int lane = threadIdx.x & 63;
@@ -582,24 +584,20 @@ __global__ __launch_bounds__(kOrderedThreads, kOrderedWgPerCu) void pmpd_ordered
   const OperandOffsets<1> off(im, lane, 1);
   const int wscale = weight_scale_register();
 
-  // The tables a stage needs (its item range, the workgroup's first item, that item's layer and
-  // chain records) are three dependent reads.  They are taken ahead of time, so that none of them
-  // sits between the end of one stage and the first weight loads of the next: at the top of
-  // stage s the records of stage s + 1, the item of stage s + 2 and the range end of stage s + 3
-  // are requested, each from values that arrived a stage earlier.  A request is one load per
-  // lane (lane k holds word k of the record), so a whole record waits in one vector register and
-  // is moved to scalar registers lane by lane when it is needed.
+  // The tables an item needs (the item, then its layer and chain records) are two dependent reads.
+  // They are taken ahead of time, so that neither sits between the end of one item and the first
+  // weight loads of the next: while an item runs, the records of the next and the item after that
+  // are requested, each from values that arrived an item earlier.  A request is one load per lane
+  // (lane k holds word k of the record), so a whole record waits in one vector register and is
+  // moved to scalar registers lane by lane when it is needed.
   static_assert(sizeof(LayerDesc) == 18 * 4 && sizeof(ChainDesc) == 6 * 4, "records are read one 32-bit word per lane");
   auto request_records = [&](int layer) {  // lanes 0..17: LayerDesc, lanes 32..37: ChainDesc
     const uint32_t* pl = reinterpret_cast<const uint32_t*>(layers + (layer < 0 ? 0 : layer));
     const uint32_t* pc = reinterpret_cast<const uint32_t*>(chains + (layer < 0 ? 0 : layer));
     return lane < 32 ? pl[lane < 18 ? lane : 0] : pc[lane < 38 ? lane - 32 : 0];
   };
-  auto request_item = [&](int b_lo, int b_hi, int range_index) {  // lanes 0, 1: the item; lanes 2..: stage_begin[range_index]
-    const int i = b_lo + static_cast<int>(blockIdx.x);
-    const uint32_t* pi = reinterpret_cast<const uint32_t*>(items + (i < b_hi ? i : 0));
-    const uint32_t* pb = reinterpret_cast<const uint32_t*>(stage_begin + (range_index < n_stages ? range_index : n_stages));
-    return lane < 2 ? pi[lane] : pb[0];
+  auto request_item = [&](int i) {  // lanes 0, 1
+    return reinterpret_cast<const uint32_t*>(items + (i < n_items ? i : 0))[lane & 1];
   };
   auto word = [](uint32_t v, int k) { return static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(v), k)); };
   auto take_records = [&](uint32_t records, LayerDesc& L, ChainDesc& c) {
@@ -611,12 +609,6 @@ __global__ __launch_bounds__(kOrderedThreads, kOrderedWgPerCu) void pmpd_ordered
     __builtin_memcpy(&L, w, sizeof(L));
     __builtin_memcpy(&c, v, sizeof(c));
   };
-  auto begin_of = [&](int s) { return stage_begin[s < n_stages ? s : n_stages]; };
-  auto first_item = [&](int b_lo, int b_hi) {
-    const int i = b_lo + static_cast<int>(blockIdx.x);
-    return i < b_hi ? items[i] : WorkItem{-1, 0};
-  };
-
   // The K-part of an item, and the quarter of it this wave multiplies.
   struct Range {
     int g0, g1;
@@ -661,7 +653,7 @@ __global__ __launch_bounds__(kOrderedThreads, kOrderedWgPerCu) void pmpd_ordered
             __hip_atomic_store(&sync->timed_out, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             break;
           }
-          __builtin_amdgcn_s_sleep(8);
+          __builtin_amdgcn_s_sleep(16);
         }
       }
     }
@@ -706,28 +698,19 @@ __global__ __launch_bounds__(kOrderedThreads, kOrderedWgPerCu) void pmpd_ordered
     }
   };
 
-  int b0 = begin_of(0), b1 = begin_of(1), b2 = begin_of(2), b3 = begin_of(3);
-  WorkItem it = first_item(b0, b1), it_next = first_item(b1, b2);
+  const int first = static_cast<int>(blockIdx.x), step = static_cast<int>(n_wg);
+  WorkItem it = first < n_items ? items[first] : WorkItem{-1, 0};
+  WorkItem it_next = first + step < n_items ? items[first + step] : WorkItem{-1, 0};
   LayerDesc L;
   ChainDesc c;
   take_records(request_records(it.layer), L, c);
   request_weights(it, L, c);
-  for (int s = 0; s < n_stages; ++s) {
+  for (int i = first; i < n_items; i += step) {
     const uint32_t records = request_records(it_next.layer);
-    const bool has_after = b2 + static_cast<int>(blockIdx.x) < b3;
-    const uint32_t after = request_item(b2, b3, s + 4);
+    const uint32_t after = request_item(i + 2 * step);
     if (it.layer >= 0) run_item(it, L, c);
-    // a stage with more items than the grid has workgroups: the further rounds read their tables in place
-    for (int i = b0 + static_cast<int>(blockIdx.x + n_wg); i < b1; i += static_cast<int>(n_wg)) {
-      const WorkItem wi = items[i];
-      const LayerDesc Li = layers[wi.layer];
-      const ChainDesc ci = chains[wi.layer];
-      request_weights(wi, Li, ci);
-      run_item(wi, Li, ci);
-    }
     it = it_next;
-    it_next = has_after ? WorkItem{static_cast<int32_t>(word(after, 0)), static_cast<int32_t>(word(after, 1))} : WorkItem{-1, 0};
-    b0 = b1, b1 = b2, b2 = b3, b3 = static_cast<int>(word(after, 2));
+    it_next = i + 2 * step < n_items ? WorkItem{static_cast<int32_t>(word(after, 0)), static_cast<int32_t>(word(after, 1))} : WorkItem{-1, 0};
     take_records(records, L, c);
     request_weights(it, L, c);
   }
@@ -992,15 +975,12 @@ struct pmpd_ordered {
   const pmpd_stack* stack = nullptr;
   std::vector<ChainDesc> chains;
   std::vector<WorkItem> items;
-  std::vector<int32_t> stage_begin;
   const ChainDesc* d_chains = nullptr;
   const WorkItem* d_items = nullptr;
-  const int32_t* d_stage_begin = nullptr;
   OrderedSync* d_sync = nullptr;
   unsigned long long* d_sums = nullptr;  // fixed-point row sums, laid out like y
   int64_t n_sums = 0;
-  int n_stages = 0;
-  int max_stage_items = 0;
+  int grid = 0;  // workgroups of the launch: what the chip holds at once, or one per item if that is fewer
   uint32_t spin_limit = 1u << 20;
 };
 
@@ -1024,8 +1004,8 @@ static int32_t check_chain(const pmpd_stack* st, const pmpd_chain_t* chain, int*
 }
 
 // K-part size (in groups) of every layer: as close to kOrderedPartGroups as keeps the items of the
-// layer's stage within `slots` workgroups, never above kOrderedMaxPartGroups (rows of up to 32768
-// features then have at most 8 parts).
+// layer's stage within `slots` workgroups (a stage that takes two items of some workgroups takes
+// twice as long to deliver), and a row within kMaxParts parts; never above kOrderedMaxPartGroups.
 static std::vector<int> ordered_part_groups(const pmpd_stack* st, const pmpd_chain_t* chain, int n_stages, int slots) {
   std::vector<int64_t> stage_tiles(static_cast<size_t>(n_stages), 0);
   for (size_t i = 0; i < st->layers.size(); ++i) stage_tiles[static_cast<size_t>(chain[i].stage)] += st->layers[i].n_tiles;
@@ -1035,26 +1015,12 @@ static std::vector<int> ordered_part_groups(const pmpd_stack* st, const pmpd_cha
     const int64_t tiles = std::max<int64_t>(1, stage_tiles[static_cast<size_t>(chain[i].stage)]);
     int parts = static_cast<int>(std::max<int64_t>(1, std::min<int64_t>((G + kOrderedPartGroups - 1) / kOrderedPartGroups, slots / tiles)));
     parts = std::min(parts, kMaxParts);  // what the count bits of a sum can hold
-    int groups = (G + parts - 1) / parts;
-    groups = std::min(groups, kOrderedMaxPartGroups);
-    pg[i] = groups;
+    pg[i] = std::min((G + parts - 1) / parts, kOrderedMaxPartGroups);
   }
   return pg;
 }
 
-static int parts_of(int n_groups, int part_groups) { return (n_groups + part_groups - 1) / part_groups; }
-
-// items an ordered step of this stack needs, and the length of its y (= of the fixed-point sums)
-static void ordered_counts(const pmpd_stack* st, const std::vector<int>& pg, size_t* n_items, size_t* n_sums) {
-  *n_items = *n_sums = 0;
-  for (size_t i = 0; i < st->layers.size(); ++i) {
-    const LayerDesc& d = st->layers[i];
-    *n_items += static_cast<size_t>(d.n_tiles) * static_cast<size_t>(parts_of(d.n_groups, pg[i]));
-    *n_sums = std::max(*n_sums, static_cast<size_t>(d.y_off) + static_cast<size_t>(d.out_f));
-  }
-}
-
-// Workgroup slots the ordered kernel is planned for: kOrderedWgPerCu workgroups per compute unit.
+// Workgroup slots the parts are planned for: kOrderedWgPerCu workgroups per compute unit.
 static int ordered_slots() {
   int dev = 0;
   hipDeviceProp_t prop;
@@ -1063,38 +1029,63 @@ static int ordered_slots() {
   return kOrderedWgPerCu * prop.multiProcessorCount;
 }
 
-static size_t ordered_bytes(const pmpd_stack* st, const std::vector<int>& pg, size_t n_stages) {
-  size_t n_items, n_sums;
-  ordered_counts(st, pg, &n_items, &n_sums);
-  return align_up(st->layers.size() * sizeof(ChainDesc), 256) + align_up(n_items * sizeof(WorkItem), 256) +
-         align_up((n_stages + 1) * sizeof(int32_t), 256) +
-         align_up(sizeof(OrderedSync), 256) +
-         align_up(n_sums * sizeof(unsigned long long), 256);
+static int parts_of(int n_groups, int part_groups) { return (n_groups + part_groups - 1) / part_groups; }
+
+// Items of an ordered step (per stage and in all) and the length of its y (= of the sums).
+struct OrderedCounts {
+  std::vector<size_t> stage_items;
+  size_t n_items = 0, max_stage_items = 0, n_sums = 0;
+};
+static OrderedCounts ordered_counts(const pmpd_stack* st, const pmpd_chain_t* chain, int n_stages, const std::vector<int>& pg) {
+  OrderedCounts c;
+  c.stage_items.assign(static_cast<size_t>(n_stages), 0);
+  for (size_t i = 0; i < st->layers.size(); ++i) {
+    const LayerDesc& d = st->layers[i];
+    const size_t n = static_cast<size_t>(d.n_tiles) * static_cast<size_t>(parts_of(d.n_groups, pg[i]));
+    c.stage_items[static_cast<size_t>(chain[i].stage)] += n;
+    c.n_items += n;
+    c.n_sums = std::max(c.n_sums, static_cast<size_t>(d.y_off) + static_cast<size_t>(d.out_f));
+  }
+  for (size_t n : c.stage_items) c.max_stage_items = std::max(c.max_stage_items, n);
+  return c;
+}
+
+// Workgroups of the kernel for bit-width B that the device holds at once.
+template <int B>
+static hipError_t ordered_capacity(int* slots) {
+  int per_cu = 0, dev = 0;
+  hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, pmpd_ordered_kernel<B>, kOrderedThreads,
+                                                              lds_bytes(kOrderedMaxPartGroups, 1, kOrderedWaves, 4));
+  hipDeviceProp_t prop;
+  if (e != hipSuccess || (e = hipGetDevice(&dev)) != hipSuccess || (e = hipGetDeviceProperties(&prop, dev)) != hipSuccess) return e;
+  *slots = std::min(per_cu, kOrderedWgPerCu) * prop.multiProcessorCount;
+  return hipSuccess;
+}
+
+// The item list gives every stage a whole number of rounds of the grid (empty items fill up), so
+// that workgroup w meets item w of every stage.  `grid_bound`: the largest grid the list may be built for.
+static size_t ordered_bytes(const pmpd_stack* st, const OrderedCounts& c, size_t grid_bound) {
+  const size_t list_bound = c.n_items + c.stage_items.size() * std::min(grid_bound, std::max<size_t>(1, c.max_stage_items));
+  return align_up(st->layers.size() * sizeof(ChainDesc), 256) + align_up(list_bound * sizeof(WorkItem), 256) +
+         align_up(sizeof(OrderedSync), 256) + align_up(c.n_sums * sizeof(unsigned long long), 256);
 }
 
 template <int B>
 static hipError_t launch_ordered(const pmpd_ordered* o, const void* x, float* y, hipStream_t s) {
   const pmpd_stack* st = o->stack;
   const size_t lds = lds_bytes(kOrderedMaxPartGroups, 1, kOrderedWaves, 4);
-  int per_cu = 0, dev = 0;
-  hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, pmpd_ordered_kernel<B>, kOrderedThreads, lds);
-  if (e != hipSuccess) return e;
-  hipDeviceProp_t prop;
-  if ((e = hipGetDevice(&dev)) != hipSuccess || (e = hipGetDeviceProperties(&prop, dev)) != hipSuccess) return e;
-  int grid = std::min(per_cu, kOrderedWgPerCu) * prop.multiProcessorCount;
-  if (grid < 1) return hipErrorCooperativeLaunchTooLarge;
-  grid = std::min(grid, o->max_stage_items);
   hipLaunchKernelGGL(pmpd_ordered_reset_kernel, dim3(1024), dim3(256), 0, s, o->d_sums, o->n_sums);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
   const LayerDesc* layers = st->d_layers;
   const _Float16* xb = static_cast<const _Float16*>(x);
-  int n_stages = o->n_stages;
+  int n_items = static_cast<int>(o->items.size());
   uint32_t spin = o->spin_limit;
   int n_layers = static_cast<int>(st->layers.size());
-  void* args[] = {&layers, const_cast<ChainDesc**>(&o->d_chains), const_cast<WorkItem**>(&o->d_items),
-                  const_cast<int32_t**>(&o->d_stage_begin), &n_stages, &xb, &y, const_cast<unsigned long long**>(&o->d_sums),
-                  const_cast<OrderedSync**>(&o->d_sync), &spin, &n_layers};
-  return hipLaunchCooperativeKernel(reinterpret_cast<const void*>(&pmpd_ordered_kernel<B>), dim3(grid), dim3(kOrderedThreads),
+  void* args[] = {&layers, const_cast<ChainDesc**>(&o->d_chains), const_cast<WorkItem**>(&o->d_items), &n_items, &xb, &y,
+                  const_cast<unsigned long long**>(&o->d_sums), const_cast<OrderedSync**>(&o->d_sync), &spin, &n_layers};
+  // a cooperative launch is refused, not queued, when the grid does not fit the device at once
+  return hipLaunchCooperativeKernel(reinterpret_cast<const void*>(&pmpd_ordered_kernel<B>), dim3(o->grid), dim3(kOrderedThreads),
                                     args, static_cast<unsigned>(lds), s);
 }
 
@@ -1105,7 +1096,8 @@ int32_t pmpd_ordered_workspace_size(const pmpd_stack_t* stack, const pmpd_chain_
   int32_t rc = check_chain(stack, chain, &n_stages);
   if (rc) return rc;
   if (!bytes) return fail(PMPD_EINVAL, "pmpd_ordered_workspace_size: bytes is NULL");
-  *bytes = ordered_bytes(stack, ordered_part_groups(stack, chain, n_stages, ordered_slots()), static_cast<size_t>(n_stages));
+  const std::vector<int> pg = ordered_part_groups(stack, chain, n_stages, ordered_slots());
+  *bytes = ordered_bytes(stack, ordered_counts(stack, chain, n_stages, pg), static_cast<size_t>(ordered_slots()));
   return PMPD_OK;
 }
 
@@ -1118,15 +1110,22 @@ int32_t pmpd_ordered_create(const pmpd_stack_t* stack, const pmpd_chain_t* chain
   if (reinterpret_cast<uintptr_t>(workspace) % 256) return fail(PMPD_EALIGN, "pmpd_ordered_create: workspace not 256-byte aligned");
   const size_t n_layers = stack->layers.size();
   const std::vector<int> pg = ordered_part_groups(stack, chain, n_stages, ordered_slots());
-  const size_t need = ordered_bytes(stack, pg, static_cast<size_t>(n_stages));
+  const OrderedCounts counts = ordered_counts(stack, chain, n_stages, pg);
+  const size_t need = ordered_bytes(stack, counts, static_cast<size_t>(ordered_slots()));
   if (workspace_bytes < need) return fail(PMPD_ESIZE, "pmpd_ordered_create: workspace %zu bytes, need %zu", workspace_bytes, need);
-  size_t n_items, n_sums;
-  ordered_counts(stack, pg, &n_items, &n_sums);
-  if (n_items > static_cast<size_t>(INT32_MAX)) return fail(PMPD_EINVAL, "pmpd_ordered_create: too many work items");
+  if (counts.n_items + static_cast<size_t>(n_stages) * static_cast<size_t>(ordered_slots()) > static_cast<size_t>(INT32_MAX))
+    return fail(PMPD_EINVAL, "pmpd_ordered_create: too many work items");
+  int slots[3] = {0, 0, 0};
+  hipError_t e = ordered_capacity<2>(&slots[0]);
+  if (e == hipSuccess) e = ordered_capacity<3>(&slots[1]);
+  if (e == hipSuccess) e = ordered_capacity<4>(&slots[2]);
+  if (e != hipSuccess) return hip_fail(e, "pmpd_ordered_create occupancy");
+  const int capacity = std::min(std::min(slots[0], std::min(slots[1], slots[2])), ordered_slots());
+  if (capacity < 1) return fail(PMPD_EINVAL, "pmpd_ordered_create: the device holds no workgroup of the kernel");
   auto* o = new pmpd_ordered;
   o->stack = stack;
-  o->n_stages = n_stages;
-  o->n_sums = static_cast<int64_t>(n_sums);
+  o->n_sums = static_cast<int64_t>(counts.n_sums);
+  o->grid = static_cast<int>(std::min<size_t>(static_cast<size_t>(capacity), std::max<size_t>(1, counts.max_stage_items)));
   for (size_t i = 0; i < n_layers; ++i) {
     const LayerDesc& d = stack->layers[i];
     const int src = chain[i].source;
@@ -1145,27 +1144,22 @@ int32_t pmpd_ordered_create(const pmpd_stack_t* stack, const pmpd_chain_t* chain
     if (chain[a].stage != chain[b].stage) return chain[a].stage < chain[b].stage;
     return stack->layers[a].in_f > stack->layers[b].in_f;
   });
-  o->stage_begin.assign(static_cast<size_t>(n_stages) + 1, 0);
+  int stage = -1;
   for (int li : order) {
+    if (chain[li].stage != stage)  // a new stage starts a new round
+      while (o->items.size() % static_cast<size_t>(o->grid)) o->items.push_back(WorkItem{-1, 0});
+    stage = chain[li].stage;
     const int parts = o->chains[li].n_parts;
     for (int t = 0; t < stack->layers[li].n_tiles; ++t)
       for (int q = 0; q < parts; ++q) o->items.push_back(WorkItem{li, t | (q << kItemPartShift)});
-    o->stage_begin[static_cast<size_t>(chain[li].stage) + 1] = static_cast<int32_t>(o->items.size());
   }
-  for (int sidx = 1; sidx <= n_stages; ++sidx)  // stages without layers stay empty
-    o->stage_begin[sidx] = std::max(o->stage_begin[sidx], o->stage_begin[sidx - 1]);
-  for (int sidx = 0; sidx < n_stages; ++sidx)
-    o->max_stage_items = std::max(o->max_stage_items, o->stage_begin[sidx + 1] - o->stage_begin[sidx]);
   char* w = static_cast<char*>(workspace);
-  hipError_t e = hipMemcpy(w, o->chains.data(), n_layers * sizeof(ChainDesc), hipMemcpyHostToDevice);
+  e = hipMemcpy(w, o->chains.data(), n_layers * sizeof(ChainDesc), hipMemcpyHostToDevice);  // the list fits: see ordered_bytes
   o->d_chains = reinterpret_cast<const ChainDesc*>(w);
   w += align_up(n_layers * sizeof(ChainDesc), 256);
   if (e == hipSuccess) e = hipMemcpy(w, o->items.data(), o->items.size() * sizeof(WorkItem), hipMemcpyHostToDevice);
   o->d_items = reinterpret_cast<const WorkItem*>(w);
-  w += align_up(n_items * sizeof(WorkItem), 256);
-  if (e == hipSuccess) e = hipMemcpy(w, o->stage_begin.data(), o->stage_begin.size() * sizeof(int32_t), hipMemcpyHostToDevice);
-  o->d_stage_begin = reinterpret_cast<const int32_t*>(w);
-  w += align_up(o->stage_begin.size() * sizeof(int32_t), 256);
+  w += align_up(o->items.size() * sizeof(WorkItem), 256);
   o->d_sync = reinterpret_cast<OrderedSync*>(w);
   const size_t sync_bytes = sizeof(OrderedSync);
   if (e == hipSuccess) e = hipMemset(w, 0, sync_bytes);

@@ -696,6 +696,9 @@ __global__ __launch_bounds__(kOrderedThreads, kOrderedWgPerCu) void pmpd_ordered
         }
       }
     }
+    // The rows are what the next stage waits for: they enter the compute unit's memory pipeline
+    // before the next item's weight requests (ten 1 KiB loads per wave) queue up in it.
+    __syncthreads();
   };
 
   const int first = static_cast<int>(blockIdx.x), step = static_cast<int>(n_wg);

@@ -192,8 +192,9 @@ int32_t pmpd_decode_run(const pmpd_stack_t* stack, const pmpd_schedule_t* schedu
  * down, block after block); launched one kernel per stage, the step is bound by launch overhead,
  * which the paper observes for its own kernels and leaves to future work (Section 5.2 "GPU
  * Evaluation").  Here the whole step is one cooperative launch: the layers of the stack are
- * assigned to stages, the workgroups stay resident, pass from stage to stage through a counter in
- * device memory, and load the weights of their next tile before they wait for its inputs.
+ * assigned to stages, the workgroups stay resident and take their tiles stage after stage; a tile
+ * waits only for the outputs it reads (every output word counts the partial sums added to it), and
+ * the weights of a workgroup's next tile are requested before it waits for that tile's inputs.
  * chain[l] (host, one per layer of the stack): stage of layer l (layers of one stage are independent);
  * source = -1: the layer reads x_base + x_offset[l] as in pmpd_decode_step; source = k: it reads
  * fp16(gain * y_k), the output of layer k of an earlier stage (out_features(k) == in_features(l),
@@ -201,12 +202,13 @@ int32_t pmpd_decode_run(const pmpd_stack_t* stack, const pmpd_schedule_t* schedu
  * not part of this library.  Every layer still writes its full fp32 output at y_base + y_offset[l].
  * Where a layer's rows are long enough to be split over workgroups, the parts meet in 64-bit
  * fixed-point sums (32 fractional bits, integer atomic adds: the same bits whatever the order of
- * arrival); row sums must stay below 2^31 in magnitude, which fp16 inputs and rows of up to 32768
- * features with weights below 1 always do.
- * The tables, counters and sums (8 bytes per output of the stack) live in a caller-provided device
+ * arrival).  Each part's sum is clamped to +-(2^21 - 1) (a NaN counts as the lower bound); sums of
+ * that size do not occur with fp16 activations of a decoder and weights below 1.  A layer whose
+ * rows are not split passes its fp32 outputs on unchanged.
+ * The tables and sums (8 bytes per output of the stack) live in a caller-provided device
  * workspace (256-byte aligned, untouched while the object exists); calls on one object must not
  * overlap.  y_base must be 16-byte aligned.
- * The wait between stages is bounded: if it runs out (it cannot while the launch is cooperative,
+ * The wait for inputs is bounded: if it runs out (it cannot while the launch is cooperative,
  * unless the limit is set very low) the step still ends and pmpd_ordered_status reports it. */
 typedef struct pmpd_chain {
   int32_t stage;
@@ -220,9 +222,9 @@ int32_t pmpd_ordered_create(const pmpd_stack_t* stack, const pmpd_chain_t* chain
 void pmpd_ordered_destroy(pmpd_ordered_t* ordered);
 int32_t pmpd_ordered_step(const pmpd_ordered_t* ordered, int32_t b, const void* x_base, float* y_base,
                           void* stream);
-/* Synchronous: *timed_out = 1 if a wait between stages ran out since the last call (then cleared). */
+/* Synchronous: *timed_out = 1 if a wait for inputs ran out since the last call (then cleared). */
 int32_t pmpd_ordered_status(const pmpd_ordered_t* ordered, int32_t* timed_out);
-/* Polls per wait before it gives up (default 2^20, some seconds). */
+/* Polls per wait before it gives up (default 2^20, about a second). */
 int32_t pmpd_ordered_set_spin_limit(pmpd_ordered_t* ordered, uint32_t polls);
 
 /* ---- learned scheduler: forward pass (Section 4.3 "Task-Agnostic Learned Scheduler"; Appendix A.2) *

@@ -1,5 +1,6 @@
-"""The dependency-ordered step (one cooperative launch, stages separated by in-kernel waits): every
-layer against the oracle on the inputs it really got, x = fp16(gain * y[source]) for chained layers."""
+"""The dependency-ordered step (one cooperative launch, every tile waiting in the kernel for the outputs
+it reads): every layer against the oracle on the inputs it really got, x = fp16(gain * y[source]) for
+chained layers."""
 import numpy as np
 import pytest
 
@@ -66,7 +67,7 @@ def test_ordered_step_matches_oracle_layer_by_layer(pmpd, b, shape):
     ordered = pmpd.Ordered(stack, stages, sources, gains)
     ordered.set_spin_limit(200000)
     y = torch.full((stack.y_elems,), float("nan"), dtype=torch.float32, device="cuda")
-    for rep in range(3):  # the counters are reset by every step; fresh inputs, so a stale y of the last step shows
+    for rep in range(3):  # the sums are reset by every step; fresh inputs, so a stale y of the last step shows
         xs = [synth.draw_x(21, rep, blk, pi, i)[0] for (blk, pi, nm, o, i) in shape.layers()]
         x = torch.from_numpy(np.concatenate(xs)).cuda()
         ordered.step(b, x, y)
@@ -109,6 +110,61 @@ def test_ordered_step_matches_oracle_layer_by_layer(pmpd, b, shape):
         _, t = oracle.linear(q4, s, a, b, xs[li])
         assert np.all(np.abs(y1h[o:o + q4.shape[0]] - y2h[o:o + q4.shape[0]]) <= 1e-4 * t[0] + 1e-30), f"layer {li}"
     ordered.close(); free.close(); stack.close()
+
+
+@pytest.mark.parametrize("b", [4, 2])
+def test_ordered_longest_rows_meet_in_many_parts(pmpd, b):
+    """Rows of 32768 features (the largest the library takes) are split into 29 K-parts, close to what the
+    count bits of a sum hold; a ragged layer (192 rows) reads them."""
+    import torch
+
+    print(f"[ordered] longest rows b={b}", flush=True)
+    dims = [(128, 32768), (192, 128)]
+    raw, layers = [], []
+    for li, (o, i) in enumerate(dims):
+        q4, s, a = synth.draw_weights(31, li, 0, o, i, random_min=True)
+        raw.append((q4, s, a))
+        planes, sm = pmpd.pack(q4, s, a)
+        layers.append(pmpd.upload_layer(planes, sm, o, i))
+    stack = pmpd.Stack(layers)
+    gain = 1.0 / 16.0
+    ordered = pmpd.Ordered(stack, [0, 1], [-1, 0], [1.0, gain])
+    ordered.set_spin_limit(200000)
+    xs = [synth.draw_x(31, 0, li, 0, i)[0] for li, (o, i) in enumerate(dims)]
+    x = torch.from_numpy(np.concatenate(xs)).cuda()
+    y = torch.full((stack.y_elems,), float("nan"), dtype=torch.float32, device="cuda")
+    ordered.step(b, x, y)
+    torch.cuda.synchronize()
+    assert not ordered.timed_out()
+    yh = y.cpu().numpy()
+    o0, o1 = stack.y_offsets
+    for li, xin in ((0, xs[0]), (1, (yh[o0:o0 + 128] * np.float32(gain)).astype(np.float16))):
+        q4, s, a = raw[li]
+        y_ref, t = oracle.linear(q4, s, a, b, xin)
+        got = yh[stack.y_offsets[li]:stack.y_offsets[li] + q4.shape[0]].astype(np.float64)
+        assert np.all(np.abs(got - y_ref[0]) <= ABS_FACTOR * t[0] + 1e-30), f"layer {li}"
+        assert np.linalg.norm(got - y_ref[0]) / np.linalg.norm(y_ref[0]) <= REL_L2, f"layer {li}"
+    ordered.close(); stack.close()
+
+
+def test_ordered_values_out_of_range_do_not_stall(pmpd):
+    """A gain that drives the chained activations to infinity: the K-parts are clamped before they are
+    added, so the counts in the sums stay intact and no tile waits for ever."""
+    import torch
+
+    shape = synth.StackShape("mid", 1, 2048, 5632)
+    layers, raw = _build(pmpd, shape, seed=24)
+    stack = pmpd.Stack(layers)
+    stages, sources, gains = _chain_of(shape)
+    ordered = pmpd.Ordered(stack, stages, sources, [1.0 if k < 0 else 6.0e4 for k in sources])
+    ordered.set_spin_limit(200000)
+    xs = [synth.draw_x(24, 0, blk, pi, i)[0] for (blk, pi, nm, o, i) in shape.layers()]
+    x = torch.from_numpy(np.concatenate(xs)).cuda()
+    y = torch.zeros(stack.y_elems, dtype=torch.float32, device="cuda")
+    ordered.step(4, x, y)
+    torch.cuda.synchronize()
+    assert not ordered.timed_out()
+    ordered.close(); stack.close()
 
 
 def test_ordered_wait_is_bounded_and_reported(pmpd):

@@ -147,6 +147,41 @@ def test_ordered_longest_rows_meet_in_many_parts(pmpd, b):
     ordered.close(); stack.close()
 
 
+def test_ordered_stage_with_more_tiles_than_workgroups(pmpd):
+    """70400 output rows are 1100 tiles, more than the chip holds workgroups at once: the stage runs in
+    two rounds of the grid.  The wide layer reads a narrow one of the stage before."""
+    import torch
+
+    print("[ordered] stage of 1100 tiles", flush=True)
+    dims = [(256, 128), (70400, 256)]
+    raw, layers = [], []
+    for li, (o, i) in enumerate(dims):
+        q4, s, a = synth.draw_weights(32, li, 0, o, i, random_min=True)
+        raw.append((q4, s, a))
+        planes, sm = pmpd.pack(q4, s, a)
+        layers.append(pmpd.upload_layer(planes, sm, o, i))
+    stack = pmpd.Stack(layers)
+    gain = 0.25
+    ordered = pmpd.Ordered(stack, [0, 1], [-1, 0], [1.0, gain])
+    ordered.set_spin_limit(200000)
+    xs = [synth.draw_x(32, 0, li, 0, i)[0] for li, (o, i) in enumerate(dims)]
+    x = torch.from_numpy(np.concatenate(xs)).cuda()
+    y = torch.full((stack.y_elems,), float("nan"), dtype=torch.float32, device="cuda")
+    for b in (4, 2):
+        ordered.step(b, x, y)
+        torch.cuda.synchronize()
+        assert not ordered.timed_out()
+        yh = y.cpu().numpy()
+        o0 = stack.y_offsets[0]
+        for li, xin in ((0, xs[0]), (1, (yh[o0:o0 + 256] * np.float32(gain)).astype(np.float16))):
+            q4, s, a = raw[li]
+            y_ref, t = oracle.linear(q4, s, a, b, xin)
+            got = yh[stack.y_offsets[li]:stack.y_offsets[li] + q4.shape[0]].astype(np.float64)
+            assert np.all(np.abs(got - y_ref[0]) <= ABS_FACTOR * t[0] + 1e-30), f"layer {li} b={b}"
+            assert np.linalg.norm(got - y_ref[0]) / np.linalg.norm(y_ref[0]) <= REL_L2, f"layer {li} b={b}"
+    ordered.close(); stack.close()
+
+
 def test_ordered_values_out_of_range_do_not_stall(pmpd):
     """A gain that drives the chained activations to infinity: the K-parts are clamped before they are
     added, so the counts in the sums stay intact and no tile waits for ever."""

@@ -1116,7 +1116,8 @@ int32_t pmpd_ordered_create(const pmpd_stack_t* stack, const pmpd_chain_t* chain
   const OrderedCounts counts = ordered_counts(stack, chain, n_stages, pg);
   const size_t need = ordered_bytes(stack, counts, static_cast<size_t>(ordered_slots()));
   if (workspace_bytes < need) return fail(PMPD_ESIZE, "pmpd_ordered_create: workspace %zu bytes, need %zu", workspace_bytes, need);
-  if (counts.n_items + static_cast<size_t>(n_stages) * static_cast<size_t>(ordered_slots()) > static_cast<size_t>(INT32_MAX))
+  // the kernel indexes the list with int, two rounds of the grid beyond the current item
+  if (counts.n_items + static_cast<size_t>(n_stages) * static_cast<size_t>(ordered_slots()) > (size_t{1} << 30))
     return fail(PMPD_EINVAL, "pmpd_ordered_create: too many work items");
   int slots[3] = {0, 0, 0};
   hipError_t e = ordered_capacity<2>(&slots[0]);

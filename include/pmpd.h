@@ -85,10 +85,14 @@ typedef struct pmpd_layer {
 typedef struct pmpd_stack pmpd_stack_t;       /* a list of layers prepared for one-launch decode steps */
 typedef struct pmpd_schedule pmpd_schedule_t; /* precision-switching schedule <P, S> */
 
+/* Error reporting (library plumbing, no counterpart in the paper): a fixed English name for a
+ * status code, and the message of the calling thread's last failed call (valid until its next call). */
 const char* pmpd_strerror(int32_t status);
 const char* pmpd_last_error(void);
 
-/* Bytes of one plane and of the scale_min array for a layer of this shape. */
+/* Bytes of one plane and of the scale_min array for a layer of this shape: the nested store of
+ * Section 2.1 / Section 5 "PMPD Implementation Details" holds every precision in the memory of the
+ * highest one (4 planes of out*in/8 bytes, rows padded to 64) plus one (scale, min) word per group. */
 int32_t pmpd_packed_size(int32_t out_features, int32_t in_features, int32_t group_size,
                          size_t* plane_bytes, size_t* scale_min_bytes);
 
@@ -99,8 +103,9 @@ int32_t pmpd_packed_size(int32_t out_features, int32_t in_features, int32_t grou
 int32_t pmpd_pack(const uint8_t* q4, const uint16_t* scale, const uint16_t* minv, int32_t out_features,
                   int32_t in_features, int32_t group_size, void* const planes[4], void* scale_min);
 
-/* Host inverse of pmpd_pack for the top b planes: qb_out[r][i] = q4[r][i] >> (4-b), b in 1..4.
- * Reads host_layer->planes[0..b-1] only. */
+/* Host inverse of pmpd_pack for the top b planes: qb_out[r][i] = q4[r][i] >> (4-b), b in 1..4: the
+ * lower-precision model is a prefix of the stored one (Section 2.1, nested quantisation; Section 5
+ * "PMPD Implementation Details").  Reads host_layer->planes[0..b-1] only.  All pointers host. */
 int32_t pmpd_unpack(const pmpd_layer_t* host_layer, int32_t b, uint8_t* qb_out);
 
 /* y = W_b x for one layer (the decode-phase linear layer, Algorithm 1 line 16).
@@ -129,6 +134,18 @@ int32_t pmpd_stack_create(const pmpd_layer_t* layers, int32_t n_layers, const in
                           const int64_t* y_offset, void* workspace, size_t workspace_bytes,
                           pmpd_stack_t** out);
 void pmpd_stack_destroy(pmpd_stack_t* stack);
+
+/* Launch shape of pmpd_decode_step on this stack at bit-width b (chosen by pmpd_stack_create from
+ * the number of row tiles and the row lengths; it affects speed and summation order, never which
+ * planes are read):
+ *   0  workgroup = 4 waves x 1 tile each, whole K     1  4 waves on 1 tile, K split 4 ways
+ *   2  4 waves on 2 tiles, K split 2 ways            3  8 waves on 1 tile, K split 8 ways
+ *   4  16 waves on 1 tile, K split 16 ways
+ * pmpd_stack_variant reads it (so that a test can state which shape it checked, and a benchmark
+ * which one it timed); pmpd_stack_set_variant overrides it for later steps on this stack (tuning
+ * and tests; every shape computes the linear layers of Algorithm 1 line 16 for any stack).  Host only. */
+int32_t pmpd_stack_variant(const pmpd_stack_t* stack, int32_t b, int32_t* variant);
+int32_t pmpd_stack_set_variant(pmpd_stack_t* stack, int32_t b, int32_t variant);
 
 /* One decode step: every layer of the stack at bit-width b, one kernel launch. */
 int32_t pmpd_decode_step(const pmpd_stack_t* stack, int32_t b, const void* x_base, float* y_base,
@@ -227,7 +244,7 @@ int32_t pmpd_ordered_status(const pmpd_ordered_t* ordered, int32_t* timed_out);
 /* Polls per wait before it gives up (default 2^20, about a second). */
 int32_t pmpd_ordered_set_spin_limit(pmpd_ordered_t* ordered, uint32_t polls);
 
-/* ---- learned scheduler: forward pass (Section 4.3 "Task-Agnostic Learned Scheduler"; Appendix A.2) *
+/* ---- learned scheduler: forward pass (Section 4.3 "Task-Agnostic Learned Scheduler"; Appendix A.1.1) *
  * Run once per prompt between prefill and decoding (Algorithm 1, deployment stage):
  *     p = softmax_t(q . K_t / sqrt(d_k)),  O = sum_t p_t V_t,
  *     probs = softmax(W2 relu(W1 O + b1) + b2),  class = first index of the largest probability;

@@ -274,7 +274,7 @@ def schedule_search_brute_force(precisions, OL: int, N: int, quality, q_ref: flo
     return list(best[1]), best[2], count
 
 
-# ------------------------------------------- learned scheduler (Section 4.3, Appendix A.2) ----
+# ------------------------------------------- learned scheduler (Section 4.3, Appendix A.1.1 "Model Architecture") ----
 def learned_scheduler(q, K, V, W1, b1, W2, b2):
     """Forward pass of the learned scheduler in fp64, step by step as the appendix states it:
         scores_t = (q . K_t) / sqrt(D_k)            K: [T, D_k] key cache of the chosen block

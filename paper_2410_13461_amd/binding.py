@@ -17,6 +17,7 @@ MAX_BATCH = 8
 EXPORTS = (
     "pmpd_strerror", "pmpd_last_error", "pmpd_packed_size", "pmpd_pack", "pmpd_unpack", "pmpd_gemv", "pmpd_gemm",
     "pmpd_stack_workspace_size", "pmpd_stack_create", "pmpd_stack_destroy", "pmpd_decode_step",
+    "pmpd_stack_variant", "pmpd_stack_set_variant",
     "pmpd_schedule_create", "pmpd_schedule_destroy", "pmpd_schedule_bits", "pmpd_schedule_avg_bits",
     "pmpd_decode_run", "pmpd_prefill_step", "pmpd_batch_step",
     "pmpd_schedule_grid", "pmpd_schedule_count", "pmpd_schedule_search", "pmpd_read_stream",
@@ -100,6 +101,10 @@ def _load():
     L.pmpd_stack_destroy.argtypes = [vp]
     L.pmpd_decode_step.restype = i32
     L.pmpd_decode_step.argtypes = [vp, i32, vp, vp, vp]
+    L.pmpd_stack_variant.restype = i32
+    L.pmpd_stack_variant.argtypes = [vp, i32, P(i32)]
+    L.pmpd_stack_set_variant.restype = i32
+    L.pmpd_stack_set_variant.argtypes = [vp, i32, i32]
     L.pmpd_schedule_create.restype = i32
     L.pmpd_schedule_create.argtypes = [P(i32), P(i32), i32, i32, P(vp)]
     L.pmpd_schedule_destroy.restype = None
@@ -236,9 +241,13 @@ class PackedLayer:
     def struct(self) -> _Layer:
         if self._struct is None:
             lay = _Layer(self.out_features, self.in_features, GROUP, 0)
+            pb, sb = packed_size(self.out_features, self.in_features)
             for k in range(4):
-                lay.planes[k] = self.planes[k].data_ptr() if self.planes[k] is not None else None
-            lay.scale_min = self.scale_min.data_ptr()
+                if self.planes[k] is not None:
+                    lay.planes[k] = _dev_ptr(self.planes[k], "int32", pb // 4, f"planes[{k}]").value
+                else:
+                    lay.planes[k] = None
+            lay.scale_min = _dev_ptr(self.scale_min, "int32", sb // 4, "scale_min").value
             self._struct = lay
         return self._struct
 
@@ -256,7 +265,23 @@ def upload_layer(planes, scale_min, out_features: int, in_features: int, device=
     return PackedLayer(out_features, in_features, dp, ds)
 
 
-def _dev_ptr(t):
+def _dev_ptr(t, dtype: str, min_elems: int, what: str):
+    """Address of a torch tensor for the C ABI, after checking what the C side cannot see: the library
+    gets a bare pointer, so a host tensor, another element type, a strided view or a buffer shorter than
+    the call reads or writes would become a wild access inside a kernel.  dtype: "float16", "float32",
+    "int32" or "any"; min_elems: elements the call touches."""
+    import torch
+
+    if not isinstance(t, torch.Tensor):
+        raise PMPDError(-1, f"{what}: expected a torch tensor, got {type(t).__name__}")
+    if not t.is_cuda:
+        raise PMPDError(-1, f"{what}: tensor is on {t.device}, the kernels need device memory")
+    if dtype != "any" and t.dtype != getattr(torch, dtype):
+        raise PMPDError(-1, f"{what}: dtype {t.dtype}, expected torch.{dtype}")
+    if not t.is_contiguous():
+        raise PMPDError(-1, f"{what}: tensor is not contiguous")
+    if t.numel() < min_elems:
+        raise PMPDError(-5, f"{what}: {t.numel()} elements, the call needs {min_elems}")
     return ctypes.c_void_p(t.data_ptr())
 
 
@@ -264,9 +289,11 @@ def gemv(layer: PackedLayer, b: int, x, y=None, stream=None):
     """y = W_b x.  x: torch fp16 [in] on the GPU; returns torch fp32 [out]."""
     import torch
 
+    xp = _dev_ptr(x, "float16", layer.in_features, "gemv x")
     if y is None:
         y = torch.empty(layer.out_features, dtype=torch.float32, device=x.device)
-    _check(_load().pmpd_gemv(ctypes.byref(layer.struct()), b, _dev_ptr(x), _dev_ptr(y), _stream_handle(stream)))
+    yp = _dev_ptr(y, "float32", layer.out_features, "gemv y")
+    _check(_load().pmpd_gemv(ctypes.byref(layer.struct()), b, xp, yp, _stream_handle(stream)))
     return y
 
 
@@ -274,10 +301,14 @@ def gemm(layer: PackedLayer, b: int, X, Y=None, stream=None):
     """Y = X W_b^T.  X: torch fp16 [m, in]; returns torch fp32 [m, out] (m <= 8 skinny path, above: MFMA prefill path)."""
     import torch
 
+    if X.dim() != 2 or X.shape[1] != layer.in_features:
+        raise PMPDError(-1, f"gemm X: shape {tuple(X.shape)}, expected [m, {layer.in_features}]")
     m = X.shape[0]
+    Xp = _dev_ptr(X, "float16", m * layer.in_features, "gemm X")
     if Y is None:
         Y = torch.empty((m, layer.out_features), dtype=torch.float32, device=X.device)
-    _check(_load().pmpd_gemm(ctypes.byref(layer.struct()), b, _dev_ptr(X), m, _dev_ptr(Y), _stream_handle(stream)))
+    Yp = _dev_ptr(Y, "float32", m * layer.out_features, "gemm Y")
+    _check(_load().pmpd_gemm(ctypes.byref(layer.struct()), b, Xp, m, Yp, _stream_handle(stream)))
     return Y
 
 
@@ -319,6 +350,15 @@ class Stack:
     def bytes_at(self, b: int) -> int:
         return sum(l.bytes_at(b) for l in self.layers)
 
+    def variant(self, b: int) -> int:
+        """Launch shape (0..4, see include/pmpd.h) that decode_step uses on this stack at bit-width b."""
+        v = ctypes.c_int32()
+        _check(_load().pmpd_stack_variant(self._h, b, ctypes.byref(v)))
+        return v.value
+
+    def set_variant(self, b: int, variant: int):
+        _check(_load().pmpd_stack_set_variant(self._h, b, variant))
+
     def close(self):
         if getattr(self, "_h", None):
             _load().pmpd_stack_destroy(self._h)
@@ -333,19 +373,27 @@ class Stack:
 
 def decode_step(stack: Stack, b: int, x, y, stream=None):
     """One decode step over the stack at bit-width b.  x: fp16 [x_elems], y: fp32 [y_elems]."""
-    _check(_load().pmpd_decode_step(stack._h, b, _dev_ptr(x), _dev_ptr(y), _stream_handle(stream)))
+    xp = _dev_ptr(x, "float16", stack.x_elems, "decode_step x")
+    yp = _dev_ptr(y, "float32", stack.y_elems, "decode_step y")
+    _check(_load().pmpd_decode_step(stack._h, b, xp, yp, _stream_handle(stream)))
     return y
 
 
 def batch_step(stack: Stack, b: int, X, m: int, Y, stream=None):
     """m tokens through every layer: layer l reads X[m*x_off[l]:][m, in_l] and writes Y[m*y_off[l]:][m, out_l]."""
-    _check(_load().pmpd_batch_step(stack._h, b, _dev_ptr(X), m, _dev_ptr(Y), _stream_handle(stream)))
+    m = int(m)
+    Xp = _dev_ptr(X, "float16", max(m, 1) * stack.x_elems, "batch_step X")
+    Yp = _dev_ptr(Y, "float32", max(m, 1) * stack.y_elems, "batch_step Y")
+    _check(_load().pmpd_batch_step(stack._h, b, Xp, m, Yp, _stream_handle(stream)))
     return Y
 
 
 def prefill_step(stack: Stack, b: int, X, m: int, Y, stream=None):
     """Prefill over the stack: layer l reads X[m*x_off[l]:][m, in_l] and writes Y[m*y_off[l]:][m, out_l]."""
-    _check(_load().pmpd_prefill_step(stack._h, b, _dev_ptr(X), m, _dev_ptr(Y), _stream_handle(stream)))
+    m = int(m)
+    Xp = _dev_ptr(X, "float16", max(m, 1) * stack.x_elems, "prefill_step X")
+    Yp = _dev_ptr(Y, "float32", max(m, 1) * stack.y_elems, "prefill_step Y")
+    _check(_load().pmpd_prefill_step(stack._h, b, Xp, m, Yp, _stream_handle(stream)))
     return Y
 
 
@@ -410,7 +458,9 @@ class Ordered:
         self._h = h
 
     def step(self, b: int, x, y, stream=None):
-        _check(_load().pmpd_ordered_step(self._h, b, _dev_ptr(x), _dev_ptr(y), _stream_handle(stream)))
+        xp = _dev_ptr(x, "float16", self.stack.x_elems, "ordered step x")
+        yp = _dev_ptr(y, "float32", self.stack.y_elems, "ordered step y")
+        _check(_load().pmpd_ordered_step(self._h, b, xp, yp, _stream_handle(stream)))
         return y
 
     def timed_out(self) -> bool:
@@ -463,9 +513,13 @@ class LearnedScheduler:
         """K [T, d_k], V [T, d_v]: fp16 device tensors.  Returns (probs, cls, context) device tensors; asynchronous."""
         import torch
 
+        if K.dim() != 2 or V.dim() != 2:
+            raise PMPDError(-1, "learned scheduler: K and V must be [T, d] matrices")
         T = int(K.shape[0])
         if K.shape[1] != self.d_k or V.shape[0] != T or V.shape[1] != self.d_v:
             raise PMPDError(-1, "learned scheduler: K / V shapes do not fit the parameters")
+        Kp = _dev_ptr(K, "float16", T * self.d_k, "learned scheduler K")
+        Vp = _dev_ptr(V, "float16", T * self.d_v, "learned scheduler V")
         need = self.workspace_size(T)
         if self._ws is None or self._ws.numel() < need + 256:
             self._ws = torch.empty(need + 256, dtype=torch.uint8, device=K.device)
@@ -476,8 +530,10 @@ class LearnedScheduler:
             cls = torch.empty(1, dtype=torch.int32, device=K.device)
         if context is None:
             context = torch.empty(self.d_v, dtype=torch.float32, device=K.device)
-        _check(_load().pmpd_learned_forward(ctypes.byref(self._struct), _dev_ptr(K), _dev_ptr(V), T, base, need,
-                                            _dev_ptr(context), _dev_ptr(probs), _dev_ptr(cls), _stream_handle(stream)))
+        _check(_load().pmpd_learned_forward(ctypes.byref(self._struct), Kp, Vp, T, base, need,
+                                            _dev_ptr(context, "float32", self.d_v, "learned scheduler context"),
+                                            _dev_ptr(probs, "float32", self.n_classes, "learned scheduler probs"),
+                                            _dev_ptr(cls, "int32", 1, "learned scheduler cls"), _stream_handle(stream)))
         return probs, cls, context
 
 
@@ -496,10 +552,15 @@ def fp16_gemv(W, x, y=None, stream=None):
     """y = W x for an unquantised fp16 device matrix W [out, in] (the paper's fp16 baseline kernel)."""
     import torch
 
+    if W.dim() != 2:
+        raise PMPDError(-1, "fp16_gemv W: expected an [out, in] matrix")
     out_f, in_f = W.shape
+    Wp = _dev_ptr(W, "float16", out_f * in_f, "fp16_gemv W")
+    xp = _dev_ptr(x, "float16", in_f, "fp16_gemv x")
     if y is None:
         y = torch.empty(out_f, dtype=torch.float32, device=W.device)
-    _check(_load().pmpd_fp16_gemv(_dev_ptr(W), out_f, in_f, _dev_ptr(x), _dev_ptr(y), _stream_handle(stream)))
+    yp = _dev_ptr(y, "float32", out_f, "fp16_gemv y")
+    _check(_load().pmpd_fp16_gemv(Wp, out_f, in_f, xp, yp, _stream_handle(stream)))
     return y
 
 
@@ -511,7 +572,12 @@ class Fp16Stack:
 
         self.weights = list(weights)
         n = len(self.weights)
-        arr = (_Fp16Layer * n)(*[_Fp16Layer(int(w.shape[0]), int(w.shape[1]), _dev_ptr(w)) for w in self.weights])
+        for w in self.weights:
+            if w.dim() != 2:
+                raise PMPDError(-1, "Fp16Stack: every weight must be an [out, in] matrix")
+        arr = (_Fp16Layer * n)(*[_Fp16Layer(int(w.shape[0]), int(w.shape[1]),
+                                            _dev_ptr(w, "float16", int(w.shape[0]) * int(w.shape[1]), "Fp16Stack weight"))
+                                 for w in self.weights])
         if x_offsets is None or y_offsets is None:
             x_offsets, y_offsets, xo, yo = [], [], 0, 0
             for w in self.weights:
@@ -548,15 +614,18 @@ class Fp16Stack:
 
 
 def fp16_step(stack: Fp16Stack, x, y, stream=None):
-    _check(_load().pmpd_fp16_step(stack.handle, _dev_ptr(x), _dev_ptr(y), _stream_handle(stream)))
+    xp = _dev_ptr(x, "float16", stack.x_elems, "fp16_step x")
+    yp = _dev_ptr(y, "float32", stack.y_elems, "fp16_step y")
+    _check(_load().pmpd_fp16_step(stack.handle, xp, yp, _stream_handle(stream)))
     return y
 
 
 def read_stream(buf, sink, stream=None) -> int:
     """Launch the read-only stream kernel over the torch tensor buf; returns the bytes it reads."""
     n = ctypes.c_size_t()
-    _check(_load().pmpd_read_stream(_dev_ptr(buf), buf.numel() * buf.element_size(), _dev_ptr(sink), ctypes.byref(n),
-                                    _stream_handle(stream)))
+    bp = _dev_ptr(buf, "any", 1, "read_stream buf")
+    sp = _dev_ptr(sink, "int32", 1, "read_stream sink")
+    _check(_load().pmpd_read_stream(bp, buf.numel() * buf.element_size(), sp, ctypes.byref(n), _stream_handle(stream)))
     return n.value
 
 
@@ -595,6 +664,9 @@ def schedule_search(precisions: Sequence[int], max_steps: int, n_points: int, qu
 def decode_run(stack: Stack, schedule: Schedule, step0: int, n_steps: int, x, x_step_stride: int, y,
                y_step_stride: int, stream=None):
     """Steps step0..step0+n_steps-1, each at the schedule's bit-width."""
-    _check(_load().pmpd_decode_run(stack._h, schedule._h, step0, n_steps, _dev_ptr(x), x_step_stride, _dev_ptr(y),
-                                   y_step_stride, _stream_handle(stream)))
+    last = max(int(n_steps) - 1, 0)
+    xp = _dev_ptr(x, "float16", last * int(x_step_stride) + stack.x_elems, "decode_run x")
+    yp = _dev_ptr(y, "float32", last * int(y_step_stride) + stack.y_elems, "decode_run y")
+    _check(_load().pmpd_decode_run(stack._h, schedule._h, step0, n_steps, xp, x_step_stride, yp, y_step_stride,
+                                   _stream_handle(stream)))
     return y

@@ -59,6 +59,7 @@
 
 #include "pmpd_common.hpp"
 #include "pmpd_device.hpp"
+#include "pmpd_sumword.hpp"
 
 #ifndef PMPD_BATCH_WIDE_WAVES
 #define PMPD_BATCH_WIDE_WAVES 3  // waves per SIMD the kernels for 5..8 vectors are compiled for
@@ -163,37 +164,6 @@ __device__ __forceinline__ void split_pieces(const uint32_t (&w)[4], uint32_t E,
 // exponents and group sums, by NT threads (whole waves) of which the caller is number tid.
 // Thread idx handles columns 8 idx .. 8 idx + 7 of the range; a quad of threads owns one
 // 32-column block, a row of 16 threads one group.
-// Sums that meet across workgroups are 64-bit words: 32 fractional bits, 27 integer bits, and in the
-// top 5 bits the number of K-parts that have been added.  A part adds 2^59 + 2^53 + round_down(v 2^32)
-// with one integer atomic: the bias 2^53 (= 2^21) keeps the addend's low 59 bits positive, so nothing
-// is borrowed from the count, and up to 31 parts cannot carry into it.  Integer addition is
-// associative: the bits do not depend on the order of arrival (no floating-point atomics, no
-// partial-sum buffers), and a reader sees in the word itself whether the sum is complete, so no
-// flag, acknowledgement or barrier stands between a producer's add and its consumers.  A part's
-// value is clamped to +-(2^21 - 1) (a NaN becomes the lower bound), so that no input can damage
-// the count; what lies below 2^-32 is dropped.
-constexpr int kCountShift = 59;
-constexpr int kMaxParts = 31;
-constexpr unsigned long long kPartBias = 1ull << 53;
-constexpr float kPartLimit = 2097151.0f;
-__device__ __forceinline__ unsigned long long part_word(float v) {
-  v = fminf(fmaxf(v, -kPartLimit), kPartLimit);
-  const float fl = floorf(v);
-  const int hi = static_cast<int>(fl);
-  const uint32_t lo = static_cast<uint32_t>((v - fl) * 4294967296.0f);  // v - floor(v) is exact, in [0, 1)
-  return ((static_cast<unsigned long long>(static_cast<uint32_t>(hi)) << 32) | lo) + kPartBias + (1ull << kCountShift);
-}
-// The word of a row that has a single part carries that part as it is: its fp32 bits under a count of one.
-__device__ __forceinline__ unsigned long long whole_word(float v) { return (1ull << kCountShift) | __builtin_bit_cast(uint32_t, v); }
-__device__ __forceinline__ bool sum_complete(unsigned long long w, int n_parts) { return static_cast<int>(w >> kCountShift) == n_parts; }
-__device__ __forceinline__ float sum_value(unsigned long long w, int n_parts) {
-  if (n_parts == 1) return __builtin_bit_cast(float, static_cast<uint32_t>(w));
-  const unsigned long long f = (w & ((1ull << kCountShift) - 1)) - static_cast<unsigned long long>(n_parts) * kPartBias;
-  const int hi = static_cast<int>(static_cast<uint32_t>(f >> 32));
-  const uint32_t lo = static_cast<uint32_t>(f);
-  return fmaf(static_cast<float>(lo), 2.3283064365386963e-10f, static_cast<float>(hi));  // one rounding, wherever it is used
-}
-
 // Where a layer's activations come from: an fp16 vector, or the output of an earlier layer of the same
 // launch, scaled by `gain` and rounded to fp16 (round to nearest even) on the way in: the sums of its
 // `parts` K-parts (y64), read again (at most `spin_limit` times, then *timed_out is set) until complete.
@@ -879,8 +849,8 @@ static size_t stack_bytes(size_t n_layers, const size_t (&n_items)[kNumItemLists
   return b;
 }
 
-// Launch shapes of the one-launch decode step (PMPD_STACK_VARIANT="v4,v3,v2" overrides the
-// per-bit-width defaults):
+// Launch shapes of the one-launch decode step (pmpd_stack_variant reports the one chosen for a
+// bit-width, pmpd_stack_set_variant overrides it):
 //   0  4 waves x 1 tile each, whole K       1  4 waves on 1 tile, K split 4 ways
 //   2  4 waves on 2 tiles, K split 2 ways   3  8 waves on 1 tile, K split 8 ways
 //   4  16 waves on 1 tile, K split 16 ways
@@ -904,14 +874,6 @@ static void pick_variants(pmpd_stack* st) {
   if (split >= 4) {
     const int v = split == 4 ? 1 : split == 8 ? 3 : 4;
     st->variant[4] = st->variant[3] = st->variant[2] = v;
-  }
-  const char* e = std::getenv("PMPD_STACK_VARIANT");
-  if (e) {
-    int v[3];
-    if (std::sscanf(e, "%d,%d,%d", &v[0], &v[1], &v[2]) == 3) {
-      for (int i = 0; i < 3; ++i)
-        if (v[i] >= 0 && v[i] < kNumVariants) st->variant[4 - i] = v[i];
-    }
   }
 }
 
@@ -1138,6 +1100,11 @@ int32_t pmpd_ordered_create(const pmpd_stack_t* stack, const pmpd_chain_t* chain
       delete o;
       return fail(PMPD_EINVAL, "pmpd_ordered_create: layer %zu is too large for the item encoding", i);
     }
+    if (parts > kMaxParts) {  // the count bits of a sum word hold at most kMaxParts
+      delete o;
+      return fail(PMPD_EINVAL, "pmpd_ordered_create: layer %zu has %d input features; rows longer than %d cannot be split into at most %d parts",
+                  i, d.in_f, kMaxParts * kOrderedMaxPartGroups * kGroup, kMaxParts);
+    }
     const int src_parts = src >= 0 ? parts_of(stack->layers[src].n_groups, pg[src]) : 0;
     o->chains.push_back(ChainDesc{src < 0 ? int64_t{-1} : stack->layers[src].y_off, chain[i].gain, parts, pg[i], src_parts});
   }
@@ -1293,6 +1260,23 @@ int32_t pmpd_stack_create(const pmpd_layer_t* layers, int32_t n, const int64_t* 
 }
 
 void pmpd_stack_destroy(pmpd_stack_t* stack) { delete stack; }
+
+int32_t pmpd_stack_variant(const pmpd_stack_t* stack, int32_t b, int32_t* variant) {
+  int32_t rc = check_bits(b, "pmpd_stack_variant");
+  if (rc) return rc;
+  if (!stack || !variant) return fail(PMPD_EINVAL, "pmpd_stack_variant: NULL argument");
+  *variant = stack->variant[b];
+  return PMPD_OK;
+}
+
+int32_t pmpd_stack_set_variant(pmpd_stack_t* stack, int32_t b, int32_t variant) {
+  int32_t rc = check_bits(b, "pmpd_stack_set_variant");
+  if (rc) return rc;
+  if (!stack) return fail(PMPD_EINVAL, "pmpd_stack_set_variant: NULL stack");
+  if (variant < 0 || variant >= kNumVariants) return fail(PMPD_EINVAL, "pmpd_stack_set_variant: variant %d outside 0..%d", variant, kNumVariants - 1);
+  stack->variant[b] = variant;
+  return PMPD_OK;
+}
 
 int32_t pmpd_decode_step(const pmpd_stack_t* stack, int32_t b, const void* x_base, float* y_base, void* stream) {
   int32_t rc = check_bits(b, "pmpd_decode_step");

@@ -1,5 +1,5 @@
 // Forward pass of the learned precision-switching scheduler (Section 4.3 "Task-Agnostic Learned
-// Scheduler"; Appendix A.2), gfx950.  Run once per prompt, after the prefill and before decoding
+// Scheduler"; Appendix A.1 "Learned Scheduler Details", A.1.1), gfx950.  Run once per prompt, after the prefill and before decoding
 // (Algorithm 1, deployment stage):
 //     scores_t = q . K_t / sqrt(D_k)      K fp16 [T][D_k]: key cache of one attention block
 //     p        = softmax_t(scores)

@@ -302,15 +302,18 @@ def test_decode_step_matches_oracle_and_single_layer_calls(pmpd, b):
 
 
 @pytest.mark.parametrize("variant", list(range(5)))
-def test_every_stack_kernel_variant_matches_oracle(pmpd, variant, monkeypatch):
-    """Each launch shape of the one-launch decode step (selected per
-    bit-width by default, forced here through PMPD_STACK_VARIANT) gives the same answers."""
+def test_every_stack_kernel_variant_matches_oracle(pmpd, variant):
+    """Each launch shape of the one-launch decode step (selected per bit-width by default, forced
+    here through the stack's setter and read back) gives the same answers."""
     import torch
 
     _say(f"[decode_step variant] {variant}")
-    monkeypatch.setenv("PMPD_STACK_VARIANT", f"{variant},{variant},{variant}")
     shape, layers, raw = _small_stack(pmpd, seed=10)
-    stack = pmpd.Stack(layers)  # the variant is picked when the stack is created
+    stack = pmpd.Stack(layers)
+    for b in (4, 3, 2):
+        assert stack.variant(b) in range(5)
+        stack.set_variant(b, variant)
+        assert stack.variant(b) == variant
     xs = [synth.draw_x(10, 0, blk, pi, i)[0] for (blk, pi, nm, o, i) in shape.layers()]
     x = torch.from_numpy(np.concatenate(xs)).cuda()
     for b in (4, 3, 2):

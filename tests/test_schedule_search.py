@@ -35,6 +35,32 @@ def test_schedule_count_closed_form():
     assert visited == pmpd.schedule_count(12, 3) == 91
 
 
+def test_brute_force_oracle_on_hand_worked_cases():
+    """Pins of the oracle's own choice (no product code involved), worked by hand.
+
+    (a) P = (4, 3, 2), OL = 4, every step a candidate (N = 5); the quality bar forbids 2 bits before step 2.
+        Bits of st = (0, a, b): 4 a + 3 (b - a) + 2 (4 - b) = 8 + a + b, smallest for a = 0 and the smallest
+        allowed b = 2: steps 0, 1 at 3 bits, steps 2, 3 at 2 bits = 10 bits = 2.5 per step.  Non-decreasing
+        pairs (a, b) out of 5 points: C(6, 2) = 15 schedules.
+    (b) The same P and OL on the grid {0, 2, 4} (N = 3), feasible iff a + b >= 4.  The fewest bits among the
+        feasible ones is 12 (3.0 per step), reached twice: (0, 0, 4) = four steps at 3 bits, and (0, 2, 2) = two
+        steps at 4 bits then two at 2 bits.  The tie goes to the lexicographically smallest st: (0, 0, 4).
+        C(4, 2) = 6 schedules on the grid."""
+    got = oracle.schedule_search_brute_force((4, 3, 2), 4, 5, lambda P, st: 1.0 if st[2] >= 2 else 0.0, 1.0, 0.0)
+    assert got == ([0, 0, 2], 2.5, 15)
+    got = oracle.schedule_search_brute_force((4, 3, 2), 4, 3, lambda P, st: 1.0 if st[1] + st[2] >= 4 else 0.0, 1.0, 0.0)
+    assert got == ([0, 0, 4], 3.0, 6)
+    # the product agrees on both (its own visit count is at most the oracle's)
+    st, avg, n = pmpd.schedule_search((4, 3, 2), 4, 5, lambda P, st: 1.0 if st[2] >= 2 else 0.0, 1.0, 0.0)
+    assert (st, avg) == ([0, 0, 2], 2.5) and n <= 15
+    st, avg, n = pmpd.schedule_search((4, 3, 2), 4, 3, lambda P, st: 1.0 if st[1] + st[2] >= 4 else 0.0, 1.0, 0.0)
+    assert (st, avg) == ([0, 0, 4], 3.0) and n <= 6
+    # limits: a bar everything passes -> the lowest precision from step 0; a bar only all-high passes
+    OL = 256
+    assert oracle.schedule_search_brute_force((4, 3, 2), OL, 5, lambda P, st: 0.0, 1.0, 1.0)[:2] == ([0, 0, 0], 2.0)
+    assert oracle.schedule_search_brute_force((4, 3, 2), OL, 5, lambda P, st: 1.0 if st[1] == OL else 0.0, 1.0, 0.0)[:2] == ([0, OL, OL], 4.0)
+
+
 def _synthetic_quality(P, OL, rng):
     """Quality falls with the tokens spent at low precision, faster early in the sequence."""
     w = {p: rng.uniform(0.0, 0.3) * (max(P) - p) for p in P}

@@ -266,6 +266,20 @@ typedef struct pmpd_learned {
 int32_t pmpd_learned_workspace_size(const pmpd_learned_t* net, int32_t T, size_t* bytes);
 int32_t pmpd_learned_forward(const pmpd_learned_t* net, const void* K, const void* V, int32_t T, void* workspace,
                              size_t workspace_bytes, float* context, float* probs, int32_t* cls, void* stream);
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid it): pmpd_learned_forward with its work area inside the library, a device
+ * array of PMPD_LEARNED_STATIC_BYTES that every GPU the library runs on holds until the process ends.
+ * The call itself calls no hipMalloc, hipFree or other allocating routine; inputs and
+ * outputs are still the caller's and everything else is as for pmpd_learned_forward, whose results it
+ * reproduces bit for bit.  A call whose pmpd_learned_workspace_size exceeds PMPD_LEARNED_STATIC_BYTES
+ * is refused with PMPD_ESIZE (d_v = 4096: T up to about 500 000).  All calls on one GPU share the one
+ * work area: calls that overlap there (different streams, different threads) race and must be
+ * serialised by the caller; calls in stream order on one stream are safe, and nothing a call reads of
+ * the work area is left over from an earlier call. */
+#define PMPD_LEARNED_STATIC_BYTES (4u << 20)
+int32_t pmpd_learned_forward_static(const pmpd_learned_t* net, const void* K, const void* V, int32_t T, float* context,
+                                    float* probs, int32_t* cls, void* stream);
+
 /* Two-precision schedule from a predicted class: `high` bits for steps 0 .. points[cls]-1 and `low` bits
  * from step points[cls] on, points = pmpd_schedule_grid(max_steps, n_points) (host only). */
 int32_t pmpd_schedule_from_class(int32_t high, int32_t low, int32_t cls, int32_t max_steps, int32_t n_points,

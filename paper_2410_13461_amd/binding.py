@@ -25,6 +25,7 @@ EXPORTS = (
     "pmpd_ordered_status", "pmpd_ordered_set_spin_limit",
     "pmpd_fp16_gemv", "pmpd_fp16_stack_workspace_size", "pmpd_fp16_stack_create", "pmpd_fp16_stack_destroy",
     "pmpd_fp16_step", "pmpd_learned_workspace_size", "pmpd_learned_forward", "pmpd_schedule_from_class",
+    "pmpd_learned_forward_static",
 )
 
 QUALITY_FN = ctypes.CFUNCTYPE(ctypes.c_double, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32),
@@ -152,6 +153,8 @@ def _load():
     L.pmpd_learned_workspace_size.argtypes = [P(_Learned), i32, P(sz)]
     L.pmpd_learned_forward.restype = i32
     L.pmpd_learned_forward.argtypes = [P(_Learned), vp, vp, i32, vp, sz, vp, vp, vp, vp]
+    L.pmpd_learned_forward_static.restype = i32
+    L.pmpd_learned_forward_static.argtypes = [P(_Learned), vp, vp, i32, vp, vp, vp, vp]
     L.pmpd_schedule_from_class.restype = i32
     L.pmpd_schedule_from_class.argtypes = [i32, i32, i32, i32, i32, P(vp)]
     L.pmpd_decode_run.restype = i32
@@ -508,6 +511,22 @@ class LearnedScheduler:
         need = ctypes.c_size_t()
         _check(_load().pmpd_learned_workspace_size(ctypes.byref(self._struct), T, ctypes.byref(need)))
         return need.value
+
+    def forward_static(self, K, V, probs, cls, context, stream=None):
+        """forward() through the entry point that allocates nothing: the work area is the library's own
+        device array, and the outputs must be passed in (this wrapper creates no tensor either)."""
+        if K.dim() != 2 or V.dim() != 2:
+            raise PMPDError(-1, "learned scheduler: K and V must be [T, d] matrices")
+        T = int(K.shape[0])
+        if K.shape[1] != self.d_k or V.shape[0] != T or V.shape[1] != self.d_v:
+            raise PMPDError(-1, "learned scheduler: K / V shapes do not fit the parameters")
+        _check(_load().pmpd_learned_forward_static(
+            ctypes.byref(self._struct), _dev_ptr(K, "float16", T * self.d_k, "learned scheduler K"),
+            _dev_ptr(V, "float16", T * self.d_v, "learned scheduler V"), T,
+            _dev_ptr(context, "float32", self.d_v, "learned scheduler context"),
+            _dev_ptr(probs, "float32", self.n_classes, "learned scheduler probs"),
+            _dev_ptr(cls, "int32", 1, "learned scheduler cls"), _stream_handle(stream)))
+        return probs, cls, context
 
     def forward(self, K, V, probs=None, cls=None, context=None, stream=None):
         """K [T, d_k], V [T, d_v]: fp16 device tensors.  Returns (probs, cls, context) device tensors; asynchronous."""

@@ -20,11 +20,39 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
+#include <mutex>
 
 #include "pmpd_common.hpp"
 
+// Work area of pmpd_learned_forward_static: the scores, the partial rows, O and the hidden layer of one
+// call, for callers that may not allocate.  Every GPU the library runs on holds its own copy, at its
+// own address, until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; the address that kernels get is the one that call returns.
+static __device__ __align__(256) unsigned char scratch[PMPD_LEARNED_STATIC_BYTES];
+
 namespace pmpd {
 namespace {
+
+// Device address of `scratch` on the current device, looked up once per device.
+constexpr int kLsMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kLsMaxDevices] = {};
+
+int32_t scratch_of_current_device(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(PMPD_EHIP, "pmpd_learned_forward_static: hipGetDevice: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= kLsMaxDevices) return fail(PMPD_EHIP, "pmpd_learned_forward_static: device index %d outside 0..%d", dev, kLsMaxDevices - 1);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return fail(PMPD_EHIP, "pmpd_learned_forward_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return PMPD_OK;
+}
 
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef float f4 __attribute__((ext_vector_type(4)));
@@ -281,18 +309,23 @@ int32_t pmpd_learned_workspace_size(const pmpd_learned_t* net, int32_t T, size_t
   return PMPD_OK;
 }
 
-int32_t pmpd_learned_forward(const pmpd_learned_t* net, const void* K, const void* V, int32_t T, void* workspace,
-                             size_t workspace_bytes, float* context, float* probs, int32_t* cls, void* stream) {
-  int32_t rc = check_net(net, T, true, "pmpd_learned_forward");
+// The argument checks both entry points share (everything but the work area).
+static int32_t check_forward_args(const pmpd_learned_t* net, const void* K, const void* V, int32_t T, const float* context,
+                                  const float* probs, const int32_t* cls, const char* who) {
+  int32_t rc = check_net(net, T, true, who);
   if (rc) return rc;
-  if (!K || !V || !workspace || !probs || !cls) return fail(PMPD_EINVAL, "pmpd_learned_forward: NULL argument");
+  if (!K || !V || !probs || !cls) return fail(PMPD_EINVAL, "%s: NULL argument", who);
   if (reinterpret_cast<uintptr_t>(K) % 16 || reinterpret_cast<uintptr_t>(V) % 16)
-    return fail(PMPD_EALIGN, "pmpd_learned_forward: K and V must be 16-byte aligned");
-  if (reinterpret_cast<uintptr_t>(workspace) % 256) return fail(PMPD_EALIGN, "pmpd_learned_forward: workspace not 256-byte aligned");
+    return fail(PMPD_EALIGN, "%s: K and V must be 16-byte aligned", who);
   if (reinterpret_cast<uintptr_t>(probs) % 4 || reinterpret_cast<uintptr_t>(cls) % 4 || reinterpret_cast<uintptr_t>(context) % 4)
-    return fail(PMPD_EALIGN, "pmpd_learned_forward: outputs must be 4-byte aligned");
-  const LsPlan p = ls_plan(*net, T);
-  if (workspace_bytes < p.bytes) return fail(PMPD_ESIZE, "pmpd_learned_forward: workspace %zu bytes, need %zu", workspace_bytes, p.bytes);
+    return fail(PMPD_EALIGN, "%s: outputs must be 4-byte aligned", who);
+  return PMPD_OK;
+}
+
+// The five launches, with the work area at `workspace` (device address, p.bytes long).  Every word
+// of the work area that is read has been written by an earlier kernel of the same call.
+static int32_t launch_forward(const pmpd_learned_t* net, const LsPlan& p, const void* K, const void* V, int32_t T, void* workspace,
+                              float* context, float* probs, int32_t* cls, void* stream, const char* who) {
   char* w = static_cast<char*>(workspace);
   float* s = reinterpret_cast<float*>(w + p.off_s);
   float* partial = reinterpret_cast<float*>(w + p.off_partial);
@@ -309,8 +342,33 @@ int32_t pmpd_learned_forward(const pmpd_learned_t* net, const void* K, const voi
   learned_hidden_kernel<<<(net->hidden + kLsWaves - 1) / kLsWaves, kLsThreads, 0, st>>>(net->w1, net->b1, O, net->hidden, net->d_v, hid);
   learned_head_kernel<<<1, kLsThreads, 0, st>>>(net->w2, net->b2, hid, net->hidden, net->n_classes, probs, cls);
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return fail(PMPD_EHIP, "pmpd_learned_forward launch: %s", hipGetErrorString(e));
+  if (e != hipSuccess) return fail(PMPD_EHIP, "%s launch: %s", who, hipGetErrorString(e));
   return PMPD_OK;
+}
+
+int32_t pmpd_learned_forward(const pmpd_learned_t* net, const void* K, const void* V, int32_t T, void* workspace,
+                             size_t workspace_bytes, float* context, float* probs, int32_t* cls, void* stream) {
+  int32_t rc = check_forward_args(net, K, V, T, context, probs, cls, "pmpd_learned_forward");
+  if (rc) return rc;
+  if (!workspace) return fail(PMPD_EINVAL, "pmpd_learned_forward: NULL argument");
+  if (reinterpret_cast<uintptr_t>(workspace) % 256) return fail(PMPD_EALIGN, "pmpd_learned_forward: workspace not 256-byte aligned");
+  const LsPlan p = ls_plan(*net, T);
+  if (workspace_bytes < p.bytes) return fail(PMPD_ESIZE, "pmpd_learned_forward: workspace %zu bytes, need %zu", workspace_bytes, p.bytes);
+  return launch_forward(net, p, K, V, T, workspace, context, probs, cls, stream, "pmpd_learned_forward");
+}
+
+int32_t pmpd_learned_forward_static(const pmpd_learned_t* net, const void* K, const void* V, int32_t T, float* context,
+                                    float* probs, int32_t* cls, void* stream) {
+  int32_t rc = check_forward_args(net, K, V, T, context, probs, cls, "pmpd_learned_forward_static");
+  if (rc) return rc;
+  const LsPlan p = ls_plan(*net, T);
+  if (p.bytes > static_cast<size_t>(PMPD_LEARNED_STATIC_BYTES))
+    return fail(PMPD_ESIZE, "pmpd_learned_forward_static: this call needs %zu bytes of work area, the built-in one holds %zu; use pmpd_learned_forward",
+                p.bytes, static_cast<size_t>(PMPD_LEARNED_STATIC_BYTES));
+  void* work = nullptr;
+  rc = scratch_of_current_device(&work);
+  if (rc) return rc;
+  return launch_forward(net, p, K, V, T, work, context, probs, cls, stream, "pmpd_learned_forward_static");
 }
 
 int32_t pmpd_schedule_from_class(int32_t high, int32_t low, int32_t cls, int32_t max_steps, int32_t n_points,

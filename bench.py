@@ -21,44 +21,41 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
 
 
-def cpu_baseline(shape, seed, bits, budget_s=20.0):
-    """Time the CPU oracle (as it stands) on a bounded sample: rows of block 0's seven projections."""
-    import numpy as np
-
+def cpu_baseline(shape, seed, bits, budget_s=15.0):
+    """Time the CPU oracle (as it stands) on whole blocks of the stack: every row of the seven projections of
+    block 0, then block 1, ... for as long as the budget lasts; the only scaling left is blocks done -> all blocks."""
     import oracle
     import pmpd_synth as synth
 
     threads = oracle.threads()
-    rows_per_layer = 256
-    per_b = {}
-    sample_weights = 0
-    t_total = 0.0
-    layers = []
-    for pi, (nm, o, i) in enumerate(shape.proj_shapes()):
-        q4, s, a = synth.draw_weights(seed, 0, pi, rows_per_layer, i)
-        planes, sa = oracle.pack(q4, s, a)
-        x = synth.draw_x(seed, 0, 0, pi, i)[0]
-        layers.append((planes, sa, rows_per_layer, i, x))
-        sample_weights += rows_per_layer * i
-    for b in bits:
-        t0 = time.perf_counter()
-        for (planes, sa, o, i, x) in layers:
-            oracle.linear_packed(planes, sa, b, o, i, x)
-        dt = time.perf_counter() - t0
-        t_total += dt
-        per_b[b] = dt / sample_weights  # seconds per weight
-        if t_total > budget_s:
+    t_per_b = {b: 0.0 for b in bits}
+    done = 0
+    weights_per_block = sum(o * i for _, o, i in shape.proj_shapes())
+    t_start = time.perf_counter()
+    for blk in range(shape.n_blocks):
+        layers = []
+        for pi, (nm, o, i) in enumerate(shape.proj_shapes()):
+            q4, s, a = synth.draw_weights(seed, blk, pi, o, i)
+            layers.append((q4, s, a, synth.draw_x(seed, 0, blk, pi, i)[0]))
+        for b in bits:
+            t0 = time.perf_counter()
+            for (q4, s, a, x) in layers:
+                oracle.linear(q4, s, a, b, x, want_budget=False)
+            t_per_b[b] += time.perf_counter() - t0
+        done += 1
+        del layers
+        if time.perf_counter() - t_start > budget_s:
             break
-    n_w = shape.n_weights()
-    us = {b: per_b[b] * n_w * 1e6 for b in per_b}
+    scale = shape.n_blocks / done
+    us = {b: t_per_b[b] * scale * 1e6 for b in bits}
     return {
         "value": sum(us.values()) / len(us),
         "unit": "us/token",
         "cores": threads,
         "kind": "oracle",
         "per_bits_us_per_token": {str(b): us[b] for b in us},
-        "sample": f"{rows_per_layer} rows of each of block 0's 7 projections ({sample_weights} weights) per bit-width, "
-                  f"scaled by weight count to the {n_w}-weight stack",
+        "sample": f"every row of all 7 projections of the first {done} of {shape.n_blocks} blocks "
+                  f"({done * weights_per_block} weights, one token) at each bit-width, times {scale:g} for the whole stack",
     }
 
 
@@ -100,8 +97,172 @@ def _timed(fn, n):
     return e0.elapsed_time(e1) / n
 
 
+# ---------------------------------------------------------------------------------------------
+# The other workloads.  Each function measures one of them and returns a dict; `--workload NAME`
+# prints it as a line of its own, and the default run gathers short forms of four of them under
+# "secondary" (the benchmark line's own fields are not touched by that).
+def _device_randn(n, seed):
+    """fp16 ~N(0,1) activations drawn on the device (seeded): host RNG time stays out of the run."""
+    import torch
+
+    g = torch.Generator(device="cuda").manual_seed(seed)
+    return torch.randn(n, device="cuda", generator=g, dtype=torch.float32).half()
+
+
+def wl_schedule(pmpd, synth, stack, seed, reps):
+    """configs[2]: 256 decode steps on the 7B-shaped stack, 64 at 4 bits, 96 at 3, 96 at 2."""
+    import torch
+
+    P, st, n_steps = synth.SCHEDULE_7B_256
+    sch = pmpd.Schedule(P, st, n_steps)
+    x = _device_randn(n_steps * stack.x_elems, seed + 1).view(n_steps, stack.x_elems)
+    y = torch.zeros(stack.y_elems, dtype=torch.float32, device="cuda")
+    run = lambda k0, n: pmpd.decode_run(stack, sch, k0, n, x[k0:], stack.x_elems, y, 0)
+    _ramp(lambda: run(0, 64))
+    phases = [(4, 0, 64), (3, 64, 96), (2, 160, 96)]
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(len(phases) + 1)]
+    tot = {b: 0.0 for b, _, _ in phases}
+    for _ in range(reps):
+        ev[0].record()
+        for j, (b, k0, n) in enumerate(phases):
+            run(k0, n)
+            ev[j + 1].record()
+        torch.cuda.synchronize()
+        for j, (b, _, _) in enumerate(phases):
+            tot[b] += ev[j].elapsed_time(ev[j + 1])
+    per, total_ms = {}, 0.0
+    for b, k0, n in phases:
+        ms = tot[b] / reps
+        total_ms += ms
+        gbps = stack.bytes_at(b) * n / (ms * 1e-3) / 1e9
+        per[str(b)] = {"steps": n, "ms": ms, "us_per_token": ms * 1e3 / n, "GBps": gbps, "frac_of_peak": gbps / HBM_PEAK_GBS,
+                       "launch_shape": stack.variant(b)}
+    overall = sum(stack.bytes_at(b) * n for b, _, n in phases) / (total_ms * 1e-3) / 1e9
+    res = {"workload": "Llama-7B-shaped stack, 256 decode steps, b per step from the schedule 64@4, 96@3, 96@2",
+           "total_ms": total_ms, "avg_bits": sch.avg_bits(n_steps), "per_phase": per, "GBps_overall": overall,
+           "frac_of_peak_overall": overall / HBM_PEAK_GBS, "repetitions": reps}
+    sch.close()
+    return res
+
+
+def wl_single(pmpd, synth, seed, K):
+    """configs[0]: one 4096 x 4096 layer, batch 1.  Latency of an isolated GEMV, and throughput when every launch
+    reads weights that are not in the 256 MB cache (64 packed copies = 570 MB at b = 4)."""
+    import torch
+
+    o = i = 4096
+    n_copies = 64
+    q4, s_, a_ = synth.draw_weights(seed, 0, 0, o, i)
+    planes, sm = pmpd.pack(q4, s_, a_)
+    copies = [pmpd.upload_layer(planes, sm, o, i) for _ in range(n_copies)]
+    x = torch.from_numpy(synth.draw_x(seed, 0, 0, 0, i)[0]).cuda()
+    y = torch.zeros(o, dtype=torch.float32, device="cuda")
+    # the same 64 copies as one list of layers: one launch keeps the memory pipe full across layer boundaries
+    pipelined = pmpd.Stack(copies)
+    xs = x.repeat(n_copies)
+    ys = torch.zeros(pipelined.y_elems, dtype=torch.float32, device="cuda")
+    res = {}
+    for b in (4, 3, 2):
+        warm = lambda: pmpd.gemv(copies[0], b, x, y)
+
+        def cold():
+            for c in copies:
+                pmpd.gemv(c, b, x, y)
+
+        _ramp(cold, 0.3)
+        t_cold = _timed(cold, max(3, K // 5)) * 1e3 / n_copies
+        _ramp(warm, 0.2)
+        t_warm = _timed(warm, 10 * K) * 1e3
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(200):
+            warm()
+            torch.cuda.synchronize()
+        t_iso = (time.perf_counter() - t0) / 200 * 1e6
+        one = lambda: pmpd.decode_step(pipelined, b, xs, ys)
+        _ramp(one, 0.2)
+        t_pipe = _timed(one, K) * 1e3 / n_copies
+        nbytes = copies[0].bytes_at(b)
+        res[f"b{b}"] = {"cold_weights_us": t_cold, "cold_GBps": nbytes / (t_cold * 1e-6) / 1e9,
+                        "warm_back_to_back_us": t_warm, "isolated_launch_and_sync_us": t_iso,
+                        "pipelined_64_copies_one_launch_us": t_pipe,
+                        "pipelined_GBps": nbytes / (t_pipe * 1e-6) / 1e9,
+                        "pipelined_frac_of_peak": nbytes / (t_pipe * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                        "pipelined_launch_shape": pipelined.variant(b)}
+    pipelined.close()
+    return {"workload": "one 4096x4096 layer, batch 1; 64 packed copies rotated (cold weights) or listed in one launch (pipelined)",
+            "results": res}
+
+
+def wl_batches(pmpd, synth, workload, which, seed, K, batches=(1, 2, 3, 4, 8, 16), stacks=None):
+    """configs[3] (which = "mobile": two distinct copies of the mobile-scale stack, alternated, so that no step finds
+    its weights in the 256 MB cache) or the same skinny batches on the 7B-shaped stack (which = "batch7b")."""
+    import torch
+
+    own = stacks is None
+    if own:
+        if which == "batch7b":
+            stacks = [workload.build_stack(synth.LLAMA_7B, seed=seed, verbose=True)[0]] * 2
+        else:
+            stacks = [workload.build_stack(synth.MOBILE, seed=seed + c)[0] for c in range(2)]
+    res = {}
+    for m in batches:
+        X = _device_randn(m * stacks[0].x_elems, seed + 2)
+        Y = torch.zeros(m * stacks[0].y_elems, dtype=torch.float32, device="cuda")
+        unit = "fp8 x fp4 scaled MFMA" if m <= 2 else "int8 MFMA" if m <= 16 else "fp16 MFMA"
+        for b in (4, 3, 2):
+            def step():
+                for stc in stacks:
+                    pmpd.batch_step(stc, b, X, m, Y)
+            _ramp(step, 0.2)
+            ms = _timed(step, K) / 2
+            gbps = stacks[0].bytes_at(b) / (ms * 1e-3) / 1e9
+            res[f"m{m}_b{b}"] = {"us_per_step": ms * 1e3, "GBps": gbps, "frac_of_peak": gbps / HBM_PEAK_GBS, "macs_on": unit}
+    name = "mobile-scale stack (22 blocks, 2048/5632)" if which == "mobile" else "7B-shaped stack (32 blocks, 4096/11008)"
+    out = {"workload": name + (", two alternating copies" if which == "mobile" else "") +
+           ", batch " + "/".join(str(m) for m in batches) + " x b=4/3/2; GB/s counts the weights' bytes only",
+           "launch_shape_batch1": {str(b): stacks[0].variant(b) for b in (4, 3, 2)}, "results": res}
+    if own and which == "mobile":
+        for stc in stacks:
+            stc.close()
+    return out
+
+
+def wl_13b(pmpd, synth, workload, seed, K):
+    """configs[4]: 13B-shaped stack, 512-token prefill at b = 4, then 128 decode steps 48 @ 3 bits + 80 @ 2 bits."""
+    import torch
+
+    shape = synth.LLAMA_13B
+    stack, layers, _ = workload.build_stack(shape, seed=seed, verbose=True)
+    m = 512
+    X = _device_randn(m * stack.x_elems, seed + 3)
+    Y = torch.zeros(m * stack.y_elems, dtype=torch.float32, device="cuda")
+    pre = lambda: pmpd.prefill_step(stack, 4, X, m, Y)
+    _ramp(pre, 0.5)
+    ms_pre = _timed(pre, max(3, K // 10))
+    flops = 2.0 * m * shape.n_weights()
+    P, st, n_steps = synth.SCHEDULE_13B_128
+    sch = pmpd.Schedule(P, st, n_steps)
+    xs = _device_randn(n_steps * stack.x_elems, seed + 4).view(n_steps, stack.x_elems)
+    y = torch.zeros(stack.y_elems, dtype=torch.float32, device="cuda")
+    dec = lambda: pmpd.decode_run(stack, sch, 0, n_steps, xs, stack.x_elems, y, 0)
+    _ramp(dec, 0.5)
+    ms_dec = _timed(dec, max(2, K // 20))
+    dec_bytes = 48 * stack.bytes_at(3) + 80 * stack.bytes_at(2)
+    res = {"workload": "13B-shaped stack (40 blocks, 5120/13824): 512-token prefill at b=4, then 128 decode steps 48@3 + 80@2",
+           "prefill": {"ms": ms_pre, "TFLOPs": flops / (ms_pre * 1e-3) / 1e12,
+                       "frac_of_2500_TFLOPs": flops / (ms_pre * 1e-3) / 1e12 / 2500.0},
+           "decode": {"ms": ms_dec, "avg_bits": sch.avg_bits(n_steps), "GBps": dec_bytes / (ms_dec * 1e-3) / 1e9,
+                      "frac_of_peak": dec_bytes / (ms_dec * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                      "us_per_token": ms_dec * 1e3 / n_steps,
+                      "launch_shape": {str(b): stack.variant(b) for b in (3, 2)}}}
+    sch.close()
+    stack.close()
+    return res
+
+
 def secondary_workload(args) -> int:
-    """The other workloads (parity-tested elsewhere): one JSON line each, for the record in the design doc."""
+    """One of the other workloads as a JSON line of its own."""
     import numpy as np
     import torch
 
@@ -113,39 +274,26 @@ def secondary_workload(args) -> int:
     K = args.steps
     out = {"n_gpus": 1, "data": "synthetic", "steps": K, "warmup": args.warmup}
     if args.workload == "schedule":
-        shape = synth.LLAMA_7B
-        P, st, n_steps = synth.SCHEDULE_7B_256
-        stack, layers, _ = workload.build_stack(shape, seed=args.seed, verbose=True)
-        sch = pmpd.Schedule(P, st, n_steps)
-        xs = np.stack([workload.draw_step_activations(shape, args.seed, k) for k in range(n_steps)])
-        x = torch.from_numpy(xs).cuda()
-        y = torch.zeros(stack.y_elems, dtype=torch.float32, device="cuda")
-        run = lambda k0, n: pmpd.decode_run(stack, sch, k0, n, x[k0:], stack.x_elems, y, 0)
-        _ramp(lambda: run(0, 64))
-        phases = [(4, 0, 64), (3, 64, 96), (2, 160, 96)]
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(len(phases) + 1)]
-        reps = max(1, K // 20)
-        tot = {b: 0.0 for b, _, _ in phases}
-        for _ in range(reps):
-            ev[0].record()
-            for j, (b, k0, n) in enumerate(phases):
-                run(k0, n)
-                ev[j + 1].record()
-            torch.cuda.synchronize()
-            for j, (b, _, _) in enumerate(phases):
-                tot[b] += ev[j].elapsed_time(ev[j + 1])
-        per = {}
-        total_ms = 0.0
-        for b, k0, n in phases:
-            ms = tot[b] / reps
-            total_ms += ms
-            per[str(b)] = {"steps": n, "ms": ms, "us_per_token": ms * 1e3 / n,
-                           "GBps": stack.bytes_at(b) * n / (ms * 1e-3) / 1e9}
+        stack, layers, _ = workload.build_stack(synth.LLAMA_7B, seed=args.seed, verbose=True)
+        r = wl_schedule(pmpd, synth, stack, args.seed, max(1, K // 20))
         out.update({"metric": "total linear-layer time of the 256-step progressive schedule (64@4, 96@3, 96@2)",
-                    "value": total_ms, "unit": "ms", "higher_is_better": False, "avg_bits": sch.avg_bits(n_steps),
-                    "config": {"workload": "Llama-7B-shaped stack, 256 decode steps, b per step from the schedule"},
-                    "per_phase": per,
-                    "GBps_overall": sum(stack.bytes_at(b) * n for b, _, n in phases) / (total_ms * 1e-3) / 1e9})
+                    "value": r["total_ms"], "unit": "ms", "higher_is_better": False, "config": {"workload": r.pop("workload")}})
+        out.update(r)
+    elif args.workload == "single":
+        r = wl_single(pmpd, synth, args.seed, K)
+        out.update({"metric": "single 4096x4096 layer, batch 1: us per GEMV (cold weights, warm back-to-back, isolated launch+sync, 64 copies in one launch)",
+                    "unit": "us", "value": r["results"]["b4"]["cold_weights_us"], "higher_is_better": False,
+                    "config": {"workload": r["workload"]}, "results": r["results"]})
+    elif args.workload in ("mobile", "batch7b"):
+        r = wl_batches(pmpd, synth, workload, args.workload, args.seed, K)
+        out.update({"metric": "us per step at batch 1,2,3,4,8,16", "unit": "us/step",
+                    "value": r["results"]["m1_b4"]["us_per_step"], "higher_is_better": False,
+                    "config": {"workload": r["workload"]}, "launch_shape_batch1": r["launch_shape_batch1"], "results": r["results"]})
+    elif args.workload == "13b":
+        r = wl_13b(pmpd, synth, workload, args.seed, K)
+        out.update({"metric": "13B-shaped stack: 512-token prefill at b=4 (ms) then 128 decode steps 48@3 + 80@2 (ms)",
+                    "unit": "ms", "value": r["prefill"]["ms"] + r["decode"]["ms"], "higher_is_better": False,
+                    "config": {"workload": r["workload"]}, "prefill": r["prefill"], "decode": r["decode"]})
     elif args.workload == "alternate":
         # The paper rejects per-token switching because of the cost of swapping weights in its system
         # (Section 3.2); with the nested plane store a switch is only a different launch argument.
@@ -248,104 +396,17 @@ def secondary_workload(args) -> int:
                             "ordered_one_cooperative_launch_us": pers, "ordered_chained_inputs_us": chain,
                             "matches_one_launch": close, "bit_identical": same, "graph_replays_match": all(replays) if replays else None,
                             "cooperative_matches_one_launch": pers_ok, "chained_finite_and_no_timeout": chain_ok}
+        # nothing of this branch is left for the interpreter's exit handlers to tear down
+        persistent_free.close()
+        persistent_chain.close()
+        for ss in stage_stacks:
+            ss.close()
+        stack.close()
+        g = None
         out.update({"metric": "us/token of the 7B-shaped step launched in dependency order (128 stage launches) vs one launch",
                     "unit": "us/token", "value": res["b4"]["ordered_chained_inputs_us"], "higher_is_better": False,
                     "config": {"workload": "Llama-7B-shaped stack, stages (q,k,v) -> o -> (up,gate) -> down per block"},
                     "results": res})
-    elif args.workload == "single":
-        # One 4096 x 4096 layer: latency of an isolated GEMV on warm weights, and throughput when every
-        # launch reads weights that are not in the 256 MB cache (64 packed copies = 570 MB at b = 4).
-        o = i = 4096
-        n_copies = 64
-        q4, s_, a_ = synth.draw_weights(args.seed, 0, 0, o, i)
-        planes, sm = pmpd.pack(q4, s_, a_)
-        copies = [pmpd.upload_layer(planes, sm, o, i) for _ in range(n_copies)]
-        x = torch.from_numpy(synth.draw_x(args.seed, 0, 0, 0, i)[0]).cuda()
-        y = torch.zeros(o, dtype=torch.float32, device="cuda")
-        # the same 64 copies as one list of layers: one launch keeps the memory pipe full across layer boundaries
-        pipelined = pmpd.Stack(copies)
-        xs = x.repeat(n_copies)
-        ys = torch.zeros(pipelined.y_elems, dtype=torch.float32, device="cuda")
-        res = {}
-        for b in (4, 3, 2):
-            warm = lambda: pmpd.gemv(copies[0], b, x, y)
-            def cold():
-                for c in copies:
-                    pmpd.gemv(c, b, x, y)
-            _ramp(cold, 0.3)
-            t_cold = _timed(cold, max(3, K // 5)) * 1e3 / n_copies
-            _ramp(warm, 0.2)
-            t_warm = _timed(warm, 10 * K) * 1e3
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(200):
-                warm()
-                torch.cuda.synchronize()
-            t_iso = (time.perf_counter() - t0) / 200 * 1e6
-            one = lambda: pmpd.decode_step(pipelined, b, xs, ys)
-            _ramp(one, 0.2)
-            t_pipe = _timed(one, K) * 1e3 / n_copies
-            res[f"b{b}"] = {"cold_weights_us": t_cold, "cold_GBps": copies[0].bytes_at(b) / (t_cold * 1e-6) / 1e9,
-                            "warm_back_to_back_us": t_warm, "isolated_launch_and_sync_us": t_iso,
-                            "pipelined_64_copies_one_launch_us": t_pipe,
-                            "pipelined_GBps": copies[0].bytes_at(b) / (t_pipe * 1e-6) / 1e9}
-        out.update({"metric": "single 4096x4096 layer, batch 1: us per GEMV (cold weights, warm back-to-back, isolated launch+sync, 64 copies in one launch)",
-                    "unit": "us", "value": res["b4"]["cold_weights_us"], "higher_is_better": False,
-                    "config": {"workload": "one 4096x4096 layer, 64 packed copies rotated for the cold-weight figure"},
-                    "results": res})
-    elif args.workload in ("mobile", "batch7b"):
-        if args.workload == "batch7b":
-            # the same skinny batches on the 7B-shaped stack (3.4 GB at b = 4: no copy survives in the cache)
-            shape = synth.LLAMA_7B
-            stacks = [workload.build_stack(shape, seed=args.seed, verbose=True)[0]] * 2
-        else:
-            shape = synth.MOBILE
-            # two distinct copies of the stack, alternated, so that no step finds its weights in the 256 MB cache
-            stacks = [workload.build_stack(shape, seed=args.seed + c)[0] for c in range(2)]
-        res = {}
-        for m in (1, 2, 3, 4, 8, 16):
-            X = torch.randn(m * stacks[0].x_elems, device="cuda").half()
-            Y = torch.zeros(m * stacks[0].y_elems, dtype=torch.float32, device="cuda")
-            for b in (4, 3, 2):
-                def step():
-                    for stc in stacks:
-                        pmpd.batch_step(stc, b, X, m, Y)
-                _ramp(step, 0.3)
-                ms = _timed(step, K) / 2
-                res[f"m{m}_b{b}"] = {"us_per_step": ms * 1e3, "GBps": stacks[0].bytes_at(b) / (ms * 1e-3) / 1e9}
-        for k, v in res.items():
-            v["frac_of_peak"] = v["GBps"] / HBM_PEAK_GBS
-        name = "mobile-scale stack (22 blocks, 2048/5632)" if args.workload == "mobile" else "7B-shaped stack (32 blocks, 4096/11008)"
-        out.update({"metric": name + ", us per step at batch 1,2,3,4,8,16", "unit": "us/step",
-                    "value": res["m1_b4"]["us_per_step"], "higher_is_better": False,
-                    "config": {"workload": name + (", two alternating copies" if args.workload == "mobile" else "") +
-                               ", batch 1/2/3/4/8/16 x b=4/3/2; GB/s counts the weights' bytes only"},
-                    "results": res})
-    elif args.workload == "13b":
-        shape = synth.LLAMA_13B
-        stack, layers, _ = workload.build_stack(shape, seed=args.seed, verbose=True)
-        m = 512
-        X = torch.randn(m * stack.x_elems, device="cuda").half()
-        Y = torch.zeros(m * stack.y_elems, dtype=torch.float32, device="cuda")
-        pre = lambda: pmpd.prefill_step(stack, 4, X, m, Y)
-        _ramp(pre, 0.5)
-        ms_pre = _timed(pre, max(3, K // 10))
-        flops = 2.0 * m * shape.n_weights()
-        P, st, n_steps = synth.SCHEDULE_13B_128
-        sch = pmpd.Schedule(P, st, n_steps)
-        xs = torch.randn((n_steps, stack.x_elems), device="cuda").half()
-        y = torch.zeros(stack.y_elems, dtype=torch.float32, device="cuda")
-        dec = lambda: pmpd.decode_run(stack, sch, 0, n_steps, xs, stack.x_elems, y, 0)
-        _ramp(dec, 0.5)
-        ms_dec = _timed(dec, max(2, K // 20))
-        dec_bytes = 48 * stack.bytes_at(3) + 80 * stack.bytes_at(2)
-        out.update({"metric": "13B-shaped stack: 512-token prefill at b=4 (ms) then 128 decode steps 48@3 + 80@2 (ms)",
-                    "unit": "ms", "value": ms_pre + ms_dec, "higher_is_better": False,
-                    "config": {"workload": "13B-shaped stack (40 blocks, 5120/13824)"},
-                    "prefill": {"ms": ms_pre, "TFLOPs": flops / (ms_pre * 1e-3) / 1e12,
-                                "frac_of_2500_TFLOPs": flops / (ms_pre * 1e-3) / 1e12 / 2500.0},
-                    "decode": {"ms": ms_dec, "avg_bits": sch.avg_bits(n_steps), "GBps": dec_bytes / (ms_dec * 1e-3) / 1e9,
-                               "us_per_token": ms_dec * 1e3 / n_steps}})
     elif args.workload == "learned":
         # learned scheduler, once per prompt: key / value cache of one block of a 7B-shaped model (32 heads x 128),
         # hidden layer of 256 units, 5 candidate switch points; random parameters (trained ones are not public)
@@ -398,6 +459,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--blocks", type=int, default=None, help="debug: fewer blocks (result is then not the named workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-secondary", action="store_true", help="default workload: skip the 'secondary' object (the other configurations)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-graph", action="store_true", help="ordered workload: skip the HIP-graph replay of the stage launches (the profiler's exit handler crashes after captured graphs)")
     ap.add_argument("--workload", default="7b", choices=["7b", "schedule", "alternate", "ordered", "single", "mobile", "batch7b", "13b", "learned"],
@@ -546,7 +608,9 @@ def main() -> int:
         "fp16_reference": fp16_reference,
         "roofline": {
             "bound": "hbm",
-            "kernel": "pmpd_stack_kernel<B=4, SETS=1, NW=4, SPLITK=1> (one launch = one b=4 decode step)",
+            "kernel": "pmpd_stack_kernel<B=4, SETS=1, NW=4, SPLITK=1> (one launch = one b=4 decode step)"
+                      if stack.variant(4) == 0 else f"pmpd_stack_kernel<B=4>, launch shape {stack.variant(4)}",
+            "launch_shape": {str(b): stack.variant(b) for b in bits},
             "achieved": dom["GBps"],
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
@@ -556,9 +620,26 @@ def main() -> int:
             "frac_of_read_stream": dom["GBps"] / stream_gbps,
         },
     }
+    if not args.no_secondary and args.blocks is None:
+        # The other configurations, measured in the same run (each with its own warm-up; stacks smaller than the
+        # 256 MB cache are rotated).  Parity of exactly these stacks and calls: tests/test_gpu_full_size.py.
+        sec = {}
+        print("secondary: 256-step schedule on the 7B stack", file=sys.stderr, flush=True)
+        sec["schedule_256_steps_7b"] = wl_schedule(pmpd, synth, stack, args.seed, max(2, K // 20))
+        stack.close()
+        del stack, layers, x_dev
+        torch.cuda.empty_cache()
+        print("secondary: single 4096x4096 layer", file=sys.stderr, flush=True)
+        sec["single_layer_4096"] = wl_single(pmpd, synth, args.seed, K)
+        print("secondary: mobile-scale stack, batches", file=sys.stderr, flush=True)
+        sec["mobile_stack_batches"] = wl_batches(pmpd, synth, workload, "mobile", args.seed, K, batches=(1, 2, 4, 8, 16))
+        print("secondary: 13B-shaped stack, prefill + decode", file=sys.stderr, flush=True)
+        sec["prefill_and_decode_13b"] = wl_13b(pmpd, synth, workload, args.seed, K)
+        out["secondary"] = sec
+    else:
+        stack.close()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(shape, args.seed, bits)
-    stack.close()
     print(json.dumps(out))
     return 0
 

@@ -173,6 +173,16 @@ def linear(q4, s, a, b: int, x, want_budget: bool = True):
     return y, t
 
 
+def linear_dense(q4, s, a, b: int, x):
+    """linear() with a library matmul as the summation step, for whole layers at hundreds of tokens (the
+    plain loops of linear() take minutes there): the dense fp64 matrix W_b of dequant() (every entry exact),
+    then Y = X W_b^T and T = |X| |W_b|^T by numpy's fp64 matmul.  Same definition; only the order of the fp64
+    additions differs (relative 1e-13).  Returns (Y [m, out], T [m, out])."""
+    W = dequant(q4, s, a, b)
+    X = np.asarray(x, dtype=np.float16).astype(np.float64).reshape(-1, W.shape[1])
+    return X @ W.T, np.abs(X) @ np.abs(W).T
+
+
 def linear_packed(planes, sa, b: int, out_f: int, in_f: int, x, row0: int = 0,
                   nrows: Optional[int] = None, want_budget: bool = True):
     """Same as linear() but from the packed store, reading planes[0..b-1] only."""

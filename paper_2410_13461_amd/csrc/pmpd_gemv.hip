@@ -858,15 +858,16 @@ static constexpr int kNumVariants = 5;
 // which work list (tiles per workgroup: list 0 = 4, 1 = 1, 2 = 2) each variant walks
 static constexpr int kVariantList[kNumVariants] = {0, 1, 2, 1, 1};
 static void pick_variants(pmpd_stack* st) {
-  // Measured on the 7B-, 13B-shaped and mobile-scale stacks: shapes 0..2 are within 2 % of each
-  // other.  Whole-K waves (shape 0) split x once for four tiles and win at b = 4 and 3 when the
-  // stack has enough four-tile workgroups to fill the machine several times; shape 2 otherwise
-  // and at b = 2, where the split of x weighs more against the shorter weight stream.  Short
+  // Measured on the 7B-, 13B-shaped and mobile-scale stacks and on 64 copies of one 4096 x 4096
+  // layer: shapes 0 and 2 are within 2 to 5 % of each other.  Whole-K waves (shape 0) split x once for
+  // four tiles; shape 2 puts twice as many workgroups on the machine.  Stacks with at least 4096
+  // four-tile workgroups: 0 at b = 4 and 3, 2 at b = 2.  Smaller stacks: 2 at b = 4, 0 at b = 3 and 2
+  // (at b = 3 shape 2 loses 2 % on the mobile-scale stack and 5 % on the 64 copies).  Short
   // stacks (the layers of one dependency stage, say) split K further, like single layers.
   const bool big = st->items[0].size() >= 4096;
   st->variant[4] = big ? 0 : 2;
-  st->variant[3] = big ? 0 : 2;
-  st->variant[2] = 2;
+  st->variant[3] = 0;
+  st->variant[2] = big ? 2 : 0;
   const int64_t n_tiles = static_cast<int64_t>(st->items[1].size());
   int min_groups = st->max_in / kGroup;
   for (const LayerDesc& d : st->layers) min_groups = std::min(min_groups, d.n_groups);

@@ -17,11 +17,14 @@ from . import binding
 
 
 def build_stack(shape: synth.StackShape, seed: int = 0, n_blocks: Optional[int] = None, workers: int = 8,
-                keep_host: Optional[set] = None, verbose: bool = False):
+                keep_host: Optional[set] = None, verbose: bool = False, keep_rows=None):
     """Generate, pack and upload every linear layer of `shape`.
 
     Returns (stack, layers, kept) where kept[(block, proj)] = (q4, s, a) for the layer
     indices listed in keep_host (host copies for parity checks; everything else is freed).
+    With keep_rows(block, proj, out_features) -> row indices, kept[(block, proj)] is instead
+    (rows, q4[rows], s[rows], a[rows]) for every layer: a few logical rows per layer, enough to
+    check sampled outputs of a full-size stack without holding its codes on the host.
     """
     n_blocks = shape.n_blocks if n_blocks is None else n_blocks
     todo = [(blk, pi, o, i) for blk in range(n_blocks) for pi, (nm, o, i) in enumerate(shape.proj_shapes())]
@@ -33,7 +36,12 @@ def build_stack(shape: synth.StackShape, seed: int = 0, n_blocks: Optional[int] 
         blk, pi, o, i = job
         q4, s, a = synth.draw_weights(seed, blk, pi, o, i)
         planes, sm = binding.pack(q4, s, a)
-        return job, planes, sm, ((q4, s, a) if (blk, pi) in keep_host else None)
+        if (blk, pi) in keep_host:
+            return job, planes, sm, (q4, s, a)
+        if keep_rows is not None:
+            rows = np.asarray(keep_rows(blk, pi, o), dtype=np.int64)
+            return job, planes, sm, (rows, q4[rows].copy(), s[rows].copy(), a[rows].copy())
+        return job, planes, sm, None
 
     layers: List[binding.PackedLayer] = []
     with ThreadPoolExecutor(max_workers=workers) as pool:

@@ -98,6 +98,19 @@ def test_linear_equals_numpy_matmul_on_dense_matrix(b):
 
 
 # ------------------------------------------- P3: nested bin-midpoint invariant --
+@pytest.mark.parametrize("b", [4, 3, 2])
+def test_linear_dense_is_the_same_definition(b):
+    """The matmul form used for whole layers agrees with the plain loops (themselves pinned by exact
+    rationals above) far below any tolerance in use, and its budget T is the loops' budget."""
+    q4, s, a = synth.draw_weights(41, 0, 0, 70, 384, random_min=True)
+    x = synth.draw_x(41, 0, 0, 0, 384, m=5)
+    y, t = oracle.linear(q4, s, a, b, x)
+    yd, td = oracle.linear_dense(q4, s, a, b, x)
+    assert yd.shape == y.shape == (5, 70)
+    assert np.max(np.abs(yd - y)) <= 1e-12 * np.max(t)
+    assert np.max(np.abs(td - t)) <= 1e-12 * np.max(t)
+
+
 def test_nested_bin_midpoints():
     rng = np.random.default_rng(0)
     s = rng.uniform(1e-3, 1e-2, size=(1, 1)).astype(np.float16)

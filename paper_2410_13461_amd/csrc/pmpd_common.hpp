@@ -44,7 +44,7 @@ struct WorkItem {
 // Work lists of a stack, one per workgroup size in 64-row tiles.
 constexpr int kNumItemLists = 4;
 constexpr int kStackTilesPerWg[kNumItemLists] = {4, 1, 2, 8};
-constexpr int kPrefillItemList = 3;  // the prefill kernel works on 8-tile (512-row) blocks
+constexpr int kEightTileList = 3;  // the 8-wave batch kernels work on 8-tile (512-row) blocks
 
 int32_t check_bits(int32_t b, const char* who);  // b in {2,3,4}
 constexpr int kMaxPrefillRows = 65536;

@@ -817,6 +817,9 @@ static int32_t linear_entry(const char* who, const pmpd_layer_t* layer, int32_t 
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
   if (m > PMPD_MAX_BATCH) {  // compute-bound shape: fp16 MFMA tile kernel
+    // the kernel addresses X with 32-bit byte offsets from the layer's first activation
+    if (static_cast<uint64_t>(m) * static_cast<uint64_t>(d.in_f) * 2u >= (uint64_t{1} << 32))
+      return fail(PMPD_EINVAL, "%s: m x in_features = %d x %d: X of one layer must stay below 4 GiB", who, m, d.in_f);
     e = launch_prefill_layer(d, b, x, m, y, s);
   } else {  // memory-bound shapes: unpack once for all vectors
     e = b == 4 ? launch_layer_b<4>(d, x, m, y, s)
@@ -1312,6 +1315,8 @@ int32_t pmpd_batch_step(const pmpd_stack_t* stack, int32_t b, const void* x_base
         : b == 3 ? launch_stack_batch<3>(stack, x_base, m, y_base, s)
                  : launch_stack_batch<2>(stack, x_base, m, y_base, s);
   } else {
+    if (static_cast<uint64_t>(m) * static_cast<uint64_t>(stack->max_in) * 2u >= (uint64_t{1} << 32))
+      return fail(PMPD_EINVAL, "pmpd_batch_step: m x in_features = %d x %d: X of one layer must stay below 4 GiB", m, stack->max_in);
     e = launch_prefill_stack(stack, b, x_base, m, y_base, s);
   }
   if (e != hipSuccess) return hip_fail(e, "pmpd_batch_step launch");

@@ -33,16 +33,32 @@
 
 namespace pmpd {
 
-constexpr int kPfWaves = 8;             // waves (= 64-row tiles) per workgroup
+constexpr int kPfWaves = 4;             // waves (= 64-row tiles) per workgroup; two workgroups share a compute unit
 constexpr int kPfTokens = 128;          // rows of X per workgroup
 constexpr int kPfThreads = kPfWaves * 64;
 constexpr int kPfMB = kPfTokens / 16;   // 16-token MFMA blocks
-constexpr int kPfXStride = 128 + 8;     // halves per X row in LDS (272 bytes)
-constexpr size_t kPrefillLds = 2 * static_cast<size_t>(kPfTokens) * kPfXStride * 2;
-constexpr int kPfXV = kPfTokens * 16 / kPfThreads;  // uint4 of the X tile per thread
+constexpr int kPfRowBytes = 256;        // one token's 128 columns of a group in LDS
+constexpr int kPfTileBytes = kPfTokens * kPfRowBytes;
+constexpr size_t kPrefillLds = 2 * static_cast<size_t>(kPfTileBytes);
+constexpr int kPfXV = kPfTokens * 16 / kPfThreads;  // 16-byte pieces of the X tile per thread
 
 __device__ __forceinline__ half2_t h2(uint32_t v) { return __builtin_bit_cast(half2_t, v); }
 __device__ __forceinline__ uint32_t u32(half2_t v) { return __builtin_bit_cast(uint32_t, v); }
+
+// X tile in LDS: token row r holds its 16 chunks of 16 bytes (8 columns) at chunk position c ^ swz(r).
+// A ds_read_b128 serves 16 lanes per cycle, and not 16 consecutive ones: the groups are lanes
+// {0-3, 12-15, 20-27}, {4-11, 16-19, 28-31} and the same plus 32 (measured on gfx950 with the bank-conflict
+// counter, one pair of active lanes per dispatch).  The MFMA operand read has lane 16 kb + i fetch chunk
+// 4 kb + s of token i, so a group mixes chunks 4 kb + s and 4 (kb ^ 1) + s: with
+//     swz(i) = i for i < 4,  i + 4 for 4 <= i < 12,  i - 8 for i >= 12     (i = r % 16)
+// tokens {0-3, 12-15} get the values 0..7 and tokens {4-11} the values 8..15; both sets are closed under
+// ^ 4, so the sixteen lanes of every group land in sixteen different 16-byte bank columns (4 cycles per
+// read instead of 8 with rows padded to 272 bytes).  The tile's 16-byte stores (16 consecutive lanes =
+// one row, rows 4 k .. 4 k + 3 per wave) are conflict-free as well.
+__device__ __forceinline__ int pf_swz(int r) {
+  const int hi = (r >> 2) & 3;
+  return (r & 3) | (((0x78 >> (2 * hi)) & 3) << 2);  // hi: 0, 1, 2, 3 -> 0, 2, 3, 1
+}
 
 // 4-bit aligned codes q~ of one 32-bit word of each plane (32 columns of one row): word v holds
 // columns 8 v .. 8 v + 7, nibbles 0,4 / 1,5 / 2,6 / 3,7 = column pairs (0,1) / (2,3) / (4,5) / (6,7).
@@ -56,10 +72,30 @@ __device__ __forceinline__ void code_words(const u32x4 (&pl)[B], int t, uint32_t
   for (int v = 0; v < 4; ++v) code[v] = (B == 2) ? (hi[v] << 2) : ((hi[v] << 2) | lo[v]);
 }
 
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+__device__ __forceinline__ lds_ptr_t to_lds(const void* p) {
+  return reinterpret_cast<lds_ptr_t>(static_cast<uint32_t>(reinterpret_cast<uintptr_t>(p)));  // low half of a generic LDS address
+}
+
 // One workgroup: tokens [mtile * 128, +128) x the 8 row tiles from tile0 of one layer.
+//
+// A wave alternates between a VALU phase (dequantise the four B operands of a K-step: 56 instructions, plus
+// 88 once per group to merge the plane words) and a matrix phase (32 MFMAs fed by 8 LDS reads).  Measured on
+// gfx950 with two-wave probes: one 16x16x32 MFMA per 16 cycles and SIMD, and two VALU instructions of the
+// SIMD's other wave ride under each MFMA for free; but the hardware serves the older wave of a SIMD first
+// and a workgroup barrier per group keeps a workgroup's waves in step, so two waves of ONE workgroup on a
+// SIMD run their VALU phases together and then queue for the matrix pipe together.  A workgroup is therefore
+// four waves, one per SIMD, and two workgroups share a compute unit: the two waves of a SIMD belong to
+// different workgroups, no barrier couples them, and their phases drift apart and overlap.
+// Global loads: the plane words of group g + 2 are requested right after those of group g + 1 have been
+// merged, at the end of group g (their registers are free then), and have a whole group to arrive.  The X
+// tile goes from global memory straight to LDS (no registers, no LDS store instructions), requested one
+// group ahead, right after the barrier that frees its buffer; every wave waits for its own loads before
+// the barrier that ends the next group.  A wait for loads is always a wait for ALL of the wave's loads
+// (the counter is not tracked across the loop's back edge), so new loads are only issued after that wait.
 template <int B>
 __device__ __forceinline__ void prefill_tile(const LayerDesc& L, const _Float16* __restrict__ X, int m_rows,
-                                             float* __restrict__ Y, int mtile, int tile0, _Float16* lds) {
+                                             float* __restrict__ Y, int mtile, int tile0, char* lds) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -71,30 +107,45 @@ __device__ __forceinline__ void prefill_tile(const LayerDesc& L, const _Float16*
   const int tile = tile0 + wave;
   const int tl = tile < L.n_tiles ? tile : L.n_tiles - 1;
   const int64_t tbase = (static_cast<int64_t>(tl) * G) * 64;
-  global_u32x4_ptr pp[B];
+  // Addresses are a wave-uniform 64-bit base (scalar registers) plus a 32-bit byte offset per lane, so that
+  // a pointer costs no vector registers: plane words of group g at plane[k] + (tbase + 64 g) 16 + 16 lane,
+  // (scale, min) words at sa + (tbase / 4 + 16 g) 16 + 16 (lane % 16).
+  const uint32_t plane_lane = static_cast<uint32_t>(lane) * 16u, sa_lane = static_cast<uint32_t>(lane & 15) * 16u;
+  auto uniform = [](const void* p) {  // the same pointer, known to the compiler as wave-uniform
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v)), hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v >> 32));
+    return reinterpret_cast<const char*>((static_cast<uint64_t>(hi) << 32) | lo);
+  };
+  const char* pbase[B];
 #pragma unroll
-  for (int k = 0; k < B; ++k) pp[k] = (global_u32x4_ptr)(L.plane[k]) + tbase + lane;  // + g*64
-  global_u32x4_ptr sp = (global_u32x4_ptr)(L.sa) + tbase / 4 + (lane & 15);         // + g*16
+  for (int k = 0; k < B; ++k) pbase[k] = uniform(static_cast<const char*>(L.plane[k]) + tbase * 16);
+  const char* sbase = uniform(static_cast<const char*>(L.sa) + tbase * 4);
 
-  // X tile copy: 128 rows x 16 uint4; thread handles (row, c) = (idx / 16, idx % 16), idx = tid + 512 i,
-  // i.e. rows tid / 16 + 32 i, the same 16 bytes of each
-  const int xrow = tid >> 4, xc = tid & 15;
-  const uint4* xg = reinterpret_cast<const uint4*>(X) + xc;  // + token * in_f / 8 + g * 16
-  const int64_t xrow_stride = static_cast<int64_t>(in_f / 8);
-  const int xdst = xrow * kPfXStride + xc * 8;
-  auto load_x = [&](uint4 (&xr)[kPfXV], int g) {
+  // X tile: a wave's load instruction i fills the four token rows 4 (wave + 8 i) .. + 3 of the tile, 1 KiB
+  // that the hardware places at consecutive LDS addresses in lane order: lane l is position l % 16 of row
+  // 4 (wave + 8 i) + l / 16 and therefore fetches the chunk that the swizzle puts there.  Rows 32 i apart
+  // share r % 16, so the lane's chunk is the same for its four loads.  Tokens past the end repeat the last
+  // one (their outputs are never stored).  Byte offsets from X fit 32 bits (checked by the launcher).
+  const int xrow = 4 * wave + (lane >> 4);
+  const int xchunk = (lane & 15) ^ pf_swz(xrow);
+  uint32_t xoff[kPfXV];
 #pragma unroll
-    for (int i = 0; i < kPfXV; ++i) {
-      const int token = m0 + xrow + 32 * i;
-      xr[i] = token < m_rows ? xg[token * xrow_stride + g * 16] : make_uint4(0, 0, 0, 0);
-    }
-  };
-  auto store_x = [&](const uint4 (&xr)[kPfXV], _Float16* buf) {
+  for (int i = 0; i < kPfXV; ++i) {
+    int token = m0 + xrow + 4 * kPfWaves * i;
+    token = token < m_rows ? token : m_rows - 1;
+    xoff[i] = static_cast<uint32_t>(token) * static_cast<uint32_t>(in_f) * 2u + static_cast<uint32_t>(xchunk) * 16u;
+  }
+  const char* xbase = uniform(X);
+  auto request_x = [&](int g, char* buf) {
+    const char* xg = xbase + g * (kGroup * 2);
 #pragma unroll
-    for (int i = 0; i < kPfXV; ++i) *reinterpret_cast<uint4*>(buf + xdst + 32 * i * kPfXStride) = xr[i];
+    for (int i = 0; i < kPfXV; ++i)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(xg + xoff[i]),
+                                       to_lds(buf + (4 * wave + 4 * kPfWaves * i) * kPfRowBytes), 16, 0, 0);
   };
-  // A operand of this lane: token 16 mb + lane % 16, columns 32 (lane / 16) + 8 s
-  const int a_off = (lane & 15) * kPfXStride + (lane >> 4) * 32;
+  // A operand of this lane for K-step s: token 16 mb + lane % 16, chunk 4 (lane / 16) + s
+  const int a_row = (lane & 15) * kPfRowBytes;
+  const int a_col = (4 * (lane >> 4)) ^ pf_swz(lane & 15);  // chunk position of K-step s: a_col ^ s
 
   float4_t acc[kPfMB][4];
 #pragma unroll
@@ -110,74 +161,92 @@ __device__ __forceinline__ void prefill_tile(const LayerDesc& L, const _Float16*
   uint32_t magic = 0x64006400u;  // fp16 pair (1024, 1024)
   asm volatile("" : "+v"(magic));
 
-  // group 0: plane words and X tile
-  u32x4 pc[B], sac;
-#pragma unroll
-  for (int k = 0; k < B; ++k) pc[k] = pp[k][0];
-  sac = sp[0];
-  {
-    uint4 xr[kPfXV];
-    load_x(xr, 0);
-    store_x(xr, lds);
-  }
-  __syncthreads();
+  u32x4 pc[B], sac;           // plane words and (scale, min) words of the group that is merged next
+  uint32_t code[4][4];        // codes of the group being dequantised: [16-row block][K-step]
+  half2_t sa[4];              // (scale, min) of the lane's four rows
+  u32x4 bw[4];                // B operands of one K-step
 
-  for (int g = 0; g < G; ++g) {
-    const _Float16* xs = lds + (g & 1) * (kPfTokens * kPfXStride);
-    _Float16* xn = lds + ((g + 1) & 1) * (kPfTokens * kPfXStride);
-    // ---- codes of the lane's 4 x 32 weights, scale / min pairs of its 4 rows
-    uint32_t code[4][4];
-    half2_t s2[4], a2[4];
+  // Once per group: codes of the lane's 4 x 32 weights, scale / min pairs of its 4 rows.
+  auto merge = [&]() {
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       code_words<B>(pc, t, code[t]);
-      const uint32_t w = word_of(sac, t);
-      const _Float16 sv = __builtin_bit_cast(_Float16, static_cast<uint16_t>(w & 0xffffu));
-      const _Float16 av = __builtin_bit_cast(_Float16, static_cast<uint16_t>(w >> 16));
-      s2[t] = half2_t{sv, sv};
-      a2[t] = half2_t{av, av};
+      sa[t] = h2(word_of(sac, t));
     }
-    // ---- the plane words are consumed: the loads of the next group reuse their registers and fly
-    // while this group is multiplied; its X tile goes to the other LDS buffer after the first K-step
-    const int gn = g + 1 < G ? g + 1 : g;
-    uint4 xr[kPfXV];
-    load_x(xr, gn);
+  };
+  auto request_planes = [&](int g) {
+    const int gn = g < G ? g : G - 1;
 #pragma unroll
-    for (int k = 0; k < B; ++k) pc[k] = pp[k][gn * 64];
-    sac = sp[gn * 16];
-    // ---- 4 K-steps of 32: dequantise the 4 B operands, then 8 x 4 MFMAs
-    half8_t af = *reinterpret_cast<const half8_t*>(xs + a_off);
+    for (int k = 0; k < B; ++k) pc[k] = *(global_u32x4_ptr)(pbase[k] + gn * 1024 + plane_lane);
+    sac = *(global_u32x4_ptr)(sbase + gn * 256 + sa_lane);
+  };
+  // VALU phase: the four B operands of K-step s.  Exact codes q~ + 2^(3-b) (low-nibble pairs carry 1024 + q~,
+  // high-nibble pairs 1024 + 16 q~), then one fused multiply-add with the row's scale and minimum, which
+  // the instruction's operand selects broadcast from the two halves of one register.
+  auto dequant = [&](int s) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const uint32_t w = code[t][s], w8 = w >> 8;
+      const half2_t sc = {sa[t].x, sa[t].x}, mn = {sa[t].y, sa[t].y};
+      const half2_t q0 = h2(and_or(w, maskL, magic)) + cL;
+      const half2_t q1 = __builtin_elementwise_fma(h2(and_or(w, maskH, magic)), sixteenth, cH);
+      const half2_t q2 = h2(and_or(w8, maskL, magic)) + cL;
+      const half2_t q3 = __builtin_elementwise_fma(h2(and_or(w8, maskH, magic)), sixteenth, cH);
+      bw[t].x = u32(__builtin_elementwise_fma(q0, sc, mn));
+      bw[t].y = u32(__builtin_elementwise_fma(q1, sc, mn));
+      bw[t].z = u32(__builtin_elementwise_fma(q2, sc, mn));
+      bw[t].w = u32(__builtin_elementwise_fma(q3, sc, mn));
+    }
+  };
+  // Matrix phase: 8 token blocks x 4 row blocks; the operands of the next two token blocks are on their way
+  // from LDS while the MFMAs of one block issue.
+  auto multiply = [&](int s, const char* xs) {
+    const char* ap = xs + a_row + ((a_col ^ s) << 4);
+    half8_t af[3];
+    af[0] = *reinterpret_cast<const half8_t*>(ap);
+    af[1] = *reinterpret_cast<const half8_t*>(ap + 16 * kPfRowBytes);
+#pragma unroll
+    for (int mb = 0; mb < kPfMB; ++mb) {
+      if (mb + 2 < kPfMB) af[(mb + 2) % 3] = *reinterpret_cast<const half8_t*>(ap + (mb + 2) * 16 * kPfRowBytes);
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+        acc[mb][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[mb % 3], __builtin_bit_cast(half8_t, bw[t]), acc[mb][t], 0, 0, 0);
+    }
+  };
+  auto phase_end = []() { __builtin_amdgcn_sched_barrier(0); };  // phases stay apart in the instruction stream
+
+  // All of a wave's outstanding loads have arrived (the LDS writes of its X loads included).
+  auto loads_landed = []() {
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0), other counters untouched
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  // group 0: X tile to buffer 0, plane words merged; group 1 requested
+  request_x(0, lds);
+  request_planes(0);
+  merge();
+  loads_landed();
+  request_planes(1);
+  __syncthreads();
+  if (G > 1) request_x(1, lds + kPfTileBytes);
+
+  for (int g = 0; g < G; ++g) {
+    const char* xs = lds + (g & 1) * kPfTileBytes;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
-      half8_t bw[4];
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const uint32_t w = code[t][s], w8 = w >> 8;
-        // exact codes q~ + 2^(3-b): low-nibble pairs carry 1024 + q~, high-nibble pairs 1024 + 16 q~
-        const half2_t q0 = h2(and_or(w, maskL, magic)) + cL;
-        const half2_t q1 = __builtin_elementwise_fma(h2(and_or(w, maskH, magic)), sixteenth, cH);
-        const half2_t q2 = h2(and_or(w8, maskL, magic)) + cL;
-        const half2_t q3 = __builtin_elementwise_fma(h2(and_or(w8, maskH, magic)), sixteenth, cH);
-        u32x4 o;
-        o.x = u32(__builtin_elementwise_fma(q0, s2[t], a2[t]));
-        o.y = u32(__builtin_elementwise_fma(q1, s2[t], a2[t]));
-        o.z = u32(__builtin_elementwise_fma(q2, s2[t], a2[t]));
-        o.w = u32(__builtin_elementwise_fma(q3, s2[t], a2[t]));
-        bw[t] = __builtin_bit_cast(half8_t, o);
-      }
-#pragma unroll
-      for (int mb = 0; mb < kPfMB; ++mb) {
-        const half8_t a_cur = af;
-        // the operand of the next MFMA block is read from LDS before the MFMAs of this one issue
-        const int nmb = mb + 1 < kPfMB ? mb + 1 : 0, ns = mb + 1 < kPfMB ? s : s + 1;
-        if (ns < 4) af = *reinterpret_cast<const half8_t*>(xs + a_off + nmb * 16 * kPfXStride + ns * 8);
-#pragma unroll
-        for (int t = 0; t < 4; ++t) acc[mb][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_cur, bw[t], acc[mb][t], 0, 0, 0);
-      }
-      if (s == 0) store_x(xr, xn);
-      __builtin_amdgcn_sched_barrier(0);  // keep the dequantised operands of one K-step live at a time
+      dequant(s);
+      phase_end();
+      multiply(s, xs);
+      phase_end();
     }
-    __syncthreads();
+    // The loads of group g + 1 (plane words, then X tile) were issued a group ago: merge the plane words, make
+    // sure the X tile has landed, and only then issue new loads, so that no wait ever covers a fresh load.
+    merge();
+    loads_landed();
+    request_planes(g + 2);
+    __syncthreads();  // every wave's part of X tile g + 1 is in LDS, and buffer g % 2 is free
+    if (g + 2 < G) request_x(g + 2, lds + (g & 1) * kPfTileBytes);
   }
 
   // ---- store: D[i][j] of a 16 x 16 block sits in lane j + 16 (i / 4), register i % 4
@@ -204,7 +273,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void pmpd_prefill_layer_kernel(Layer
   extern __shared__ uint4 lds_raw[];
   const int mtile = static_cast<int>(blockIdx.x) % m_tiles;
   const int ntile = static_cast<int>(blockIdx.x) / m_tiles;
-  prefill_tile<B>(L, X, m, Y, mtile, ntile * kPfWaves, reinterpret_cast<_Float16*>(lds_raw));
+  prefill_tile<B>(L, X, m, Y, mtile, ntile * kPfWaves, reinterpret_cast<char*>(lds_raw));
 }
 
 template <int B>
@@ -217,7 +286,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void pmpd_prefill_stack_kernel(const
   const WorkItem it = items[static_cast<int>(blockIdx.x) / m_tiles];
   const LayerDesc L = layers[it.layer];
   prefill_tile<B>(L, x_base + static_cast<int64_t>(m) * L.x_off, m, y_base + static_cast<int64_t>(m) * L.y_off, mtile,
-                  it.tile0, reinterpret_cast<_Float16*>(lds_raw));
+                  it.tile0, reinterpret_cast<char*>(lds_raw));
 }
 
 // The X tile needs more than the 64 KiB of dynamic LDS a kernel gets by default.
@@ -245,10 +314,12 @@ hipError_t launch_prefill_layer(const LayerDesc& d, int b, const void* X, int m,
 
 hipError_t launch_prefill_stack(const pmpd_stack* st, int b, const void* X, int m, float* Y, hipStream_t s) {
   const int m_tiles = (m + kPfTokens - 1) / kPfTokens;
-  const size_t n_items = st->items[kPrefillItemList].size();
+  constexpr int kList = 0;  // work list of 4-tile items: one 64-row tile per wave
+  static_assert(kStackTilesPerWg[kList] == kPfWaves, "one tile per wave");
+  const size_t n_items = st->items[kList].size();
   const unsigned grid = static_cast<unsigned>(m_tiles) * static_cast<unsigned>(n_items);
   const _Float16* x = static_cast<const _Float16*>(X);
-  const WorkItem* items = st->d_items[kPrefillItemList];
+  const WorkItem* items = st->d_items[kList];
   hipError_t e = b == 4 ? allow_lds(&pmpd_prefill_stack_kernel<4>)
                  : b == 3 ? allow_lds(&pmpd_prefill_stack_kernel<3>)
                           : allow_lds(&pmpd_prefill_stack_kernel<2>);

@@ -281,7 +281,7 @@ __global__ __launch_bounds__(NW * 64, sk_waves_per_simd<SETS>()) void pmpd_skinn
 
 template <int B, int SETS, int NW>
 static hipError_t launch_skinny(const pmpd_stack* st, const _Float16* x, int m, float* y, hipStream_t s) {
-  constexpr int list = NW == 8 ? kPrefillItemList : 0;
+  constexpr int list = NW == 8 ? kEightTileList : 0;
   static_assert(kStackTilesPerWg[list] == NW, "one tile per wave");
   // a layer's chunk is at most what the budget holds and at most its own number of groups
   const size_t lds = static_cast<size_t>(std::min(sk_budget(NW) / sk_group_bytes(m), st->max_in / kGroup)) * sk_group_bytes(m);

@@ -7,20 +7,20 @@
 //
 // The weights never touch LDS.  In the storage format lane 16 kb + j of a wave holds, in word t
 // of its 16 bytes of a plane, 32 columns (32 kb .. 32 kb + 31 of the group) of row 16 t + j.  The
-// B operand of the 16x16x32 MFMA wants, in lane 16 kb + j, column j of B for K = 8 kb .. 8 kb + 7:
-// taking weight row 16 t + j as column j and the lane's columns 32 kb + 8 s .. 32 kb + 8 s + 7 as
+// first operand of the 16x16x32 MFMA wants, in lane 16 kb + j, row j for K = 8 kb .. 8 kb + 7:
+// taking weight row 16 t + j as row j and the lane's columns 32 kb + 8 s .. 32 kb + 8 s + 7 as
 // its K slice (s = 0..3), the lane's own words are four operands per t after dequantisation,
 //     w = fp16(a_g + s_g * (q~ + 2^(3-b)))    (exact code, then one fused multiply-add),
-// with the K index of MFMA s meaning column 32 kb + 8 s + e of the group for K = 8 kb + e.  The A
-// operand (rows = 16 tokens) follows the same K order: lane 16 kb + i reads the 16 bytes at
+// with the K index of MFMA s meaning column 32 kb + 8 s + e of the group for K = 8 kb + e.  The
+// second operand (columns = 16 tokens) follows the same K order: lane 16 kb + i reads the 16 bytes at
 // columns 32 kb + 8 s of token i from the X tile in LDS.
 //
-// Workgroup = 8 waves; wave w owns row tile tile0 + w (64 weight rows) and all 128 tokens of the
+// Workgroup = 4 waves; wave w owns row tile tile0 + w (64 weight rows) and all 128 tokens of the
 // block: 8 x 4 accumulator blocks of 16 x 16 (128 registers).  Per group of 128 columns a wave
 // dequantises its 128 weights per lane once and issues 128 MFMAs; the workgroup shares one X tile
-// (128 tokens x 128 columns, double-buffered in LDS, rows padded to 272 bytes so that the 16-byte
-// operand reads of 16 consecutive lanes fall into different banks).  Plane words, (scale, min)
-// words and the X tile of the next group are loaded while the current one is multiplied.
+// (128 tokens x 128 columns, double-buffered in LDS in a swizzled layout whose 16-byte operand reads
+// are free of bank conflicts).  Plane words, (scale, min) words and the X tile of the next group are
+// loaded while the current one is multiplied.
 // The weight is rounded to fp16 once (relative error 2^-11 per weight, about 3e-4 relative L2
 // on y, inside the 1e-3 bar); the decode kernels keep exact codes instead because there the
 // per-group scaling is free.
@@ -198,20 +198,41 @@ __device__ __forceinline__ void prefill_tile(const LayerDesc& L, const _Float16*
       bw[t].w = u32(__builtin_elementwise_fma(q3, sc, mn));
     }
   };
-  // Matrix phase: 8 token blocks x 4 row blocks; the operands of the next two token blocks are on their way
-  // from LDS while the MFMAs of one block issue.
+  // Matrix phase: 8 token blocks x 4 row blocks.  The A operands are read from LDS three blocks ahead into
+  // a ring of four.  LDS reads complete in order, so before the MFMAs of block mb it is enough to wait until
+  // at most the reads issued after block mb's are outstanding.  The compiler's own wait insertion does not do
+  // that here (it waits for every read, the one just issued included, which puts most of an LDS latency in
+  // front of every other block), so the reads and their waits are written out: the read is an asm statement
+  // whose result the compiler takes as available at once, and the wait is an asm statement that "modifies"
+  // the operand registers, so that the MFMAs that use them cannot be moved in front of it.  No other LDS or
+  // scalar-memory access is outstanding during the phase.
   auto multiply = [&](int s, const char* xs) {
-    const char* ap = xs + a_row + ((a_col ^ s) << 4);
-    half8_t af[3];
-    af[0] = *reinterpret_cast<const half8_t*>(ap);
-    af[1] = *reinterpret_cast<const half8_t*>(ap + 16 * kPfRowBytes);
+    const uint32_t ap = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(xs + a_row + ((a_col ^ s) << 4)));  // LDS address
+    half8_t af[4];
+#define PMPD_PF_READ(dst, block) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(ap), "n"((block) * 16 * kPfRowBytes))
+    PMPD_PF_READ(af[0], 0);
+    PMPD_PF_READ(af[1], 1);
+    PMPD_PF_READ(af[2], 2);
 #pragma unroll
     for (int mb = 0; mb < kPfMB; ++mb) {
-      if (mb + 2 < kPfMB) af[(mb + 2) % 3] = *reinterpret_cast<const half8_t*>(ap + (mb + 2) * 16 * kPfRowBytes);
+      half8_t& a = af[mb & 3];
+      // reads issued so far: min(mb + 3, 8); those after block mb's may stay outstanding
+      if (mb + 3 <= kPfMB) asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(a));
+      else if (mb + 2 == kPfMB) asm volatile("s_waitcnt lgkmcnt(1)" : "+v"(a));
+      else asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a));
 #pragma unroll
       for (int t = 0; t < 4; ++t)
-        acc[mb][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af[mb % 3], __builtin_bit_cast(half8_t, bw[t]), acc[mb][t], 0, 0, 0);
+        acc[mb][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, bw[t]), a, acc[mb][t], 0, 0, 0);
+      switch (mb) {  // the read for three blocks on (offsets are immediates)
+        case 0: PMPD_PF_READ(af[3], 3); break;
+        case 1: PMPD_PF_READ(af[0], 4); break;
+        case 2: PMPD_PF_READ(af[1], 5); break;
+        case 3: PMPD_PF_READ(af[2], 6); break;
+        case 4: PMPD_PF_READ(af[3], 7); break;
+        default: break;
+      }
     }
+#undef PMPD_PF_READ
   };
   auto phase_end = []() { __builtin_amdgcn_sched_barrier(0); };  // phases stay apart in the instruction stream
 
@@ -249,19 +270,27 @@ __device__ __forceinline__ void prefill_tile(const LayerDesc& L, const _Float16*
     if (g + 2 < G) request_x(g + 2, lds + (g & 1) * kPfTileBytes);
   }
 
-  // ---- store: D[i][j] of a 16 x 16 block sits in lane j + 16 (i / 4), register i % 4
+  // ---- store.  The weights are the first MFMA operand (rows i of D = weight rows) and X the second (columns
+  // j = tokens): D[i][j] sits in lane j + 16 (i / 4), register i % 4, so a lane holds four consecutive
+  // output features of one token, 16 bytes of Y.  They go out as one 16-byte store where Y allows it (written
+  // once, never read here: nontemporal).
   if (tile < L.n_tiles) {
+    const bool wide = (reinterpret_cast<uintptr_t>(Y) % 16 == 0) && (L.out_f % 4 == 0);
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const int col = tile * 64 + 16 * t + (lane & 15);
-      if (col < L.out_f) {
+    for (int mb = 0; mb < kPfMB; ++mb) {
+      const int row = m0 + 16 * mb + (lane & 15);
+      if (row >= m_rows) continue;
+      float* yrow = Y + static_cast<int64_t>(row) * L.out_f;
 #pragma unroll
-        for (int mb = 0; mb < kPfMB; ++mb)
+      for (int t = 0; t < 4; ++t) {
+        const int col = tile * 64 + 16 * t + 4 * (lane >> 4);
+        if (wide) {
+          if (col < L.out_f) __builtin_nontemporal_store(acc[mb][t], reinterpret_cast<float4_t*>(yrow + col));
+        } else {
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const int row = m0 + 16 * mb + 4 * (lane >> 4) + r;
-            if (row < m_rows) Y[static_cast<int64_t>(row) * L.out_f + col] = acc[mb][t][r];
-          }
+          for (int r = 0; r < 4; ++r)
+            if (col + r < L.out_f) yrow[col + r] = acc[mb][t][r];
+        }
       }
     }
   }

@@ -236,7 +236,8 @@ __device__ __forceinline__ void skinny_tiles(const LayerDesc& L, int tile0, cons
           for (int s = 0; s < SETS; ++s) {
             i32x4 d = __builtin_amdgcn_mfma_i32_16x16x64_i8(A[s][0], op[0], i32x4{0, 0, 0, 0}, 0, 0, 0);
             d = __builtin_amdgcn_mfma_i32_16x16x64_i8(A[s][1], op[1], d, 0, 0, 0);
-            const float f = fmaf(static_cast<float>(d[0]), 65536.f, fmaf(static_cast<float>(d[1]), 256.f, static_cast<float>(d[2])));
+            // 65536 D2 + 256 D1 + D0: the two low digits are added as integers (below 2^27), one conversion fewer
+            const float f = fmaf(static_cast<float>(d[0]), 65536.f, static_cast<float>((d[1] << 8) + d[2]));
             yacc[s][t] = fmaf(sc * rs[s], f, yacc[s][t]);
             yacc[s][t] = fmaf(off, xg[s], yacc[s][t]);
           }

@@ -423,8 +423,8 @@ __device__ __forceinline__ void prefill_tile(const LayerDesc& L, const _Float16*
 
   // ---- store.  The weights are the first MFMA operand (rows i of D = weight rows) and X the second (columns
   // j = tokens): D[i][j] sits in lane j + 16 (i / 4), register i % 4, so a lane holds four consecutive
-  // output features of one token, 16 bytes of Y.  They go out as one 16-byte store where Y allows it (written
-  // once, never read here: nontemporal).
+  // output features of one token, 16 bytes of Y.  They go out as one 16-byte store where Y allows it.  (Plain
+  // stores: the write-back caches absorb the burst at the end of a workgroup; nontemporal ones measured 4 % slower.)
   if (tile < L.n_tiles) {
     const bool wide = (reinterpret_cast<uintptr_t>(Y) % 16 == 0) && (L.out_f % 4 == 0);
 #pragma unroll
@@ -439,7 +439,7 @@ __device__ __forceinline__ void prefill_tile(const LayerDesc& L, const _Float16*
 #pragma unroll
         for (int r = 0; r < 4; ++r) asm volatile("v_accvgpr_read_b32 %0, a[%1]" : "=v"(d[r]) : "n"(16 * mb + 4 * t + r));
         if (wide) {
-          if (col < L.out_f) __builtin_nontemporal_store(d, reinterpret_cast<float4_t*>(yrow + col));
+          if (col < L.out_f) *reinterpret_cast<float4_t*>(yrow + col) = d;
         } else {
 #pragma unroll
           for (int r = 0; r < 4; ++r)
@@ -465,6 +465,9 @@ __global__ __launch_bounds__(kPfThreads, 1) void pmpd_prefill_stack_kernel(const
                                                                      const _Float16* __restrict__ x_base, int m,
                                                                      float* __restrict__ y_base, int m_tiles) {
   extern __shared__ uint4 lds_raw[];
+  // Workgroups go to the 8 XCDs round-robin: with the token block as the fast index, an XCD sees one token block
+  // (two of them: even XCDs the first, odd XCDs the second) and its L2 holds that block's X for all its workgroups.
+  // (Placing the token blocks of an item on one XCD instead, to share the plane words, measured slower.)
   const int mtile = static_cast<int>(blockIdx.x) % m_tiles;
   const WorkItem it = items[static_cast<int>(blockIdx.x) / m_tiles];
   const LayerDesc L = layers[it.layer];

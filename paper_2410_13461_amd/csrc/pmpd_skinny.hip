@@ -135,19 +135,43 @@ __device__ __forceinline__ void sk_stage4(const uint4& v, int cn, int gb, const 
 }
 
 // Bytes of the 4-bit aligned codes (B = 2: of q~ / 4) of 16-row block t: two operands of 16 bytes.
+// With r1 = odd bits of plane 0 and even bits of plane 1, r2 the other way round (s1, s2 the same from planes 2, 3),
+// the upper two bits of the nibbles of the four code words are r1 << 2, r1, rotl(r2, 3), r2 << 1 under the mask
+// 0xCCCCCCCC and the lower two s1, s1 >> 2, rotl(s2, 1), s2 >> 1 under its complement, so one 3-input boolean
+// operation joins a code word: 14 instructions per 16 rows and group, then 3 per code word to spread the nibbles
+// into bytes.  With three planes the lower halves come from plane 2 alone (its odd bits for words 0, 1, its even
+// bits for words 2, 3: the bit the complement mask keeps is then the plane's, the other is zero).  With two planes
+// the bytes are cut out of r1 and r2 directly.
 template <int B>
 __device__ __forceinline__ void code_bytes(const u32x4 (&pl)[B], int t, i32x4 (&op)[2]) {
-  uint32_t hi[4], lo[4], code[4];
-  pair_words(word_of(pl[0], t), word_of(pl[1], t), hi);
-  if constexpr (B == 4) pair_words(word_of(pl[2], t), word_of(pl[3], t), lo);
-  if constexpr (B == 3) single_words(word_of(pl[2], t), lo);
-  const uint32_t m = opaque_sgpr(0x0F0F0F0Fu);
-#pragma unroll
-  for (int v = 0; v < 4; ++v) code[v] = (B == 2) ? hi[v] : ((hi[v] << 2) | lo[v]);
-#pragma unroll
-  for (int h = 0; h < 2; ++h)
-    op[h] = i32x4{static_cast<int>(code[2 * h] & m), static_cast<int>((code[2 * h] >> 4) & m),
-                  static_cast<int>(code[2 * h + 1] & m), static_cast<int>((code[2 * h + 1] >> 4) & m)};
+  const uint32_t odd = opaque_sgpr(0xAAAAAAAAu);
+  const uint32_t h0 = word_of(pl[0], t), l0 = word_of(pl[1], t);
+  const uint32_t r1 = bfi(odd, h0, l0), r2 = bfi(odd, l0, h0);
+  if constexpr (B == 2) {
+    const uint32_t m2 = opaque_sgpr(0x03030303u);
+    op[0] = i32x4{static_cast<int>(r1 & m2), static_cast<int>((r1 >> 4) & m2), static_cast<int>((r1 >> 2) & m2),
+                  static_cast<int>((r1 >> 6) & m2)};
+    op[1] = i32x4{static_cast<int>(__builtin_amdgcn_alignbit(r2, r2, 31) & m2), static_cast<int>((r2 >> 3) & m2),
+                  static_cast<int>((r2 >> 1) & m2), static_cast<int>((r2 >> 5) & m2)};
+  } else {
+    const uint32_t top = opaque_sgpr(0xCCCCCCCCu), m = opaque_sgpr(0x0F0F0F0Fu);
+    uint32_t s1, s2, d;
+    if constexpr (B == 4) {
+      const uint32_t h1 = word_of(pl[2], t), l1 = word_of(pl[3], t);
+      s1 = bfi(odd, h1, l1);
+      s2 = bfi(odd, l1, h1);
+      d = __builtin_amdgcn_alignbit(s2, s2, 31);
+    } else {
+      const uint32_t h1 = word_of(pl[2], t);
+      s1 = h1 & odd;
+      s2 = h1 & opaque_sgpr(0x55555555u);
+      d = s2 << 1;
+    }
+    const uint32_t c0 = bfi(top, r1 << 2, s1), c1 = bfi(top, r1, s1 >> 2);
+    const uint32_t c2 = bfi(top, __builtin_amdgcn_alignbit(r2, r2, 29), d), c3 = bfi(top, r2 << 1, s2 >> 1);
+    op[0] = i32x4{static_cast<int>(c0 & m), static_cast<int>((c0 >> 4) & m), static_cast<int>(c1 & m), static_cast<int>((c1 >> 4) & m)};
+    op[1] = i32x4{static_cast<int>(c2 & m), static_cast<int>((c2 >> 4) & m), static_cast<int>(c3 & m), static_cast<int>((c3 >> 4) & m)};
+  }
 }
 
 template <int B, int SETS, int NW>

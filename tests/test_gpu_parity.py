@@ -170,7 +170,10 @@ def test_gemm_skinny_matches_oracle(pmpd, b, m):
 
 
 @pytest.mark.parametrize("b", [4, 3, 2])
-@pytest.mark.parametrize("m,out_f,in_f", [(16, 200, 512), (100, 130, 2048), (512, 256, 1408), (129, 320, 5120)])
+# the prefill tile is 256 tokens x 4 row tiles of 64, groups taken two at a time: token counts around one and two
+# tiles, ragged row counts (multiples of 4 and not), 1, 2, 3, 5 and 11 groups
+@pytest.mark.parametrize("m,out_f,in_f", [(16, 200, 512), (100, 130, 2048), (512, 256, 1408), (129, 320, 5120),
+                                          (257, 64, 128), (300, 192, 256), (256, 70, 384), (255, 64, 640), (513, 260, 256)])
 def test_gemm_prefill_matches_oracle(pmpd, b, m, out_f, in_f):
     """m > 8 takes the MFMA path: ragged M and N tiles, several K steps, all bit-widths."""
     import torch
@@ -184,6 +187,25 @@ def test_gemm_prefill_matches_oracle(pmpd, b, m, out_f, in_f):
     torch.cuda.synchronize()
     y_ref, t = oracle.linear(q4, s, a, b, X)
     assert_parity(Y.cpu().numpy(), y_ref, t, f"prefill gemm m={m} {out_f}x{in_f} b={b}")
+
+
+def test_gemm_prefill_into_a_y_that_is_not_16_byte_aligned(pmpd):
+    """The prefill kernel stores 16 bytes per lane where Y allows it; a Y that starts 4 bytes off takes the scalar stores."""
+    import torch
+
+    m, out_f, in_f, b = 40, 128, 512, 4
+    _say(f"[prefill gemm, unaligned Y] m={m} out={out_f} in={in_f} b={b}")
+    q4, s, a = synth.draw_weights(14, out_f, m, out_f, in_f, random_min=True)
+    X = synth.draw_x(14, 0, out_f, m, in_f, m=m)
+    layer = _device_layer(pmpd, q4, s, a)
+    buf = torch.full((m * out_f + 1,), float("nan"), dtype=torch.float32, device="cuda")
+    Y = buf[1:].view(m, out_f)
+    assert Y.data_ptr() % 16 == 4
+    pmpd.gemm(layer, b, torch.from_numpy(X).cuda(), Y)
+    torch.cuda.synchronize()
+    y_ref, t = oracle.linear(q4, s, a, b, X)
+    assert_parity(Y.cpu().numpy(), y_ref, t, "prefill gemm, unaligned Y")
+    assert torch.isnan(buf[0]).item()  # the word before Y is untouched
 
 
 @pytest.mark.parametrize("b", [4, 2])

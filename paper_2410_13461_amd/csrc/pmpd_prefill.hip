@@ -18,7 +18,10 @@
 // on y, inside the 1e-3 bar); the decode kernels keep exact codes instead because there the
 // per-group scaling is free.
 //
-// Shape of the kernel.  A workgroup is four waves, one per SIMD, and it is alone on its compute unit.  Wave w
+// Shape of the kernel.  A workgroup is four waves, one per SIMD, and it is alone on its compute unit; the grid is
+// one round of the chip and every workgroup walks through its share of the work items (four row tiles x 256
+// tokens each) as one sequence of groups, so that loads run ahead across item boundaries and only a workgroup's
+// first item has a prologue.  Wave w
 // owns row tile tile0 + w (64 weight rows) and all 256 tokens of the block: 16 x 4 accumulator blocks of
 // 16 x 16, the 256 accumulation registers of a lane.  Per group of 128 columns it issues 256 MFMAs (4 K-steps
 // x 16 token blocks x 4 row blocks) and dequantises its 128 weights per lane once, so the VALU work per MFMA
@@ -30,7 +33,7 @@
 // of the same wave fit between two of them without delaying the second; everything else costs time.  The
 // stream is therefore MFMA, <= 2 VALU, MFMA, <= 2 VALU, ... with the whole of the remaining work cut into
 // such pieces:
-//   * the dequantisation of the operands of the NEXT K-step (32 pieces of two instructions per K-step),
+//   * the dequantisation of the operands of the NEXT K-step (28 units of one or two instructions per K-step),
 //   * the merge of the plane words of the NEXT group into 4-bit codes (7 pieces per 16-row block, one row
 //     block per K-step),
 //   * one LDS read per token block, three blocks ahead of its use, with a counted wait,
@@ -103,21 +106,53 @@ __device__ __forceinline__ lds_ptr_t to_lds(const void* p) {
   "a237", "a238", "a239", "a240", "a241", "a242", "a243", "a244", "a245", "a246", "a247", "a248", "a249", "a250", \
   "a251", "a252", "a253", "a254", "a255"
 
-// One workgroup: tokens [mtile * 256, +256) x the 4 row tiles from tile0 of one layer.
-template <int B>
-__device__ __forceinline__ void prefill_tile(const LayerDesc& L, const _Float16* __restrict__ X, int m_rows,
-                                             float* __restrict__ Y, int mtile, int tile0, char* lds) {
+// What the kernel needs to know of a work item: four consecutive 64-row tiles of one layer (one per wave).
+struct PfItem {
+  LayerDesc L;
+  const _Float16* X;  // the layer's activations, row-major [m][in_f]
+  float* Y;           // the layer's outputs, row-major [m][out_f]
+  int tile0;
+};
+// Items of a stack: entry idx of the work list (longest rows first).
+struct PfStackSource {
+  const LayerDesc* layers;
+  const WorkItem* items;
+  const _Float16* x_base;
+  float* y_base;
+  int m;
+  __device__ __forceinline__ PfItem get(int idx) const {
+    const WorkItem it = items[idx];
+    PfItem r;
+    r.L = layers[it.layer];
+    r.X = x_base + static_cast<int64_t>(m) * r.L.x_off;
+    r.Y = y_base + static_cast<int64_t>(m) * r.L.y_off;
+    r.tile0 = it.tile0;
+    return r;
+  }
+};
+// Items of one layer: entry idx is its idx-th block of four tiles.
+struct PfLayerSource {
+  LayerDesc L;
+  const _Float16* X;
+  float* Y;
+  __device__ __forceinline__ PfItem get(int idx) const { return PfItem{L, X, Y, idx * kPfWaves}; }
+};
+
+// One workgroup: token block mtile (256 tokens) of the work items first, first + stride, ... (n_mine of them), one
+// after the other, as ONE sequence of groups: the loads run ahead of the MFMAs across item boundaries (the X tile
+// by one group, the plane words by three), so only the first item of a workgroup has a prologue, and the stores of
+// an item's results are followed at once by the next item's MFMAs.  Three cursors walk the sequence of (item, group)
+// pairs, each with the buffer resources of its own item: one for the plane loads, one for the X loads, one for the
+// MFMAs; they move between groups, never inside one.  All cursor state is wave-uniform.
+template <int B, typename Source>
+__device__ __forceinline__ void prefill_run(const Source& src, int m_rows, int mtile, int first, int stride, int n_mine,
+                                            char* lds) {
+  if (n_mine <= 0) return;  // (the launchers never start such a workgroup)
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int G = L.n_groups;
-  const int in_f = L.in_f;
   const int m0 = mtile * kPfTokens;
 
-  // this wave's row tile (clamped: rows past the end are never stored)
-  const int tile = tile0 + wave;
-  const int tl = tile < L.n_tiles ? tile : L.n_tiles - 1;
-  const int64_t tbase = (static_cast<int64_t>(tl) * G) * 64;
   // All loads go through buffer resources (a base and a byte count in scalar registers) with a 32-bit byte offset
   // per lane and a scalar offset for the group, so that an address costs neither vector registers nor vector
   // instructions: plane k of this wave's tile is the 1 KiB per group at plane[k] + (tbase + 64 g) 16, lane l
@@ -125,36 +160,82 @@ __device__ __forceinline__ void prefill_tile(const LayerDesc& L, const _Float16*
   // taking bytes 16 (l % 16)...  A read past a resource's end would return zero instead of faulting.
   constexpr int kRsrcFlags = 0x00020000;  // raw buffer, 32-bit data format
   const uint32_t plane_lane = static_cast<uint32_t>(lane) * 16u, sa_lane = static_cast<uint32_t>(lane & 15) * 16u;
-  __amdgpu_buffer_rsrc_t pr[B];
-#pragma unroll
-  for (int k = 0; k < B; ++k)
-    pr[k] = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(static_cast<const char*>(L.plane[k]) + tbase * 16), 0, G * 1024, kRsrcFlags);
-  const __amdgpu_buffer_rsrc_t sr =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(static_cast<const char*>(L.sa) + tbase * 4), 0, G * 256, kRsrcFlags);
-  // X: all m_rows rows (their byte count fits 32 bits, checked by the launcher)
-  const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<_Float16*>(X), 0, static_cast<int>(static_cast<uint32_t>(m_rows) * static_cast<uint32_t>(in_f) * 2u), kRsrcFlags);
 
-  // X tile: a wave's load instruction i fills the four token rows 4 (wave + 4 i) .. + 3 of the tile, 1 KiB
-  // that the hardware places at consecutive LDS addresses in lane order: lane l is position l % 16 of row
-  // 4 (wave + 4 i) + l / 16 and therefore fetches the chunk that the swizzle puts there.  Rows 16 i apart
-  // share r % 16, so the lane's chunk is the same for its sixteen loads.  Tokens past the end repeat the last
-  // one (their outputs are never stored).
-  const int xrow = 4 * wave + (lane >> 4);
-  const int xchunk = (lane & 15) ^ pf_swz(xrow);
-  uint32_t xoff[kPfXV];
+  // ---- plane cursor: item kp, group gp of its Gp
+  int kp = 0, gp = 0, Gp = 1;
+  __amdgpu_buffer_rsrc_t pr[B], sr;
+  auto plane_item = [&](int k) {
+    const PfItem it = src.get(first + k * stride);
+    const int tile = it.tile0 + wave;  // this wave's row tile (clamped: rows past the end are never stored)
+    const int tl = tile < it.L.n_tiles ? tile : it.L.n_tiles - 1;
+    Gp = it.L.n_groups;
+    const int64_t tbase = (static_cast<int64_t>(tl) * Gp) * 64;
 #pragma unroll
-  for (int i = 0; i < kPfXV; ++i) {
-    int token = m0 + xrow + 4 * kPfWaves * i;
-    token = token < m_rows ? token : m_rows - 1;
-    xoff[i] = static_cast<uint32_t>(token) * static_cast<uint32_t>(in_f) * 2u + static_cast<uint32_t>(xchunk) * 16u;
-  }
-  // load i of X tile g (a group past the end repeats the last one: a load into the free buffer is harmless)
-  auto load_x = [&](int i, int g, char* buf) {
-    const int gn = g < G ? g : G - 1;
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, to_lds(buf + (4 * wave + 4 * kPfWaves * i) * kPfRowBytes), 16, xoff[i],
-                                             gn * (kGroup * 2), 0, 0);
+    for (int q = 0; q < B; ++q)
+      pr[q] = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(static_cast<const char*>(it.L.plane[q]) + tbase * 16), 0, Gp * 1024, kRsrcFlags);
+    sr = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(static_cast<const char*>(it.L.sa) + tbase * 4), 0, Gp * 256, kRsrcFlags);
   };
+  // to the next group; past the last group of the last item the cursor stays where it is (loads repeat, unused)
+  auto plane_next = [&]() {
+    if (gp + 1 < Gp) {
+      ++gp;
+    } else if (kp + 1 < n_mine) {
+      ++kp;
+      gp = 0;
+      plane_item(kp);
+    }
+  };
+
+  // ---- X cursor: item kx, group gx of its Gx.  X tile: a wave's load instruction i fills the four token rows
+  // 4 (wave + 4 i) .. + 3 of the tile, 1 KiB that the hardware places at consecutive LDS addresses in lane order: lane
+  // l is position l % 16 of row 4 (wave + 4 i) + l / 16 and therefore fetches the chunk that the swizzle puts there.
+  // Rows 16 i apart share r % 16, so the lane's chunk is the same for its sixteen loads.  Tokens past the end repeat
+  // the last one (their outputs are never stored).  The byte count of X fits 32 bits (checked by the launcher).
+  int kx = 0, gx = 0, Gx = 1;
+  __amdgpu_buffer_rsrc_t xr;
+  uint32_t xoff[kPfXV];
+  const int xrow = 4 * wave + (lane >> 4);
+  const uint32_t xchunk16 = static_cast<uint32_t>((lane & 15) ^ pf_swz(xrow)) * 16u;
+  auto x_item = [&](int k) {
+    const PfItem it = src.get(first + k * stride);
+    Gx = it.L.n_groups;
+    const uint32_t row_bytes = static_cast<uint32_t>(it.L.in_f) * 2u;
+    xr = __builtin_amdgcn_make_buffer_rsrc(const_cast<_Float16*>(it.X), 0, static_cast<int>(static_cast<uint32_t>(m_rows) * row_bytes), kRsrcFlags);
+#pragma unroll
+    for (int i = 0; i < kPfXV; ++i) {
+      int token = m0 + xrow + 4 * kPfWaves * i;
+      token = token < m_rows ? token : m_rows - 1;
+      xoff[i] = static_cast<uint32_t>(token) * row_bytes + xchunk16;
+    }
+  };
+  auto x_next = [&]() {
+    if (gx + 1 < Gx) {
+      ++gx;
+    } else if (kx + 1 < n_mine) {
+      ++kx;
+      gx = 0;
+      x_item(kx);
+    }
+  };
+  // load i of the X tile the cursor points to, into the buffer at LDS address buf
+  auto load_x = [&](int i, uint32_t buf) {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, reinterpret_cast<lds_ptr_t>(buf + (4 * wave + 4 * kPfWaves * i) * kPfRowBytes), 16,
+                                             xoff[i], gx * (kGroup * 2), 0, 0);
+  };
+  const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds));  // low half of a generic LDS address
+
+  // ---- MFMA cursor: item kc, group gc of its Gc, and where the item's results go
+  int kc = 0, gc = 0, Gc = 1, c_tile = 0, c_ntiles = 0, c_out = 0;
+  float* c_y = nullptr;
+  auto mfma_item = [&](int k) {
+    const PfItem it = src.get(first + k * stride);
+    Gc = it.L.n_groups;
+    c_tile = it.tile0 + wave;
+    c_ntiles = it.L.n_tiles;
+    c_out = it.L.out_f;
+    c_y = it.Y;
+  };
+
   // A operand of this lane for K-step s: token 16 mb + lane % 16, chunk 4 (lane / 16) + s
   const int a_row = (lane & 15) * kPfRowBytes;
   const int a_col = (4 * (lane >> 4)) ^ pf_swz(lane & 15);  // chunk position of K-step s: a_col ^ s
@@ -188,14 +269,9 @@ __device__ __forceinline__ void prefill_tile(const LayerDesc& L, const _Float16*
   uint32_t sa[2][4];          // (scale, min) of the lane's four rows, two fp16
   uint32_t bw[2][4][4];       // [K-step parity][16-row block][register of the operand]
 
-  auto load_plane = [&](int q, int k, int g) {
-    const int gn = g < G ? g : G - 1;
-    pcs[q][k] = __builtin_amdgcn_raw_buffer_load_b128(pr[k], plane_lane, gn * 1024, 0);
-  };
-  auto load_sa = [&](int q, int g) {
-    const int gn = g < G ? g : G - 1;
-    sacs[q] = __builtin_amdgcn_raw_buffer_load_b128(sr, sa_lane, gn * 256, 0);
-  };
+  // the words of the group the plane cursor points to, into register set q
+  auto load_plane = [&](int q, int k) { pcs[q][k] = __builtin_amdgcn_raw_buffer_load_b128(pr[k], plane_lane, gp * 1024, 0); };
+  auto load_sa = [&](int q) { sacs[q] = __builtin_amdgcn_raw_buffer_load_b128(sr, sa_lane, gp * 256, 0); };
   // Everything that rides under the MFMAs is written as asm statements, one instruction each: such statements keep
   // their order, so the instruction stream is the one written here and the compiler only assigns registers.
   // Measured on gfx950 with one wave per SIMD: two VALU instructions after an MFMA do not delay the next MFMA, a
@@ -306,7 +382,7 @@ __device__ __forceinline__ void prefill_tile(const LayerDesc& L, const _Float16*
   // every third block a load of X tile g + 1 into the other buffer xn (16 in all); in K-step 3 the last three
   // blocks load the plane words and (scale, min) words of group g + 3 into the set of parity mq, which the merge
   // has finished with by then.
-  auto step = [&](int g, int s, const char* xs, char* xn, const uint32_t (&cur)[4][4], int nq, int ns, uint32_t (&nxt)[4][4], int mq) {
+  auto step = [&](int s, const char* xs, uint32_t xn, const uint32_t (&cur)[4][4], int nq, int ns, uint32_t (&nxt)[4][4], int mq) {
     const uint32_t ap = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(xs + a_row + ((a_col ^ s) << 4)));  // LDS address
     half8_t af[4];
     u32x4 cw[4];
@@ -349,41 +425,85 @@ __device__ __forceinline__ void prefill_tile(const LayerDesc& L, const _Float16*
         default: break;
       }
       if (s < 3) {
-        if (mb % 3 == 0 && mb < 15) load_x(5 * s + mb / 3, g + 1, xn);
-        if (s == 2 && mb == 15) load_x(15, g + 1, xn);
+        if (mb % 3 == 0 && mb < 15) load_x(5 * s + mb / 3, xn);
+        if (s == 2 && mb == 15) load_x(15, xn);
       } else {
         if (mb == 13) {
-          load_plane(mq, 0, g + 3);
-          load_plane(mq, 1, g + 3);
+          load_plane(mq, 0);
+          load_plane(mq, 1);
         }
         if (mb == 14 && B > 2) {
-          load_plane(mq, 2, g + 3);
-          if constexpr (B > 3) load_plane(mq, 3, g + 3);
+          load_plane(mq, 2);
+          if constexpr (B > 3) load_plane(mq, 3);
         }
-        if (mb == 15) load_sa(mq, g + 3);
+        if (mb == 15) load_sa(mq);
       }
     }
 #undef PMPD_PF_READ
 #undef PMPD_PF_MFMA
   };
 
-  // Before the first group: X tile 0 to buffer 0; plane words of group 0 merged and the operands of its K-step 0
-  // made; plane words of groups 1 and 2 in their sets.  Nothing is outstanding afterwards.
+  // Results of the item the MFMA cursor has just finished: the weights are the first MFMA operand (rows i of D =
+  // weight rows) and X the second (columns j = tokens), so D[i][j] sits in lane j + 16 (i / 4), register i % 4: a
+  // lane holds four consecutive output features of one token, 16 bytes of Y, which go out as one 16-byte store where
+  // Y allows it.  (Plain stores: the write-back caches absorb the burst; nontemporal ones measured 4 % slower.)  Every
+  // accumulator is cleared right after it is read.  The MFMAs that wrote them are at least a barrier away.
+  auto store_item = [&]() {
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    const bool mine = c_tile < c_ntiles;
+    const bool wide = (reinterpret_cast<uintptr_t>(c_y) % 16 == 0) && (c_out % 4 == 0);
 #pragma unroll
-  for (int i = 0; i < kPfXV; ++i) load_x(i, 0, lds);
+    for (int mb = 0; mb < kPfMB; ++mb) {
+      const int row = m0 + 16 * mb + (lane & 15);
+      float* yrow = c_y + static_cast<int64_t>(row) * c_out;
+      const bool row_ok = mine && row < m_rows;
 #pragma unroll
-  for (int k = 0; k < B; ++k) load_plane(0, k, 0);
-  load_sa(0, 0);
+      for (int t = 0; t < 4; ++t) {
+        const int col = c_tile * 64 + 16 * t + 4 * (lane >> 4);
+        float4_t d;
 #pragma unroll
-  for (int k = 0; k < B; ++k) load_plane(1, k, 1);
-  load_sa(1, 1);
+        for (int r = 0; r < 4; ++r) {
+          asm volatile("v_accvgpr_read_b32 %0, a[%1]" : "=v"(d[r]) : "n"(16 * mb + 4 * t + r));
+          asm volatile("v_accvgpr_write_b32 a[%0], 0" ::"n"(16 * mb + 4 * t + r));
+        }
+        if (row_ok) {
+          if (wide) {
+            if (col < c_out) *reinterpret_cast<float4_t*>(yrow + col) = d;
+          } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+              if (col + r < c_out) yrow[col + r] = d[r];
+          }
+        }
+      }
+    }
+  };
+
+  // Before the first group: X tile of group 0 to buffer 0; plane words of group 0 merged and the operands of its
+  // K-step 0 made; plane words of groups 1 and 2 in their sets; the plane cursor three groups ahead, the X cursor
+  // one.  Nothing is outstanding afterwards.
+  mfma_item(0);
+  x_item(0);
+  plane_item(0);
+#pragma unroll
+  for (int i = 0; i < kPfXV; ++i) load_x(i, lds0);
+  x_next();
+#pragma unroll
+  for (int k = 0; k < B; ++k) load_plane(0, k);
+  load_sa(0);
+  plane_next();
+#pragma unroll
+  for (int k = 0; k < B; ++k) load_plane(1, k);
+  load_sa(1);
+  plane_next();
 #pragma unroll
   for (int t = 0; t < 4; ++t)
 #pragma unroll
     for (int k = 0; k < 7; ++k) merge_pair(0, t, k);
 #pragma unroll
-  for (int k = 0; k < B; ++k) load_plane(0, k, 2);
-  load_sa(0, 2);
+  for (int k = 0; k < B; ++k) load_plane(0, k);
+  load_sa(0);
+  plane_next();
 #pragma unroll
   for (int t = 0; t < 4; ++t)
 #pragma unroll
@@ -391,88 +511,86 @@ __device__ __forceinline__ void prefill_tile(const LayerDesc& L, const _Float16*
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0), other counters untouched
   __syncthreads();
 
-  // Group g of parity p.  On entry: codes of group g in code[p], operands of its K-step 0 in bw[0], plane words of
-  // group g + 1 in pcs[1 - p] (arrived), those of group g + 2 on their way to pcs[p] or there, X tile g in LDS
-  // buffer p.
-  auto group = [&](auto parity, int g) {
+  // One group of the sequence, of parity p (groups are counted through all items).  On entry: codes of this group in
+  // code[p], operands of its K-step 0 in bw[0], plane words of the next group in pcs[1 - p] (arrived), those of the
+  // one after on their way to pcs[p] or there, this group's X tile in LDS buffer p; the X cursor points to the next
+  // group, the plane cursor three groups ahead.  Returns false after the last group of the last item.
+  auto group = [&](auto parity) -> bool {
     constexpr int p = decltype(parity)::value;
     const char* xs = lds + p * kPfTileBytes;
-    char* xn = lds + (1 - p) * kPfTileBytes;
-    step(g, 0, xs, xn, bw[0], p, 1, bw[1], 1 - p);
-    step(g, 1, xs, xn, bw[1], p, 2, bw[0], 1 - p);
-    step(g, 2, xs, xn, bw[0], p, 3, bw[1], 1 - p);
-    step(g, 3, xs, xn, bw[1], 1 - p, 0, bw[0], 1 - p);
-    // Loads complete in order: with at most the B + 1 loads of K-step 3 outstanding, this wave's part of X tile
-    // g + 1 is in LDS and the plane words of group g + 2 are in their registers.
+    // (opaque: the sixteen destination addresses of the X loads are then computed where they are used, one scalar
+    // add each, instead of being kept in sixteen scalar registers per buffer)
+    const uint32_t xn = opaque_sgpr(lds0 + (1 - p) * kPfTileBytes);
+    step(0, xs, xn, bw[0], p, 1, bw[1], 1 - p);
+    step(1, xs, xn, bw[1], p, 2, bw[0], 1 - p);
+    step(2, xs, xn, bw[0], p, 3, bw[1], 1 - p);
+    step(3, xs, xn, bw[1], 1 - p, 0, bw[0], 1 - p);
+    // Loads complete in order: with at most the B + 1 loads of K-step 3 outstanding, this wave's part of the next X
+    // tile is in LDS and the plane words of the group after next are in their registers.
     if constexpr (B == 4) __builtin_amdgcn_s_waitcnt(0x0F75);  // vmcnt(5), other counters untouched
     if constexpr (B == 3) __builtin_amdgcn_s_waitcnt(0x0F74);
     if constexpr (B == 2) __builtin_amdgcn_s_waitcnt(0x0F73);
-    __syncthreads();  // everybody's part of X tile g + 1 is in LDS; buffer p is free
+    __syncthreads();  // everybody's part of the next X tile is in LDS; buffer p is free
+    x_next();
+    plane_next();
+    if (++gc == Gc) {
+      store_item();
+      if (++kc == n_mine) return false;
+      gc = 0;
+      mfma_item(kc);
+    }
+    return true;
   };
-  for (int g = 0; g < G; g += 2) {
-    group(std::integral_constant<int, 0>{}, g);
-    if (g + 1 < G) group(std::integral_constant<int, 1>{}, g + 1);
+  while (group(std::integral_constant<int, 0>{}) && group(std::integral_constant<int, 1>{})) {
   }
 #undef PMPD_V2
 #undef PMPD_VN
 #undef PMPD_VS
 #undef PMPD_BFI
 #undef PMPD_ROTL
-  // the last MFMAs have written their accumulators before these are read; no load is left outstanding
-  asm volatile("s_nop 15\n\ts_nop 15\n\ts_waitcnt vmcnt(0)" ::: "memory");
+}
 
-  // ---- store.  The weights are the first MFMA operand (rows i of D = weight rows) and X the second (columns
-  // j = tokens): D[i][j] sits in lane j + 16 (i / 4), register i % 4, so a lane holds four consecutive
-  // output features of one token, 16 bytes of Y.  They go out as one 16-byte store where Y allows it.  (Plain
-  // stores: the write-back caches absorb the burst at the end of a workgroup; nontemporal ones measured 4 % slower.)
-  if (tile < L.n_tiles) {
-    const bool wide = (reinterpret_cast<uintptr_t>(Y) % 16 == 0) && (L.out_f % 4 == 0);
-#pragma unroll
-    for (int mb = 0; mb < kPfMB; ++mb) {
-      const int row = m0 + 16 * mb + (lane & 15);
-      if (row >= m_rows) continue;
-      float* yrow = Y + static_cast<int64_t>(row) * L.out_f;
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const int col = tile * 64 + 16 * t + 4 * (lane >> 4);
-        float4_t d;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) asm volatile("v_accvgpr_read_b32 %0, a[%1]" : "=v"(d[r]) : "n"(16 * mb + 4 * t + r));
-        if (wide) {
-          if (col < L.out_f) *reinterpret_cast<float4_t*>(yrow + col) = d;
-        } else {
-#pragma unroll
-          for (int r = 0; r < 4; ++r)
-            if (col + r < L.out_f) yrow[col + r] = d[r];
-        }
-      }
-    }
+// Which token block and which items workgroup b of the grid takes.  The lists are sorted by row length and every
+// workgroup takes one item per round of per_block items, so all workgroups get the same work to within one item.
+// Workgroups go to the 8 XCDs round-robin (b % 8), and every workgroup of an item re-reads the item's X (64 KiB per
+// group): what keeps that traffic inside an XCD's L2 is that the workgroups of one XCD work on the same token block
+// and on neighbouring items (the same layer or the next).  So with m_tiles dividing 8 and per_xcd > 0, XCD x takes
+// token block x % m_tiles, and its per_xcd workgroups take per_xcd consecutive items of every round; otherwise
+// (per_xcd = 0) workgroup b simply takes token block b % m_tiles and items b / m_tiles + k per_block.
+struct PfShare {
+  int mtile, first;
+};
+__device__ __forceinline__ PfShare pf_share(int m_tiles, int per_xcd) {
+  const int b = static_cast<int>(blockIdx.x);
+  if (per_xcd > 0) {
+    const int x = b % 8;
+    return PfShare{x % m_tiles, (x / m_tiles) * per_xcd + b / 8};
   }
+  return PfShare{b % m_tiles, b / m_tiles};
 }
 
 template <int B>
 __global__ __launch_bounds__(kPfThreads, 1) void pmpd_prefill_layer_kernel(LayerDesc L, const _Float16* __restrict__ X, int m,
-                                                                     float* __restrict__ Y, int m_tiles) {
+                                                                     float* __restrict__ Y, int m_tiles, int n_items,
+                                                                     int per_block, int per_xcd) {
   extern __shared__ uint4 lds_raw[];
-  const int mtile = static_cast<int>(blockIdx.x) % m_tiles;
-  const int ntile = static_cast<int>(blockIdx.x) / m_tiles;
-  prefill_tile<B>(L, X, m, Y, mtile, ntile * kPfWaves, reinterpret_cast<char*>(lds_raw));
+  const PfShare sh = pf_share(m_tiles, per_xcd);
+  const int n_mine = (n_items - sh.first + per_block - 1) / per_block;
+  const PfLayerSource src{L, X, Y};
+  prefill_run<B>(src, m, sh.mtile, sh.first, per_block, n_mine, reinterpret_cast<char*>(lds_raw));
 }
 
 template <int B>
 __global__ __launch_bounds__(kPfThreads, 1) void pmpd_prefill_stack_kernel(const LayerDesc* __restrict__ layers,
                                                                      const WorkItem* __restrict__ items,
                                                                      const _Float16* __restrict__ x_base, int m,
-                                                                     float* __restrict__ y_base, int m_tiles) {
+                                                                     float* __restrict__ y_base, int m_tiles, int n_items,
+                                                                     int per_block, int per_xcd) {
   extern __shared__ uint4 lds_raw[];
-  // Workgroups go to the 8 XCDs round-robin: with the token block as the fast index, an XCD sees one token block
-  // (two of them: even XCDs the first, odd XCDs the second) and its L2 holds that block's X for all its workgroups.
-  // (Placing the token blocks of an item on one XCD instead, to share the plane words, measured slower.)
-  const int mtile = static_cast<int>(blockIdx.x) % m_tiles;
-  const WorkItem it = items[static_cast<int>(blockIdx.x) / m_tiles];
-  const LayerDesc L = layers[it.layer];
-  prefill_tile<B>(L, x_base + static_cast<int64_t>(m) * L.x_off, m, y_base + static_cast<int64_t>(m) * L.y_off, mtile,
-                  it.tile0, reinterpret_cast<char*>(lds_raw));
+  const PfShare sh = pf_share(m_tiles, per_xcd);
+  const int n_mine = (n_items - sh.first + per_block - 1) / per_block;
+  const PfStackSource src{layers, items, x_base, y_base, m};
+  prefill_run<B>(src, m, sh.mtile, sh.first, per_block, n_mine, reinterpret_cast<char*>(lds_raw));
 }
 
 // The X tile needs more than the 64 KiB of dynamic LDS a kernel gets by default.
@@ -482,19 +600,41 @@ static hipError_t allow_lds(K kernel) {
                              static_cast<int>(kPrefillLds));
 }
 
+// Grid: one workgroup is resident per compute unit, so the grid is one round of the chip (or one workgroup per item
+// where there are fewer items than that).  per_block = workgroups (= items per round) per token block; per_xcd > 0
+// selects the XCD-aware deal of pf_share.
+struct PfGrid {
+  int per_block, per_xcd;
+  unsigned grid;
+};
+static hipError_t prefill_grid(int n_items, int m_tiles, PfGrid* g) {
+  int dev = 0, cus = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+  if (e != hipSuccess) return e;
+  const int per_xcd = cus / 8;
+  if (m_tiles <= 8 && 8 % m_tiles == 0 && per_xcd > 0 && n_items >= per_xcd * (8 / m_tiles)) {
+    *g = PfGrid{per_xcd * (8 / m_tiles), per_xcd, static_cast<unsigned>(8 * per_xcd)};
+  } else {
+    const int per_block = std::max(1, std::min(n_items, cus / m_tiles));
+    *g = PfGrid{per_block, 0, static_cast<unsigned>(m_tiles) * static_cast<unsigned>(per_block)};
+  }
+  return hipSuccess;
+}
+
 // Launchers used by the C entry points (defined in pmpd_gemv.hip).
 hipError_t launch_prefill_layer(const LayerDesc& d, int b, const void* X, int m, float* Y, hipStream_t s) {
   const int m_tiles = (m + kPfTokens - 1) / kPfTokens;
-  const int n_tiles = (d.n_tiles + kPfWaves - 1) / kPfWaves;
-  const unsigned grid = static_cast<unsigned>(m_tiles) * static_cast<unsigned>(n_tiles);
-  const _Float16* x = static_cast<const _Float16*>(X);
-  hipError_t e = b == 4 ? allow_lds(&pmpd_prefill_layer_kernel<4>)
-                 : b == 3 ? allow_lds(&pmpd_prefill_layer_kernel<3>)
-                          : allow_lds(&pmpd_prefill_layer_kernel<2>);
+  const int n_items = (d.n_tiles + kPfWaves - 1) / kPfWaves;
+  PfGrid g;
+  hipError_t e = prefill_grid(n_items, m_tiles, &g);
   if (e != hipSuccess) return e;
-  if (b == 4) hipLaunchKernelGGL((pmpd_prefill_layer_kernel<4>), dim3(grid), dim3(kPfThreads), kPrefillLds, s, d, x, m, Y, m_tiles);
-  else if (b == 3) hipLaunchKernelGGL((pmpd_prefill_layer_kernel<3>), dim3(grid), dim3(kPfThreads), kPrefillLds, s, d, x, m, Y, m_tiles);
-  else hipLaunchKernelGGL((pmpd_prefill_layer_kernel<2>), dim3(grid), dim3(kPfThreads), kPrefillLds, s, d, x, m, Y, m_tiles);
+  const _Float16* x = static_cast<const _Float16*>(X);
+  e = b == 4 ? allow_lds(&pmpd_prefill_layer_kernel<4>) : b == 3 ? allow_lds(&pmpd_prefill_layer_kernel<3>) : allow_lds(&pmpd_prefill_layer_kernel<2>);
+  if (e != hipSuccess) return e;
+  if (b == 4) hipLaunchKernelGGL((pmpd_prefill_layer_kernel<4>), dim3(g.grid), dim3(kPfThreads), kPrefillLds, s, d, x, m, Y, m_tiles, n_items, g.per_block, g.per_xcd);
+  else if (b == 3) hipLaunchKernelGGL((pmpd_prefill_layer_kernel<3>), dim3(g.grid), dim3(kPfThreads), kPrefillLds, s, d, x, m, Y, m_tiles, n_items, g.per_block, g.per_xcd);
+  else hipLaunchKernelGGL((pmpd_prefill_layer_kernel<2>), dim3(g.grid), dim3(kPfThreads), kPrefillLds, s, d, x, m, Y, m_tiles, n_items, g.per_block, g.per_xcd);
   return hipGetLastError();
 }
 
@@ -502,17 +642,17 @@ hipError_t launch_prefill_stack(const pmpd_stack* st, int b, const void* X, int 
   const int m_tiles = (m + kPfTokens - 1) / kPfTokens;
   constexpr int kList = 0;  // work list of 4-tile items: one 64-row tile per wave
   static_assert(kStackTilesPerWg[kList] == kPfWaves, "one tile per wave");
-  const size_t n_items = st->items[kList].size();
-  const unsigned grid = static_cast<unsigned>(m_tiles) * static_cast<unsigned>(n_items);
+  const int n_items = static_cast<int>(st->items[kList].size());
+  PfGrid g;
+  hipError_t e = prefill_grid(n_items, m_tiles, &g);
+  if (e != hipSuccess) return e;
   const _Float16* x = static_cast<const _Float16*>(X);
   const WorkItem* items = st->d_items[kList];
-  hipError_t e = b == 4 ? allow_lds(&pmpd_prefill_stack_kernel<4>)
-                 : b == 3 ? allow_lds(&pmpd_prefill_stack_kernel<3>)
-                          : allow_lds(&pmpd_prefill_stack_kernel<2>);
+  e = b == 4 ? allow_lds(&pmpd_prefill_stack_kernel<4>) : b == 3 ? allow_lds(&pmpd_prefill_stack_kernel<3>) : allow_lds(&pmpd_prefill_stack_kernel<2>);
   if (e != hipSuccess) return e;
-  if (b == 4) hipLaunchKernelGGL((pmpd_prefill_stack_kernel<4>), dim3(grid), dim3(kPfThreads), kPrefillLds, s, st->d_layers, items, x, m, Y, m_tiles);
-  else if (b == 3) hipLaunchKernelGGL((pmpd_prefill_stack_kernel<3>), dim3(grid), dim3(kPfThreads), kPrefillLds, s, st->d_layers, items, x, m, Y, m_tiles);
-  else hipLaunchKernelGGL((pmpd_prefill_stack_kernel<2>), dim3(grid), dim3(kPfThreads), kPrefillLds, s, st->d_layers, items, x, m, Y, m_tiles);
+  if (b == 4) hipLaunchKernelGGL((pmpd_prefill_stack_kernel<4>), dim3(g.grid), dim3(kPfThreads), kPrefillLds, s, st->d_layers, items, x, m, Y, m_tiles, n_items, g.per_block, g.per_xcd);
+  else if (b == 3) hipLaunchKernelGGL((pmpd_prefill_stack_kernel<3>), dim3(g.grid), dim3(kPfThreads), kPrefillLds, s, st->d_layers, items, x, m, Y, m_tiles, n_items, g.per_block, g.per_xcd);
+  else hipLaunchKernelGGL((pmpd_prefill_stack_kernel<2>), dim3(g.grid), dim3(kPfThreads), kPrefillLds, s, st->d_layers, items, x, m, Y, m_tiles, n_items, g.per_block, g.per_xcd);
   return hipGetLastError();
 }
 

@@ -230,6 +230,38 @@ def test_prefill_step_over_stack_matches_oracle(pmpd, b):
     stack.close()
 
 
+@pytest.mark.parametrize("m", [40, 300])
+def test_prefill_step_walks_many_short_items_per_workgroup(pmpd, m):
+    """The prefill grid is one round of the chip and a workgroup walks through its items as one sequence of groups,
+    with its loads up to three groups ahead.  Here every workgroup gets several items of one, two or three groups
+    (more items than compute units, rows of 128, 256 and 384 columns, a ragged last tile), so the loads run ahead
+    through up to three items at once; m = 300 also splits the tokens into two blocks."""
+    import torch
+
+    b = 4
+    _say(f"[prefill_step, many short items] m={m}")
+    dims = [(1000 + 8 * k, 128 * (1 + k % 3)) for k in range(45)]  # 16 to 22 row tiles: 4 to 6 items each
+    dims = dims + [(2048, 128 * (1 + (k + 1) % 3)) for k in range(36)]  # 8 items each: 516 items in all
+    layers, raw, Xs = [], [], []
+    for li, (o, i) in enumerate(dims):
+        q4, s_, a = synth.draw_weights(21, li, 0, o, i, random_min=(li % 2 == 1))
+        raw.append((q4, s_, a))
+        layers.append(_device_layer(pmpd, q4, s_, a))
+        Xs.append(synth.draw_x(21, 0, li, 0, i, m=m))
+    stack = pmpd.Stack(layers)
+    X = torch.from_numpy(np.concatenate([x.reshape(-1) for x in Xs])).cuda()
+    Y = torch.full((m * stack.y_elems,), float("nan"), dtype=torch.float32, device="cuda")
+    pmpd.prefill_step(stack, b, X, m, Y)
+    torch.cuda.synchronize()
+    Y = Y.cpu().numpy()
+    for li, (q4, s_, a) in enumerate(raw):
+        o = m * stack.y_offsets[li]
+        y_ref, t = oracle.linear(q4, s_, a, b, Xs[li])
+        got = Y[o:o + m * q4.shape[0]].reshape(m, q4.shape[0])
+        assert_parity(got, y_ref, t, f"prefill_step, short items, layer {li} ({q4.shape[0]} x {q4.shape[1]}) m={m}")
+    stack.close()
+
+
 @pytest.mark.parametrize("b", [4, 3, 2])
 @pytest.mark.parametrize("m", [1, 2, 3, 4, 5, 8, 9, 12, 13, 16])
 def test_batch_step_over_stack_matches_oracle(pmpd, b, m):

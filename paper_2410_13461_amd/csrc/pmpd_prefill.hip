@@ -50,6 +50,7 @@
 
 #include "pmpd_common.hpp"
 #include "pmpd_device.hpp"
+#include "pmpd_prefill_deal.hpp"
 
 namespace pmpd {
 
@@ -550,34 +551,15 @@ __device__ __forceinline__ void prefill_run(const Source& src, int m_rows, int m
 #undef PMPD_ROTL
 }
 
-// Which token block and which items workgroup b of the grid takes.  The lists are sorted by row length and every
-// workgroup takes one item per round of per_block items, so all workgroups get the same work to within one item.
-// Workgroups go to the 8 XCDs round-robin (b % 8), and every workgroup of an item re-reads the item's X (64 KiB per
-// group): what keeps that traffic inside an XCD's L2 is that the workgroups of one XCD work on the same token block
-// and on neighbouring items (the same layer or the next).  So with m_tiles dividing 8 and per_xcd > 0, XCD x takes
-// token block x % m_tiles, and its per_xcd workgroups take per_xcd consecutive items of every round; otherwise
-// (per_xcd = 0) workgroup b simply takes token block b % m_tiles and items b / m_tiles + k per_block.
-struct PfShare {
-  int mtile, first;
-};
-__device__ __forceinline__ PfShare pf_share(int m_tiles, int per_xcd) {
-  const int b = static_cast<int>(blockIdx.x);
-  if (per_xcd > 0) {
-    const int x = b % 8;
-    return PfShare{x % m_tiles, (x / m_tiles) * per_xcd + b / 8};
-  }
-  return PfShare{b % m_tiles, b / m_tiles};
-}
-
+// Which token block and which items a workgroup takes: pf_share (pmpd_prefill_deal.hpp).
 template <int B>
 __global__ __launch_bounds__(kPfThreads, 1) void pmpd_prefill_layer_kernel(LayerDesc L, const _Float16* __restrict__ X, int m,
                                                                      float* __restrict__ Y, int m_tiles, int n_items,
                                                                      int per_block, int per_xcd) {
   extern __shared__ uint4 lds_raw[];
-  const PfShare sh = pf_share(m_tiles, per_xcd);
-  const int n_mine = (n_items - sh.first + per_block - 1) / per_block;
+  const PfShare sh = pf_share(static_cast<int>(blockIdx.x), n_items, m_tiles, per_block, per_xcd);
   const PfLayerSource src{L, X, Y};
-  prefill_run<B>(src, m, sh.mtile, sh.first, per_block, n_mine, reinterpret_cast<char*>(lds_raw));
+  prefill_run<B>(src, m, sh.mtile, sh.first, per_block, sh.n_mine, reinterpret_cast<char*>(lds_raw));
 }
 
 template <int B>
@@ -587,10 +569,9 @@ __global__ __launch_bounds__(kPfThreads, 1) void pmpd_prefill_stack_kernel(const
                                                                      float* __restrict__ y_base, int m_tiles, int n_items,
                                                                      int per_block, int per_xcd) {
   extern __shared__ uint4 lds_raw[];
-  const PfShare sh = pf_share(m_tiles, per_xcd);
-  const int n_mine = (n_items - sh.first + per_block - 1) / per_block;
+  const PfShare sh = pf_share(static_cast<int>(blockIdx.x), n_items, m_tiles, per_block, per_xcd);
   const PfStackSource src{layers, items, x_base, y_base, m};
-  prefill_run<B>(src, m, sh.mtile, sh.first, per_block, n_mine, reinterpret_cast<char*>(lds_raw));
+  prefill_run<B>(src, m, sh.mtile, sh.first, per_block, sh.n_mine, reinterpret_cast<char*>(lds_raw));
 }
 
 // The X tile needs more than the 64 KiB of dynamic LDS a kernel gets by default.
@@ -600,25 +581,13 @@ static hipError_t allow_lds(K kernel) {
                              static_cast<int>(kPrefillLds));
 }
 
-// Grid: one workgroup is resident per compute unit, so the grid is one round of the chip (or one workgroup per item
-// where there are fewer items than that).  per_block = workgroups (= items per round) per token block; per_xcd > 0
-// selects the XCD-aware deal of pf_share.
-struct PfGrid {
-  int per_block, per_xcd;
-  unsigned grid;
-};
+// Grid for n_items items and m_tiles token blocks on the current device (pf_grid, pmpd_prefill_deal.hpp).
 static hipError_t prefill_grid(int n_items, int m_tiles, PfGrid* g) {
   int dev = 0, cus = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
   if (e != hipSuccess) return e;
-  const int per_xcd = cus / 8;
-  if (m_tiles <= 8 && 8 % m_tiles == 0 && per_xcd > 0 && n_items >= per_xcd * (8 / m_tiles)) {
-    *g = PfGrid{per_xcd * (8 / m_tiles), per_xcd, static_cast<unsigned>(8 * per_xcd)};
-  } else {
-    const int per_block = std::max(1, std::min(n_items, cus / m_tiles));
-    *g = PfGrid{per_block, 0, static_cast<unsigned>(m_tiles) * static_cast<unsigned>(per_block)};
-  }
+  *g = pf_grid(n_items, m_tiles, cus);
   return hipSuccess;
 }
 

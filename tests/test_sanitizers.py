@@ -46,3 +46,10 @@ def test_sum_words_of_the_ordered_step(tmp_path):
     parts, the clamp, NaN, 31 parts at either limit, order independence."""
     src = [os.path.join(ROOT, "tests", "sanitize", "sumword_driver.cpp")]
     _build_and_run(tmp_path, "g++", src, ["-std=c++17", "-I" + os.path.join(ROOT, "paper_2410_13461_amd", "csrc")], "sumword_driver")
+
+
+def test_prefill_deal_covers_every_item_once(tmp_path):
+    """pf_grid / pf_share as the prefill launcher and kernel use them, compiled for the host: every (item, token block)
+    taken exactly once, shares balanced to one item, one token block per XCD in the XCD-aware deal."""
+    src = [os.path.join(ROOT, "tests", "sanitize", "deal_driver.cpp")]
+    _build_and_run(tmp_path, "g++", src, ["-std=c++17", "-I" + os.path.join(ROOT, "paper_2410_13461_amd", "csrc")], "deal_driver")

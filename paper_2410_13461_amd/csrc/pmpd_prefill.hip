@@ -45,7 +45,6 @@
 // is copied between groups.
 #include <hip/hip_runtime.h>
 
-#include <algorithm>
 #include <type_traits>
 
 #include "pmpd_common.hpp"
@@ -64,7 +63,6 @@ constexpr size_t kPrefillLds = 2 * static_cast<size_t>(kPfTileBytes);
 constexpr int kPfXV = kPfTokens * 16 / kPfThreads;  // 16-byte pieces of the X tile per thread
 static_assert(kPfMB == 16 && kPfXV == 16, "the schedule below is written out for 16 token blocks and 16 X loads per wave");
 
-__device__ __forceinline__ half2_t h2(uint32_t v) { return __builtin_bit_cast(half2_t, v); }
 __device__ __forceinline__ uint32_t u32(half2_t v) { return __builtin_bit_cast(uint32_t, v); }
 
 // X tile in LDS: token row r holds its 16 chunks of 16 bytes (8 columns) at chunk position c ^ swz(r).

@@ -209,8 +209,10 @@ def wl_batches(pmpd, synth, workload, which, seed, K, batches=(1, 2, 3, 4, 8, 16
     for m in batches:
         X = _device_randn(m * stacks[0].x_elems, seed + 2)
         Y = torch.zeros(m * stacks[0].y_elems, dtype=torch.float32, device="cuda")
-        unit = "fp8 x fp4 scaled MFMA" if m <= 2 else "int8 MFMA" if m <= 16 else "fp16 MFMA"
         for b in (4, 3, 2):
+            # which matrix unit the library's batch step uses for this (m, b)
+            unit = ("fp8 x fp4 scaled MFMA" if m <= 2 else "fp16 MFMA, codes as subnormals" if 9 <= m <= 16 or (5 <= m <= 16 and b == 4)
+                    else "int8 MFMA" if m <= 16 else "fp16 MFMA")
             def step():
                 for stc in stacks:
                     pmpd.batch_step(stc, b, X, m, Y)

@@ -156,9 +156,10 @@ int32_t pmpd_decode_step(const pmpd_stack_t* stack, int32_t b, const void* x_bas
  * X_l = x_base + m*x_offset[l] (fp16 row-major [m][in_l]), Y_l = y_base + m*y_offset[l] (fp32
  * row-major [m][out_l]).  m == 1 is pmpd_decode_step; 2 <= m <= PMPD_MAX_STACK_BATCH reads and unpacks
  * the weights once for all m vectors (skinny batches; the paper itself stays at batch 1, Section 5.2):
- * from 3 vectors on the activations enter the int8 matrix cores as three base-256 digits of a 23-bit
- * fixed-point number per group of 128 (values within 2^-11 of the group's largest are exact, smaller ones
- * are rounded at 2^-23 of it), the codes exactly, with int32 sums;
+ * 3 to 8 vectors (3, 4 at b = 4) enter the int8 matrix cores as three base-256 digits of a 23-bit fixed-point
+ * number per group of 128 (values within 2^-11 of the group's largest are exact, smaller ones are rounded at
+ * 2^-23 of it), the codes exactly, with int32 sums; 9 to 16 vectors (from 5 at b = 4) go to the fp16 matrix
+ * cores as they are, against the 4-bit codes as fp16 subnormals (exact products, fp32 sums);
  * larger m is the compute-bound prefill shape on the matrix cores (Algorithm 1 line 10, Section 4.1).
  * pmpd_prefill_step is the same call under the paper's name for that phase. */
 int32_t pmpd_batch_step(const pmpd_stack_t* stack, int32_t b, const void* x_base, int32_t m, float* y_base,

@@ -11,7 +11,7 @@ CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libpmpd.so")
 SOURCES = [os.path.join(CSRC, "pmpd_host.cpp"), os.path.join(CSRC, "pmpd_gemv.hip"), os.path.join(CSRC, "pmpd_prefill.hip"),
            os.path.join(CSRC, "pmpd_fp16.hip"), os.path.join(CSRC, "pmpd_learned.hip"),
-           os.path.join(CSRC, "pmpd_skinny.hip")]
+           os.path.join(CSRC, "pmpd_skinny.hip"), os.path.join(CSRC, "pmpd_block16.hip")]
 HEADERS = [os.path.join(CSRC, "pmpd_common.hpp"), os.path.join(CSRC, "pmpd_device.hpp"), os.path.join(CSRC, "pmpd_sumword.hpp"), os.path.join(CSRC, "pmpd_prefill_deal.hpp"), os.path.join(ROOT, "include", "pmpd.h")]
 
 # packed-fp32 VALU forms are switched off for all device code of this library.

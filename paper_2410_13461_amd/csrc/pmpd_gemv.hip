@@ -802,6 +802,12 @@ hipError_t launch_prefill_stack(const pmpd_stack* st, int b, const void* X, int 
 // defined in pmpd_skinny.hip
 hipError_t launch_skinny_stack(const pmpd_stack* st, int b, const void* X, int m, float* Y, hipStream_t s);
 constexpr int kSkinnyMinBatch = 3, kSkinnyMaxBatch = PMPD_MAX_STACK_BATCH;  // batches the int8 kernel takes over a stack
+// defined in pmpd_block16.hip
+hipError_t launch_block16_stack(const pmpd_stack* st, int b, const void* X, int m, float* Y, hipStream_t s);
+// Which of the two takes a batch over a stack (measured on the 7B-shaped and the mobile-scale stack): the fp16 kernel
+// costs the same whatever the batch, the int8 kernel grows with every four vectors; they meet at 5 to 8 vectors,
+// where the fp16 kernel wins at b = 4 (the int8 kernel waits for memory there) and loses at b = 3 and 2.
+static bool block16_takes(int m, int b) { return m >= 9 || (m >= 5 && b == 4); }
 
 static int32_t linear_entry(const char* who, const pmpd_layer_t* layer, int32_t b, const void* x, int32_t m, int32_t max_m,
                             float* y, void* stream) {
@@ -1308,6 +1314,8 @@ int32_t pmpd_batch_step(const pmpd_stack_t* stack, int32_t b, const void* x_base
   hipError_t e;
   if (m == 1) {
     return pmpd_decode_step(stack, b, x_base, y_base, stream);
+  } else if (m <= kSkinnyMaxBatch && block16_takes(m, b)) {
+    e = launch_block16_stack(stack, b, x_base, m, y_base, s);
   } else if (m >= kSkinnyMinBatch && m <= kSkinnyMaxBatch) {
     e = launch_skinny_stack(stack, b, x_base, m, y_base, s);
   } else if (m <= PMPD_MAX_BATCH) {

@@ -284,11 +284,12 @@ def test_batch_step_over_stack_matches_oracle(pmpd, b, m):
 
 
 @pytest.mark.parametrize("b", [4, 3, 2])
-@pytest.mark.parametrize("m", [3, 7, 16])
+@pytest.mark.parametrize("m", [3, 7, 11, 16])
 def test_batch_step_long_rows_and_adversarial_vectors(pmpd, b, m):
-    """Rows long enough for several K-chunks of the batch kernel's activation image (86 and 33 groups, ragged
+    """Rows long enough for several K-chunks of the batch kernels' activation images (86 and 33 groups, ragged
     row counts), and one vector of each awkward kind among ordinary ones: a huge entry among small ones, tiny
-    values, subnormals, zeros, ones, a single sign, a one-hot vector."""
+    values, subnormals, zeros, ones, a single sign, a one-hot vector.  Both batch kernels are met: the int8 one
+    at 3 vectors (and at 7 for b = 3, 2), the fp16 one at 11 and 16 (and at 7 for b = 4)."""
     import torch
 
     _say(f"[batch_step long/adversarial] b={b} m={m}")

@@ -139,11 +139,10 @@ __device__ __forceinline__ void b16_tiles(const LayerDesc& L, int tile0, const _
 
   u32x4 pa[B], pb[B], sa_a = {0, 0, 0, 0}, sa_b = {0, 0, 0, 0};
   auto load = [&](u32x4 (&dst)[B], u32x4& dsa, int g) {
-    if (g < G) {
+    const int gl = g < G ? g : G - 1;  // past the end: the last group again (no branch: the wave keeps counting its loads)
 #pragma unroll
-      for (int k = 0; k < B; ++k) dst[k] = __builtin_nontemporal_load(&pp[k][g * 64]);
-      dsa = sp[g * 16];
-    }
+    for (int k = 0; k < B; ++k) dst[k] = __builtin_nontemporal_load(&pp[k][gl * 64]);
+    dsa = sp[gl * 16];
   };
   auto consume = [&](const u32x4 (&pl)[B], const u32x4& csa, int gr) {
     half8_t cx[4];

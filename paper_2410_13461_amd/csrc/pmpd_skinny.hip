@@ -1,4 +1,5 @@
-// Skinny batches (3..16 activation vectors) over a list of layers on the int8 matrix cores (gfx950).
+// Skinny batches (3..8 activation vectors) over a list of layers on the int8 matrix cores (gfx950).
+// (From 9 vectors, and from 5 at b = 4, the fp16 kernel of pmpd_block16.hip is faster: its cost does not grow with the batch.)
 //
 // The weights are still read once per step (memory-bound, the paper's decode regime, Section 1 and
 // Section 5.2, widened to a few sequences); what changes against the batch-1 kernel is the
@@ -47,7 +48,7 @@ constexpr int kSkKbStride = 272;                   // bytes between the four 16-
 constexpr int kSkHalfStride = 4 * kSkKbStride;     // 1088: from MFMA h = 0 to h = 1
 constexpr int kSkGroupBytes = 2 * kSkHalfStride;   // 2176 per operand set and group
 __host__ __device__ constexpr int sk_budget(int nw) { return nw == 8 ? 72 * 1024 : 36 * 1024; }  // two / four workgroups per CU
-constexpr int kSkMaxVectors = 16;
+constexpr int kSkMaxVectors = 8;
 
 __host__ __device__ inline int sk_sets(int m) { return (m + 3) / 4; }
 __host__ __device__ inline int sk_group_bytes(int m) { return sk_sets(m) * kSkGroupBytes + m * 8; }
@@ -291,11 +292,8 @@ __device__ __forceinline__ void skinny_tiles(const LayerDesc& L, int tile0, cons
   }
 }
 
-template <int SETS>
-constexpr int sk_waves_per_simd() { return SETS <= 2 ? 4 : 2; }
-
 template <int B, int SETS, int NW>
-__global__ __launch_bounds__(NW * 64, sk_waves_per_simd<SETS>()) void pmpd_skinny_stack_kernel(
+__global__ __launch_bounds__(NW * 64, 4) void pmpd_skinny_stack_kernel(
     const LayerDesc* __restrict__ layers, const WorkItem* __restrict__ items, const _Float16* __restrict__ x_base, int m,
     float* __restrict__ y_base) {
   extern __shared__ uint4 lds[];
@@ -324,15 +322,10 @@ static hipError_t launch_skinny(const pmpd_stack* st, const _Float16* x, int m, 
 // Up to four vectors: 4-wave workgroups (four per CU); above: 8 waves, so that the image is built half as often.
 template <int B>
 static hipError_t launch_skinny_b(const pmpd_stack* st, const _Float16* x, int m, float* y, hipStream_t s) {
-  switch (sk_sets(m)) {
-    case 1: return launch_skinny<B, 1, 4>(st, x, m, y, s);
-    case 2: return launch_skinny<B, 2, 8>(st, x, m, y, s);
-    case 3: return launch_skinny<B, 3, 8>(st, x, m, y, s);
-    default: return launch_skinny<B, 4, 8>(st, x, m, y, s);
-  }
+  return sk_sets(m) == 1 ? launch_skinny<B, 1, 4>(st, x, m, y, s) : launch_skinny<B, 2, 8>(st, x, m, y, s);
 }
 
-// Called by the C entry points (pmpd_gemv.hip) for 3 <= m <= 16 vectors over a stack.
+// Called by the C entry points (pmpd_gemv.hip) for 3 <= m <= 8 vectors over a stack.
 hipError_t launch_skinny_stack(const pmpd_stack* st, int b, const void* X, int m, float* Y, hipStream_t s) {
   if (m < 1 || m > kSkMaxVectors) return hipErrorInvalidValue;
   const _Float16* x = static_cast<const _Float16*>(X);

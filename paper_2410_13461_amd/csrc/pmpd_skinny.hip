@@ -52,11 +52,12 @@ constexpr int kSkMaxVectors = 8;
 
 __host__ __device__ inline int sk_sets(int m) { return (m + 3) / 4; }
 __host__ __device__ inline int sk_group_bytes(int m) { return sk_sets(m) * kSkGroupBytes + m * 8; }
-// Groups per K-chunk: as few chunks as the LDS budget allows, of equal length.
+// Groups per K-chunk: as few chunks as the LDS budget allows, of about equal and even length (a chunk that starts
+// at an even group keeps the turns of the two weight register sets, whose loads run on across chunk boundaries).
 __host__ __device__ inline int sk_chunk(int n_groups, int m, int nw) {
-  const int fit = sk_budget(nw) / sk_group_bytes(m);
+  const int fit = (sk_budget(nw) / sk_group_bytes(m)) & ~1;
   const int n_chunks = (n_groups + fit - 1) / fit;
-  return (n_groups + n_chunks - 1) / n_chunks;
+  return ((n_groups + n_chunks - 1) / n_chunks + 1) & ~1;
 }
 
 // Staging units (one vector x four groups) a wave handles per K-chunk, at most, for SETS operand sets.
@@ -206,17 +207,20 @@ __device__ __forceinline__ void skinny_tiles(const LayerDesc& L, int tile0, cons
 #pragma unroll
     for (int t = 0; t < 4; ++t) yacc[s][t] = 0.f;
 
+  // The weight loads run one group ahead through the whole K: the first group of a chunk is requested by the last
+  // iteration of the chunk before and is in flight while the image is built.  Past the end the last group is read
+  // again (no branch around the loads: the wave keeps counting them).
+  u32x4 pa[B], pb[B], sa_a = {0, 0, 0, 0}, sa_b = {0, 0, 0, 0};
+  auto load = [&](u32x4 (&dst)[B], u32x4& dsa, int g) {
+    const int gl = g < G ? g : G - 1;
+#pragma unroll
+    for (int k = 0; k < B; ++k) dst[k] = __builtin_nontemporal_load(&pp[k][gl * 64]);
+    dsa = sp[gl * 16];
+  };
+  if (active) load(pa, sa_a, 0);
   for (int c0 = 0; c0 < G; c0 += im.cg) {
     const int cn = (G - c0 < im.cg) ? (G - c0) : im.cg;
     const int g1 = c0 + cn;
-    u32x4 pa[B], pb[B], sa_a = {0, 0, 0, 0}, sa_b = {0, 0, 0, 0};
-    auto load = [&](u32x4 (&dst)[B], u32x4& dsa, int g) {
-      const int gl = g < g1 ? g : g1 - 1;
-#pragma unroll
-      for (int k = 0; k < B; ++k) dst[k] = __builtin_nontemporal_load(&pp[k][gl * 64]);
-      dsa = sp[gl * 16];
-    };
-    if (active) load(pa, sa_a, c0);  // in flight while the image is built
     // (vector, block of four groups) units dealt round-robin to the waves: unit u = vector u % m, block u / m.
     // All of a wave's activation loads are issued before the barrier, so that their latency is paid once.
     const int n_units = m * ((cn + 3) >> 2);
@@ -306,8 +310,9 @@ template <int B, int SETS, int NW>
 static hipError_t launch_skinny(const pmpd_stack* st, const _Float16* x, int m, float* y, hipStream_t s) {
   constexpr int list = NW == 8 ? kEightTileList : 0;
   static_assert(kStackTilesPerWg[list] == NW, "one tile per wave");
-  // a layer's chunk is at most what the budget holds and at most its own number of groups
-  const size_t lds = static_cast<size_t>(std::min(sk_budget(NW) / sk_group_bytes(m), st->max_in / kGroup)) * sk_group_bytes(m);
+  // a layer's chunk is at most what the budget holds and at most its own number of groups, both made even
+  const int fit = (sk_budget(NW) / sk_group_bytes(m)) & ~1, longest = (st->max_in / kGroup + 1) & ~1;
+  const size_t lds = static_cast<size_t>(std::min(fit, longest)) * sk_group_bytes(m);
   auto kernel = pmpd_skinny_stack_kernel<B, SETS, NW>;
   if (lds > 65536) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,

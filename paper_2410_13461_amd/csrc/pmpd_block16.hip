@@ -8,8 +8,8 @@
 //     sum_i W_b x = s_g sum_i q~_i x_i + (a_g + s_g 2^(3-b)) sum_i x_i
 // with q~ the 4-bit aligned code.  The integer q~ (0..15) sits in the low four bits of an otherwise zero fp16
 // word, which is the subnormal number q~ 2^-24: v_mfma_f32_16x16x32_f16 multiplies subnormal inputs exactly, so
-// the code words need no conversion at all, only an AND per pair of columns (and a shift for three of every four
-// pairs).  The products q~ x 2^-24 are exact in fp32, the activations are the caller's fp16 values, unscaled and
+// the code words need no conversion at all, only an AND per pair of columns (after a shift for two of every four
+// pairs; the last pair of a word falls out of one packed 16-bit shift).  The products q~ x 2^-24 are exact in fp32, the activations are the caller's fp16 values, unscaled and
 // unrounded: the only rounding is that of the fp32 accumulation.  The second sum comes from the same
 // instruction, with a second operand of ones.  Scale and minimum meet the sums once per group and output:
 // two fused multiply-adds.
@@ -18,15 +18,15 @@
 // 16 t + j.  Merged into four code words (eight codes each, columns 8 v .. 8 v + 7 of the lane's 32), code word v
 // is the lane's K slice of matrix instruction v of the group: lane 16 kb + j gives row j for K = 8 kb .. 8 kb + 7,
 // meaning columns 32 kb + 8 v + e.  The activations are the first operand: lane 16 kb + i reads token i's same
-// eight columns, 16 bytes straight from X (the 16 x in_features activations of a layer stay in the caches: every
-// wave of every tile reads them), so there is no staging phase, no LDS and no barrier.  D[i][j] then sits in lane
-// j + 16 (i / 4), register i % 4: a lane holds row j of the block for four tokens, and the row's scale and minimum
-// are in the lane's own scale word.
+// eight columns, 16 bytes, from a copy of X in LDS that the four waves of a workgroup share (K is walked in chunks
+// of eight groups; read straight from the caches, every load instruction would touch 64 cache lines for 16 bytes
+// each).  D[i][j] then sits in lane j + 16 (i / 4), register i % 4: a lane holds row j of the block for four
+// tokens, and the row's scale and minimum are in the lane's own scale word.
 //
-// Against the int8 kernel (pmpd_skinny.hip): no digits, no image, half the matrix instructions at 16 vectors, and
-// two instead of seven instructions per (16 rows, four vectors) after them; the code words cost 28 instead of 12
-// instructions per 16 rows to spread, whatever the batch: about 225 vector instructions per (tile, group) and wave
-// against 207 at 8 vectors and 294 at 16.
+// Against the int8 kernel (pmpd_skinny.hip): no digits, no image to compute, half the matrix instructions at 16
+// vectors, and two instead of seven instructions per (16 rows, four vectors) after them; the code words cost 24
+// instead of 12 instructions per 16 rows to spread, whatever the batch: 215 / 223 / 198 vector instructions per
+// (tile, group) and wave at b = 4 / 3 / 2 against 207 / 210 / 171 at 8 vectors and 294 / 297 / 259 at 16.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>

@@ -9,10 +9,10 @@
 // with q~ the 4-bit aligned code.  The integer q~ (0..15) sits in the low four bits of an otherwise zero fp16
 // word, which is the subnormal number q~ 2^-24: v_mfma_f32_16x16x32_f16 multiplies subnormal inputs exactly, so
 // the code words need no conversion at all, only an AND per pair of columns (after a shift for two of every four
-// pairs; the last pair of a word falls out of one packed 16-bit shift).  The products q~ x 2^-24 are exact in fp32, the activations are the caller's fp16 values, unscaled and
-// unrounded: the only rounding is that of the fp32 accumulation.  The second sum comes from the same
-// instruction, with a second operand of ones.  Scale and minimum meet the sums once per group and output:
-// two fused multiply-adds.
+// pairs; the last pair of a word falls out of one packed 16-bit shift).  The products q~ x 2^-24 are exact in
+// fp32, the activations are the caller's fp16 values, unscaled and unrounded: the only rounding is that of the
+// fp32 accumulation.  The second sum comes from the same instruction, with a second operand of ones.  Scale and
+// minimum meet the sums once per group and output: two fused multiply-adds.
 //
 // Operands.  In the storage format lane 16 kb + j of a wave holds, in word t of a plane, 32 columns of weight row
 // 16 t + j.  Merged into four code words (eight codes each, columns 8 v .. 8 v + 7 of the lane's 32), code word v

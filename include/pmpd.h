@@ -115,7 +115,9 @@ int32_t pmpd_gemv(const pmpd_layer_t* layer, int32_t b, const void* x, float* y,
 /* Y[j][r] = sum_i W_b[r][i] X[j][i] for 1 <= m <= PMPD_MAX_ROWS.
  * m <= PMPD_MAX_BATCH: memory-bound path (the one pmpd_gemv takes), the weights are read once and
  *   codes and activations enter the matrix cores exactly (fp32 accumulation).
- * m >  PMPD_MAX_BATCH: the compute-bound prefill shape (Section 4.1: prefill runs at its own,
+ * PMPD_MAX_BATCH < m <= PMPD_MAX_STACK_BATCH: still read once and exact: the 4-bit codes meet the fp16
+ *   activations on the fp16 matrix cores as fp16 subnormals (fp32 accumulation).
+ * m >  PMPD_MAX_STACK_BATCH: the compute-bound prefill shape (Section 4.1: prefill runs at its own,
  *   higher precision of the same store): the weights are dequantised to fp16 (one rounding) and
  *   the contraction runs on the matrix cores with fp32 accumulation.
  * X: device, fp16 row-major [m][in], 16-byte aligned.  Y: device, fp32 row-major [m][out]. */

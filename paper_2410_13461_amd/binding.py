@@ -301,7 +301,7 @@ def gemv(layer: PackedLayer, b: int, x, y=None, stream=None):
 
 
 def gemm(layer: PackedLayer, b: int, X, Y=None, stream=None):
-    """Y = X W_b^T.  X: torch fp16 [m, in]; returns torch fp32 [m, out] (m <= 8 skinny path, above: MFMA prefill path)."""
+    """Y = X W_b^T.  X: torch fp16 [m, in]; returns torch fp32 [m, out] (m <= 8: the memory-bound kernel; 9..16: fp16 matrix cores, codes as subnormals; above: the prefill kernel)."""
     import torch
 
     if X.dim() != 2 or X.shape[1] != layer.in_features:

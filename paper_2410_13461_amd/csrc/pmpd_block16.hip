@@ -224,6 +224,25 @@ __global__ __launch_bounds__(kB16Waves * 64, 3) void pmpd_block16_stack_kernel(c
                reinterpret_cast<char*>(b16_lds));
 }
 
+// One layer on its own (pmpd_gemm with 9 to 16 rows of X): workgroup k takes row tiles 4 k .. 4 k + 3.
+template <int B>
+__global__ __launch_bounds__(kB16Waves * 64, 3) void pmpd_block16_layer_kernel(LayerDesc L, const _Float16* __restrict__ X, int m,
+                                                                               float* __restrict__ Y) {
+  extern __shared__ uint4 b16_lds[];
+  b16_tiles<B>(L, kB16Waves * static_cast<int>(blockIdx.x), X, m, Y, reinterpret_cast<char*>(b16_lds));
+}
+
+hipError_t launch_block16_layer(const LayerDesc& d, int b, const void* X, int m, float* Y, hipStream_t s) {
+  if (m < 1 || m > 16) return hipErrorInvalidValue;
+  const unsigned grid = static_cast<unsigned>((d.n_tiles + kB16Waves - 1) / kB16Waves);
+  const size_t lds = static_cast<size_t>(std::min(kB16Chunk, d.n_groups)) * m * 256;
+  const _Float16* x = static_cast<const _Float16*>(X);
+  if (b == 4) hipLaunchKernelGGL((pmpd_block16_layer_kernel<4>), dim3(grid), dim3(kB16Waves * 64), lds, s, d, x, m, Y);
+  else if (b == 3) hipLaunchKernelGGL((pmpd_block16_layer_kernel<3>), dim3(grid), dim3(kB16Waves * 64), lds, s, d, x, m, Y);
+  else hipLaunchKernelGGL((pmpd_block16_layer_kernel<2>), dim3(grid), dim3(kB16Waves * 64), lds, s, d, x, m, Y);
+  return hipGetLastError();
+}
+
 // Called by the C entry points (pmpd_gemv.hip) for batches of one 16-token block over a stack.
 hipError_t launch_block16_stack(const pmpd_stack* st, int b, const void* X, int m, float* Y, hipStream_t s) {
   if (m < 1 || m > 16) return hipErrorInvalidValue;

@@ -804,6 +804,7 @@ hipError_t launch_skinny_stack(const pmpd_stack* st, int b, const void* X, int m
 constexpr int kSkinnyMinBatch = 3, kSkinnyMaxBatch = PMPD_MAX_STACK_BATCH;  // batches the int8 kernel takes over a stack
 // defined in pmpd_block16.hip
 hipError_t launch_block16_stack(const pmpd_stack* st, int b, const void* X, int m, float* Y, hipStream_t s);
+hipError_t launch_block16_layer(const LayerDesc& d, int b, const void* X, int m, float* Y, hipStream_t s);
 // Which of the two takes a batch over a stack (measured on the 7B-shaped and the mobile-scale stack): the fp16 kernel
 // costs the same whatever the batch, the int8 kernel grows with every four vectors; they meet at 5 to 8 vectors,
 // where the fp16 kernel wins at b = 4 (the int8 kernel waits for memory there) and loses at b = 3 and 2.
@@ -822,7 +823,9 @@ static int32_t linear_entry(const char* who, const pmpd_layer_t* layer, int32_t 
   const LayerDesc d = make_desc(*layer, 0, 0);
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
-  if (m > PMPD_MAX_BATCH) {  // compute-bound shape: fp16 MFMA tile kernel
+  if (m > PMPD_MAX_BATCH && m <= kSkinnyMaxBatch) {  // one 16-token block: codes as fp16 subnormals, weights read once
+    e = launch_block16_layer(d, b, x, m, y, s);
+  } else if (m > PMPD_MAX_BATCH) {  // compute-bound shape: fp16 MFMA tile kernel
     // the kernel addresses X with 32-bit byte offsets from the layer's first activation
     if (static_cast<uint64_t>(m) * static_cast<uint64_t>(d.in_f) * 2u >= (uint64_t{1} << 32))
       return fail(PMPD_EINVAL, "%s: m x in_features = %d x %d: X of one layer must stay below 4 GiB", who, m, d.in_f);

@@ -170,12 +170,33 @@ def test_gemm_skinny_matches_oracle(pmpd, b, m):
 
 
 @pytest.mark.parametrize("b", [4, 3, 2])
+@pytest.mark.parametrize("m", [9, 13, 16])
+def test_gemm_one_token_block_matches_oracle(pmpd, b, m):
+    """9 to 16 rows of X on a single layer: the fp16 kernel with the codes as subnormals.  Ragged row counts (one
+    row tile, four and a bit), one group, an odd number of groups above one chunk of eight, and a row long enough
+    for several chunks."""
+    import torch
+
+    _say(f"[gemm, one token block] m={m} b={b}")
+    for (out_f, in_f) in ((200, 512), (70, 2432), (64, 128), (330, 5632)):
+        q4, s, a = synth.draw_weights(14, out_f, m, out_f, in_f, random_min=True)
+        X = synth.draw_x(14, 0, out_f, m, in_f, m=m)
+        layer = _device_layer(pmpd, q4, s, a)
+        Y = torch.full((m, out_f), float("nan"), dtype=torch.float32, device="cuda")
+        pmpd.gemm(layer, b, torch.from_numpy(X).cuda(), Y)
+        torch.cuda.synchronize()
+        y_ref, t = oracle.linear(q4, s, a, b, X)
+        assert_parity(Y.cpu().numpy(), y_ref, t, f"gemm {out_f}x{in_f} m={m} b={b}")
+
+
+@pytest.mark.parametrize("b", [4, 3, 2])
 # the prefill tile is 256 tokens x 4 row tiles of 64, groups taken two at a time: token counts around one and two
 # tiles, ragged row counts (multiples of 4 and not), 1, 2, 3, 5 and 11 groups
 @pytest.mark.parametrize("m,out_f,in_f", [(16, 200, 512), (100, 130, 2048), (512, 256, 1408), (129, 320, 5120),
                                           (257, 64, 128), (300, 192, 256), (256, 70, 384), (255, 64, 640), (513, 260, 256)])
 def test_gemm_prefill_matches_oracle(pmpd, b, m, out_f, in_f):
-    """m > 8 takes the MFMA path: ragged M and N tiles, several K steps, all bit-widths."""
+    """m > 16 takes the prefill kernel (m = 16 the fp16 kernel of one token block): ragged M and N tiles, several
+    K steps, all bit-widths."""
     import torch
 
     _say(f"[prefill gemm] m={m} out={out_f} in={in_f} b={b}")

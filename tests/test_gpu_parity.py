@@ -346,6 +346,34 @@ def test_batch_step_long_rows_and_adversarial_vectors(pmpd, b, m):
     stack.close()
 
 
+@pytest.mark.parametrize("seed", list(range(8)))
+def test_batch_step_random_shapes(pmpd, seed):
+    """Stacks of layers with random row counts (1 to 400: below one tile, ragged, several workgroups) and 1 to 40
+    groups (below, at and above one K-chunk of either batch kernel, odd and even), at a random batch of 3 to 16 and
+    every bit-width."""
+    import torch
+
+    rng = np.random.default_rng(1000 + seed)
+    m = int(rng.integers(3, 17))
+    dims = [(int(rng.integers(1, 401)), 128 * int(rng.integers(1, 41))) for _ in range(5)]
+    _say(f"[batch_step random] seed={seed} m={m} dims={dims}")
+    raw = [synth.draw_weights(40 + seed, k, 0, o, i, random_min=(k % 2 == 0)) for k, (o, i) in enumerate(dims)]
+    layers = [_device_layer(pmpd, *w) for w in raw]
+    stack = pmpd.Stack(layers)
+    Xs = [synth.draw_x(40 + seed, 0, k, 0, i, m=m) for k, (o, i) in enumerate(dims)]
+    X = torch.from_numpy(np.concatenate([x.reshape(-1) for x in Xs])).cuda()
+    for b in (4, 3, 2):
+        Y = torch.full((m * stack.y_elems,), float("nan"), dtype=torch.float32, device="cuda")
+        pmpd.batch_step(stack, b, X, m, Y)
+        torch.cuda.synchronize()
+        Yh = Y.cpu().numpy()
+        for li, (q4, s_, a) in enumerate(raw):
+            o = m * stack.y_offsets[li]
+            y_ref, t = oracle.linear(q4, s_, a, b, Xs[li])
+            assert_parity(Yh[o:o + m * q4.shape[0]].reshape(m, q4.shape[0]), y_ref, t, f"batch_step random seed={seed} layer {li} {dims[li]} m={m} b={b}")
+    stack.close()
+
+
 def _small_stack(pmpd, seed=5):
     """A two-block stack with Llama-like proportions (hidden 256, intermediate 640, ragged)."""
     shape = synth.StackShape("tiny", 2, 256, 640)
